@@ -1,0 +1,245 @@
+"""Pins of the oracle's decoder and beam search: invariants, closed forms and
+brute force on tiny inputs.  Nothing here touches the HIP path."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import MODE_CACHED, MODE_PLAIN, MODE_PLAIN_PRECUT
+from helpers import all_paths, tiny
+from paper_2602_22732_amd import synth
+
+
+def make(**kw):
+    w, W, X = tiny(**kw)
+    return w, W, X, oracle.Oracle(weights=W, **w.model_kwargs())
+
+
+def path_scores(o, x, V, length=None):
+    """Brute force: log-probability of every SID path by the teacher-forced forward."""
+    rq = o.request(x, length)
+    paths = all_paths(V)
+    scores = np.zeros(len(paths))
+    for i, p in enumerate(paths):
+        dists = rq.forward_seq(p[:-1])
+        scores[i] = sum(dists[t][p[t]] for t in range(len(V)))
+    return paths, scores
+
+
+def test_all_paths_sum_to_one():
+    w, W, X, o = make(V=[3, 4, 5], T=3)
+    _, s = path_scores(o, X[0], w.V)
+    assert abs(np.exp(s).sum() - 1.0) < 1e-12
+
+
+@pytest.mark.parametrize("mode", [MODE_CACHED, MODE_PLAIN, MODE_PLAIN_PRECUT])
+def test_exhaustive_beam_equals_brute_force(mode):
+    V = [3, 4, 5]
+    w, W, X, o = make(V=V, T=3, beam=[3, 12, 60], B=2)
+    sid, lp, _ = o.decode_batch(X, None, w.beam, mode)
+    for r in range(w.B):
+        paths, s = path_scores(o, X[r], V)
+        order = np.argsort(-s, kind="stable")
+        assert np.array_equal(sid[r], paths[order])
+        np.testing.assert_allclose(lp[r], s[order], atol=1e-12)
+
+
+@pytest.mark.parametrize("mode", [MODE_CACHED, MODE_PLAIN])
+def test_beam_one_is_greedy(mode):
+    w, W, X, o = make(V=[7, 9, 8, 6], T=4, beam=[1, 1, 1, 1], L=4, K=2)
+    sid, lp, _ = o.decode_batch(X, None, w.beam, mode)
+    for r in range(w.B):
+        rq = o.request(X[r])
+        toks, total = [], 0.0
+        for t in range(w.T):
+            dist = rq.forward_seq(toks)[-1]
+            v = int(np.argmax(dist))
+            total += dist[v]
+            toks.append(v)
+        assert sid[r, 0].tolist() == toks
+        assert abs(lp[r, 0] - total) < 1e-12
+
+
+def test_cached_equals_definition_and_precut():
+    # trunk shared by beams and levels, self-attention K/V kept per path and the two-stage
+    # selection are lossless: all three searches return the same beams
+    w, W, X, o = make(V=[12, 10, 9], T=3, beam=[4, 7, 5], L=4, K=2, B=3, S=9, len_min=3)
+    lens = synth.make_lengths(w, seed=5)
+    a = o.decode_batch(X, lens, w.beam, MODE_CACHED)
+    b = o.decode_batch(X, lens, w.beam, MODE_PLAIN)
+    c = o.decode_batch(X, lens, w.beam, MODE_PLAIN_PRECUT)
+    for other in (b, c):
+        assert np.array_equal(a[0], other[0])
+        np.testing.assert_allclose(a[1], other[1], atol=1e-12)
+        for key in ("parent", "tok"):
+            for t in range(w.T):
+                assert np.array_equal(a[2][key][t], other[2][key][t])
+
+
+def test_scores_sorted_paths_distinct_tokens_in_range():
+    w, W, X, o = make(V=[16, 12, 20], T=3, beam=[5, 9, 14], B=3)
+    sid, lp, tr = o.decode_batch(X, None, w.beam)
+    assert sid.shape == (3, 14, 3) and lp.shape == (3, 14)
+    assert (np.diff(lp, axis=1) <= 0).all()
+    for r in range(w.B):
+        assert len({tuple(p) for p in sid[r]}) == 14
+    for t in range(w.T):
+        assert sid[..., t].min() >= 0 and sid[..., t].max() < w.V[t]
+        assert tr["parent"][t].max() < ([1] + w.beam)[t]
+    # the trace reproduces the returned SIDs: follow the parents backwards
+    for r in range(w.B):
+        for j in range(14):
+            path, i = [], j
+            for t in reversed(range(w.T)):
+                path.append(tr["tok"][t][r, i])
+                i = tr["parent"][t][r, i]
+            assert path[::-1] == sid[r, j].tolist()
+
+
+def test_lazy_depth_zero_is_plain_autoregression():
+    w, W, X, o = make(V=[5, 6, 4], T=3, L=3, K=0)
+    rq = o.request(X[1])
+    for toks in ([], [2], [4, 5]):
+        np.testing.assert_allclose(rq.forward_seq(toks)[-1], rq.plain_ar_seq(toks), atol=1e-13)
+    # and with lazy layers the two differ (the trunk really ignores the tokens)
+    w2, W2, X2, o2 = make(V=[5, 6, 4], T=3, L=3, K=1)
+    rq2 = o2.request(X2[1])
+    assert np.abs(rq2.forward_seq([4, 5])[-1] - rq2.plain_ar_seq([4, 5])).max() > 1e-3
+
+
+def test_first_level_ignores_later_tokens_and_level_t_ignores_nothing_before():
+    w, W, X, o = make(V=[5, 6, 4], T=3, L=3, K=1)
+    rq = o.request(X[0])
+    a, b = rq.forward_seq([1, 2]), rq.forward_seq([3, 2])
+    np.testing.assert_array_equal(a[0], b[0])          # level 1 comes from BOS only
+    assert np.abs(a[1] - b[1]).max() > 1e-4            # level 2 depends on s_1
+    c = rq.forward_seq([1, 5])
+    np.testing.assert_array_equal(a[1], c[1])          # causal: level 2 blind to s_2
+    assert np.abs(a[2] - c[2]).max() > 1e-4
+
+
+def test_request_alone_equals_request_in_batch_and_batch_order_permutes():
+    w, W, X, o = make(V=[9, 9, 9], T=3, beam=[3, 5, 4], B=4, S=6, len_min=2)
+    lens = synth.make_lengths(w, seed=3)
+    sid, lp, _ = o.decode_batch(X, lens, w.beam)
+    for r in range(w.B):
+        s1, l1, _ = o.decode_batch(X[r:r + 1], lens[r:r + 1], w.beam)
+        assert np.array_equal(s1[0], sid[r]) and np.array_equal(l1[0], lp[r])
+    perm = np.array([2, 0, 3, 1])
+    s2, l2, _ = o.decode_batch(X[perm], lens[perm], w.beam)
+    assert np.array_equal(s2, sid[perm]) and np.array_equal(l2, lp[perm])
+
+
+def test_context_permutation_and_padding_invariance():
+    w, W, X, o = make(V=[9, 9, 9], T=3, beam=[3, 5, 4], B=1, S=8)
+    length = 5
+    sid, lp, _ = o.decode_batch(X, [length], w.beam)
+    Xp = X.copy()
+    Xp[0, :length] = X[0, np.random.default_rng(0).permutation(length)]   # no positions on X
+    Xp[0, length:] = 1e6                                                    # padding is never read
+    s2, l2, _ = o.decode_batch(Xp, [length], w.beam)
+    assert np.array_equal(sid, s2)
+    np.testing.assert_allclose(lp, l2, atol=1e-12)
+    # but a different length changes the answer (the mask is live)
+    s3, l3, _ = o.decode_batch(X, [length + 1], w.beam)
+    assert np.abs(l3 - lp).max() > 1e-6
+
+
+def test_zero_classifier_gives_uniform_levels_and_lowest_indices():
+    w, W, X = tiny(V=[4, 5, 3], T=3, beam=[3, 7, 6])
+    W["cls"] = [np.zeros_like(c) for c in W["cls"]]
+    o = oracle.Oracle(weights=W, **w.model_kwargs())
+    sid, lp, tr = o.decode_batch(X, None, w.beam)
+    np.testing.assert_allclose(lp, -np.log(4 * 5 * 3), atol=1e-12)
+    n = 1
+    for t in range(w.T):
+        flat = tr["parent"][t].astype(np.int64) * w.V[t] + tr["tok"][t]
+        assert np.array_equal(flat, np.tile(np.arange(w.beam[t]), (w.B, 1)))
+        n = w.beam[t]
+
+
+def test_classifier_bias_shifts_logits():
+    # with zero classifier weights the distribution is softmax(bias)
+    w, W, X = tiny(V=[4, 5, 3], T=3, beam=[2, 2, 2])
+    W["cls"] = [np.zeros_like(c) for c in W["cls"]]
+    bias = [np.random.default_rng(t).standard_normal(v).astype(np.float32) for t, v in enumerate(w.V)]
+    W["cls_bias"] = bias
+    o = oracle.Oracle(weights=W, **w.model_kwargs())
+    dists = o.request(X[0]).forward_seq([1, 2])
+    for t in range(3):
+        b = bias[t].astype(np.float64)
+        np.testing.assert_allclose(dists[t], b - np.log(np.exp(b).sum()), atol=1e-12)
+
+
+def test_dead_fuse_makes_every_beam_share_one_distribution():
+    # W_g = 0 and the token half of W_f = 0: the head input is 0 for every beam
+    w, W, X = tiny(V=[6, 6, 6], T=3)
+    W["w_g"] = np.zeros_like(W["w_g"])
+    W["w_f"] = W["w_f"].copy()
+    W["w_f"][:, w.d:] = 0
+    o = oracle.Oracle(weights=W, **w.model_kwargs())
+    _, lp = o.request(X[0]).prefix_dists(3, [[0, 1], [5, 2], [3, 3]])
+    np.testing.assert_allclose(lp[0], lp[1], atol=1e-13)
+    np.testing.assert_allclose(lp[0], lp[2], atol=1e-13)
+
+
+def test_prefix_dists_agree_with_trace():
+    w, W, X, o = make(V=[8, 7, 9], T=3, beam=[3, 4, 5], B=2)
+    sid, lp, tr = o.decode_batch(X, None, w.beam)
+    for r in range(w.B):
+        cum, dist = o.request(X[r]).prefix_dists(3, sid[r, :, :2])
+        np.testing.assert_allclose(cum + dist[np.arange(5), sid[r, :, 2]], lp[r], atol=1e-12)
+
+
+def test_invalid_beam_schedule_is_rejected():
+    w, W, X, o = make(V=[4, 4, 4], T=3)
+    for bad in ([5, 2, 2], [2, 9, 2], [0, 1, 1]):
+        with pytest.raises(ValueError):
+            o.decode_batch(X, None, bad)
+    o.decode_batch(X, None, [4, 16, 64])  # exactly all candidates is allowed
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_float_build_agrees_with_double_build(cfg):
+    w = synth.workload(cfg, batch=4)
+    W, X = synth.make_weights(w), synth.make_context(w)
+    o64 = oracle.Oracle(weights=W, **w.model_kwargs())
+    o32 = oracle.Oracle(weights=W, precision="f32", **w.model_kwargs())
+    for r in range(2):
+        toks = [3, 5][: w.T - 1]
+        a, b = o64.request(X[r]).forward_seq(toks), o32.request(X[r]).forward_seq(toks)
+        for t in range(w.T):
+            assert np.abs(a[t] - b[t]).max() < 1e-5
+
+
+def test_forward_seq_matches_library_composition():
+    """Trunk -> Fuse -> head -> classifier wired from PyTorch library routines
+    (section 3.2: eq. trunk, eq. fuse, eq. head and the level classifier)."""
+    import torch
+    import torch.nn.functional as F
+    from test_oracle_primitives import _torch_layer
+    w, W, X, o = make(V=[5, 6, 4, 7], T=4, L=4, K=2, d=24, H=3, F=40, S=6, B=1)
+    length, toks = 4, [3, 1, 2]
+    ctx = X[0][:length]
+    m = W["pos"].astype(np.float64).copy()
+    for l in range(w.K):
+        m = _torch_layer(W["layers"][l], m, ctx, w.H, w.eps, w.d)
+    s = np.stack([W["bos"]] + [W["emb"][t][toks[t]] for t in range(3)]).astype(np.float64)
+    h = np.concatenate([m * (s @ W["w_g"].T.astype(np.float64)), s], axis=1) @ W["w_f"].T.astype(np.float64)
+    for l in range(w.K, w.L):
+        h = _torch_layer(W["layers"][l], h, ctx, w.H, w.eps, w.d)
+    got = o.request(X[0], length).forward_seq(toks)
+    for t in range(w.T):
+        z = F.linear(F.rms_norm(torch.tensor(h[t]), (w.d,), torch.tensor(W["ln_out"].astype(np.float64)), eps=w.eps),
+                     torch.tensor(W["cls"][t].astype(np.float64)))
+        np.testing.assert_allclose(got[t], F.log_softmax(z, dim=0).numpy(), atol=1e-12)
+
+
+def test_config1_matches_stored_oracle_output():
+    import json, os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "cfg1_oracle.json")) as f:
+        g = json.load(f)
+    w = synth.workload(1)
+    W, X = synth.make_weights(w), synth.make_context(w)
+    sid, lp, _ = oracle.Oracle(weights=W, **w.model_kwargs()).decode_batch(X, None, w.beam)
+    assert np.array_equal(sid, np.array(g["sid"]))
+    np.testing.assert_allclose(lp, np.array(g["logprob"]), atol=1e-9)
