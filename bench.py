@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the LazyAR beam-decode hot path on one MI355X.
+
+A step is one gr4ad_decode_batch call over one batch of synthetic requests that
+are already resident in HBM: context K/V projection, lazy pass, and for every
+level Fuse, the autoregressive layers, classifier, log-softmax + top-k selection
+and beam reorder.  Prints ONE JSON line (requests/s, plus candidates/s,
+beam-rows/s, the roofline of the dominant kernel and the CPU oracle timed on
+the host cores).
+
+    python bench.py [--config 4] [--steps 5] [--warmup 2] [--scale 1.0] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA = 2.5e15   # dense bf16 MFMA, FLOP/s
+PEAK_F32_VALU = 157.3e12  # fp32 vector FLOP/s
+
+
+def algorithmic_flops(w, lens):
+    """Algorithmic flops of one batch (1 MAC = 2): what the method must compute."""
+    d, F, T, A, K, S = w.d, w.F, w.T, w.A, w.K, w.S
+    lens = np.asarray(lens, np.float64)
+    R = float(sum(w.rows))
+    per_req = {
+        "ctx_kv": A * 4.0 * lens.mean() * d * d,
+        "lazy": T * K * (12.0 * d * d + 4.0 * d * F + 4.0 * lens.mean() * d),
+        "fuse": R * 2.0 * d * d,
+        "ar_gemm": R * A * (12.0 * d * d + 4.0 * d * F),
+        "cross_attn": R * A * 4.0 * lens.mean() * d,
+        "self_attn": sum(n * A * 4.0 * (t + 1) * d for t, n in enumerate(w.rows)),
+        "classifier": sum(n * 2.0 * d * V for n, V in zip(w.rows, w.V)),
+    }
+    return {k: v * w.B for k, v in per_req.items()}
+
+
+def cpu_baseline(w, W, lens, budget_requests):
+    """Times the CPU oracle (double-precision build, as used for parity) on a bounded sample."""
+    import oracle
+    from paper_2602_22732_amd import synth
+    n = min(w.B, budget_requests)
+    X = synth.make_context(w, lens, requests=range(n))
+    o = oracle.Oracle(weights=W, **w.model_kwargs())
+    t0 = time.perf_counter()
+    o.decode_batch(X, lens[:n], w.beam)
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or len(os.sched_getaffinity(0))
+    return {"value": n / dt, "unit": "requests/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d of %d requests of the same workload, oracle decode (fp64 build, OpenMP), %.1f s" % (n, w.B, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5")
+    ap.add_argument("--scale", type=float, default=1.0, help="beam scale of configuration 5")
+    ap.add_argument("--batch", type=int, default=None, help="override the batch size")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (requests shard data-parallel with no communication; "
+              "run one process per GPU to scale out). --gpus %d is not supported." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_22732_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    w = synth.workload(args.config, scale=args.scale, batch=args.batch)
+    W = synth.make_weights(w)
+    lens = synth.make_lengths(w)
+    dev = torch.device("cuda:0")
+    td = binding.torch_dtype(w.dtype)
+    ctx = torch.empty(w.B, w.S, w.d, dtype=td, device=dev)
+    for r in range(w.B):  # request by request: bounded host memory
+        ctx[r] = torch.from_numpy(synth.make_context_request(w, r, int(lens[r]))).to(dev, dtype=td)
+    ctx_len = torch.from_numpy(lens).to(dev)
+    dec = binding.decoder_for(w, W)
+    ws_bytes = dec.workspace_bytes(w.B, w.S, w.beam)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    out_sid = torch.empty(w.B, w.beam[-1], w.T, dtype=torch.int32, device=dev)
+    out_lp = torch.empty(w.B, w.beam[-1], dtype=torch.float32, device=dev)
+
+    def step():
+        dec.decode_batch(ctx, ctx_len, w.beam, workspace=ws, out_sid=out_sid, out_logprob=out_lp)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.profile_read(reset=True)
+    binding.profile_enable(not args.no_profile)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = binding.profile_read(reset=True)
+    binding.profile_enable(False)
+
+    ms_per_step = elapsed / args.steps * 1e3
+    req_s = w.B * args.steps / elapsed
+    flops = algorithmic_flops(w, lens)
+    total_flops = sum(flops.values())
+
+    # dominant kernel: the one with the most event time
+    roofline = None
+    kernels = {}
+    for name, rec in prof.items():
+        kernels[name] = {"ms_per_step": rec["ms"] / args.steps, "launches_per_step": rec["launches"] / args.steps,
+                         "avg_launch_ms": rec["ms"] / rec["launches"]}
+    if prof:
+        dom = max(prof, key=lambda k: prof[k]["ms"])
+        rec = prof[dom]
+        if rec["flops"] > 0:
+            peak = PEAK_BF16_MFMA if "mfma" in dom else PEAK_F32_VALU
+            ach = rec["flops"] / (rec["ms"] * 1e-3)
+            roofline = {"kernel": dom, "bound": "mfma" if "mfma" in dom else "alu", "achieved": ach / 1e12, "peak": peak / 1e12,
+                        "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                        "avg_launch_ms": rec["ms"] / rec["launches"], "flops_per_launch": rec["flops"] / rec["launches"]}
+        else:
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": None, "peak": 8000.0, "unit": "GB/s", "frac": None, "traffic": None,
+                        "avg_launch_ms": rec["ms"] / rec["launches"]}
+
+    out = {
+        "metric": "requests_per_s", "value": req_s, "unit": "requests/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "config %d %s: B=%d S=%d d=%d L=%d K=%d H=%d F=%d T=%d V=%s beam=%s ctx_len=%s" % (
+            w.cfg_id, w.name, w.B, w.S, w.d, w.L, w.K, w.H, w.F, w.T, w.V[0], "/".join(map(str, w.beam)),
+            "all %d" % w.S if w.len_min is None else "U[%d,%d]" % (w.len_min, w.S)), "batch": w.B, "beam": list(w.beam)},
+        "candidates_per_s": req_s * w.beam[-1], "beam_rows_per_s": req_s * sum(w.rows),
+        "algorithmic_tflop_per_step": total_flops / 1e12, "whole_path_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
+        "whole_path_frac_of_bf16_mfma_peak": total_flops / (ms_per_step * 1e-3) / PEAK_BF16_MFMA,
+        "workspace_gib": ws_bytes / 2**30,
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu:
+        budget = {1: 4, 2: 32, 3: 4, 4: 1, 5: 1}[w.cfg_id]
+        out["cpu_baseline"] = cpu_baseline(w, W, lens, budget)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

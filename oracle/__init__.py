@@ -38,8 +38,8 @@ _libs = {}
 
 
 def build():
-    from . import build as _b
-    _b.build()
+    from . import build_oracle
+    build_oracle.build()
 
 
 def _lib(precision):

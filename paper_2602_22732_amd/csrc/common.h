@@ -1,0 +1,96 @@
+// Internal declarations shared by the HIP translation units of libgr4ad.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/gr4ad.h"
+
+typedef __bf16 bf16;
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float to_f(float x) { return x; }
+__device__ __forceinline__ float to_f(bf16 x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f(float x);
+template <> __device__ __forceinline__ float from_f<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16 from_f<bf16>(float x) { return (bf16)x; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- GEMM: C[M,N] = A[M,K] * W[N,K]^T with a fused epilogue -----------------
+enum { ACT_NONE = 0, ACT_SILU = 1 };
+struct GemmEpilogue {
+    void *C;             // output, row stride ldc elements
+    int64_t ldc;
+    int out_f32;         // 1: C is float, 0: C has the storage dtype
+    const float *resid;  // float32 [M, stride ldr] residual stream, added to the product (may alias C)
+    int64_t ldr;
+    const float *bias;   // [N] float, added per column
+    const float *table;  // float32 [*, N]: row tok[row] (or row 0 if tok == NULL) added per row
+    const int32_t *tok;  // [M] row selector of `table`
+    const void *rowmul;  // unused by the GEMM (reserved)
+    int act;             // ACT_*
+};
+// A row stride lda, W row stride ldw (elements).  dtype: storage type of A, W (and C unless out_f32).
+int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K,
+                const GemmEpilogue &epi, hipStream_t st);
+
+// ---- element-wise / norm kernels -------------------------------------------
+// y[r,:] = g * x[r,:] / sqrt(mean(x[r,:]^2) + eps); x is the float32 residual stream, g and y have the storage dtype
+int launch_rmsnorm(gr4ad_dtype dtype, const void *x, const void *g, void *y, int64_t rows, int d, float eps, hipStream_t st);
+// a[(b*n+i), :] = m[b*m_stride + :] * G[tok(b,i), :]   (tok == NULL: row 0 of G); m float32, G and a storage dtype
+int launch_fuse_gate(gr4ad_dtype dtype, const void *m, int64_t m_req_stride, const void *G, const int32_t *tok, void *a, int B, int n,
+                     int d, hipStream_t st);
+// dst[b*T + t, :] = pos[t, :]   (pos storage dtype, dst float32)
+int launch_broadcast_rows(gr4ad_dtype dtype, const void *pos, void *dst, int B, int T, int d, hipStream_t st);
+// dst[b, j, 0:row_elems] = src[b, parent[b,j], 0:row_elems]
+int launch_gather_rows(gr4ad_dtype dtype, const void *src, const int32_t *parent, void *dst, int B, int n, int k, int64_t row_elems,
+                       int64_t row_stride, hipStream_t st);
+
+// ---- attention ---------------------------------------------------------------
+// beam-shared cross-attention; q/out row stride ldq/ldo elements, rows (b*n+i)
+int launch_cross_attention(gr4ad_dtype dtype, const void *q, int64_t ldq, const void *kv, const int32_t *ctx_len, void *out, int64_t ldo,
+                           int B, int n, int S, int d, int H, hipStream_t st);
+// autoregressive self-attention of position `pos` for rows (b*n+i): qkv [rows,3d];
+// cache [B*n_stride... ] laid out [rows][T][2d] with per-request capacity cache_rows; writes k,v at `pos`
+int launch_self_attention_step(gr4ad_dtype dtype, const void *qkv, void *cache, void *out, int64_t rows, int pos, int T, int d, int H,
+                               hipStream_t st);
+// causal self-attention over the T trunk positions of each request: qkv [B*T,3d] -> out [B*T,d]
+int launch_trunk_self_attention(gr4ad_dtype dtype, const void *qkv, void *out, int B, int T, int d, int H, hipStream_t st);
+
+// ---- selection ---------------------------------------------------------------
+size_t select_workspace_bytes(int B, int n, int V, int k);
+// sid_old [B,n,T] / sid_new [B,k,T] may be NULL (no path bookkeeping); level = 0-based t
+int launch_select(const float *logits, const float *cum, int B, int n, int V, int k, void *ws, size_t ws_bytes, int32_t *parent,
+                  int32_t *tok, float *score, const int32_t *sid_old, int32_t *sid_new, int T, int level, hipStream_t st);
+
+// ---- optional per-kernel event timing ----------------------------------------
+enum KernelClass { KC_GEMM_256 = 0, KC_GEMM_128, KC_GEMM_SIMPLE, KC_XATTN_FLASH, KC_XATTN_SIMPLE, KC_SELF_STEP, KC_TRUNK_SELF,
+                   KC_RMSNORM, KC_FUSE_GATE, KC_SELECT_ROWS, KC_SELECT_REQUEST, KC_GATHER, KC_BROADCAST, KC_COUNT };
+// Declared around a kernel launch: records an event before and (on scope exit) after it when timing is on.
+struct ProfScope {
+    ProfScope(int cls, hipStream_t st, double flops = 0.0);
+    ~ProfScope();
+    int idx_;
+    hipStream_t st_;
+};
+
+#define GR4AD_LAUNCH_CHECK()                                   \
+    do {                                                       \
+        hipError_t e_ = hipGetLastError();                     \
+        if (e_ != hipSuccess) return GR4AD_EHIP;               \
+    } while (0)

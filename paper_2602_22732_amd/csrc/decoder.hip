@@ -1,0 +1,467 @@
+// Host side of libgr4ad.so: the C ABI, weight packing, workspace plan and the
+// per-level decode loop (section 3.2 LazyAR decoder under the beam search of
+// section 4.2).  All device work is enqueued on the caller's stream.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+namespace {
+
+struct LayerPacked {
+    void *ln_x, *wq_x, *wkv_x, *wo_x;   // wkv_x [2d,d]: rows of W_k then W_v (context projection)
+    void *ln_s, *wqkv_s, *wo_s;         // wqkv_s [3d,d]
+    void *ln_f, *w1, *w2;
+};
+
+thread_local char g_init_error[512] = "";
+
+}  // namespace
+
+struct gr4ad_decoder {
+    int d, H, F, L, K, T, A;
+    int V[GR4AD_MAX_LEVELS], max_beam[GR4AD_MAX_LEVELS];
+    int max_batch, max_ctx;
+    gr4ad_dtype dtype;
+    size_t esz;
+    float eps;
+    int device;
+    void *pos, *ln_out, *wf1;
+    void *G[GR4AD_MAX_LEVELS], *P[GR4AD_MAX_LEVELS];  // per-level Fuse tables: W_g s and W_f[:,d:] s of the previous token
+    void *cls[GR4AD_MAX_LEVELS];
+    float *cls_bias[GR4AD_MAX_LEVELS];
+    std::vector<LayerPacked> layers;
+    std::vector<void *> allocs;
+    int32_t *tr_parent[GR4AD_MAX_LEVELS], *tr_tok[GR4AD_MAX_LEVELS];
+    float *tr_score[GR4AD_MAX_LEVELS];
+    bool trace;
+    char err[512];
+};
+
+namespace {
+
+int fail(gr4ad_decoder *dec, int code, const char *fmt, ...) {
+    char *buf = dec ? dec->err : g_init_error;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, 512, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Everything decode_batch carves out of the caller's workspace.
+struct Plan {
+    size_t kv_ar, kv_lazy, trunk, h, xn, q, o, qkv, f, logits, selws, cache[2], cum[2], par, tok[2], sid[2], total;
+    int64_t rows_max, nmax, bmax;
+    size_t cache_layer_elems;
+};
+
+bool beams_ok(const gr4ad_decoder *dec, const int32_t *beam) {
+    int64_t n = 1;
+    for (int t = 0; t < dec->T; t++) {
+        if (beam[t] < 1 || beam[t] > dec->max_beam[t] || (int64_t)beam[t] > n * dec->V[t]) return false;
+        n = beam[t];
+    }
+    return true;
+}
+
+Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *beam) {
+    Plan p;
+    memset(&p, 0, sizeof(p));
+    const size_t e = dec->esz;
+    const int64_t d = dec->d, T = dec->T;
+    int64_t n = 1, nmax = 1, bmax = 1, logit_max = 0;
+    size_t selmax = 0;
+    for (int t = 0; t < T; t++) {
+        if (n > nmax) nmax = n;
+        if (beam[t] > bmax) bmax = beam[t];
+        if (n * dec->V[t] > logit_max) logit_max = n * dec->V[t];
+        size_t s = select_workspace_bytes((int)B, (int)n, dec->V[t], beam[t]);
+        if (s > selmax) selmax = s;
+        n = beam[t];
+    }
+    p.nmax = nmax;
+    p.bmax = bmax;
+    p.rows_max = B * (nmax > T ? nmax : T);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+    p.kv_ar = take((size_t)dec->A * B * S * 2 * d * e);
+    p.kv_lazy = take(dec->K > 0 ? (size_t)B * S * 2 * d * e : 0);
+    p.trunk = take((size_t)B * T * d * sizeof(float));  // residual streams stay float32 whatever the storage dtype
+    p.h = take((size_t)p.rows_max * d * sizeof(float));
+    p.xn = take((size_t)p.rows_max * d * e);
+    p.q = take((size_t)p.rows_max * d * e);
+    p.o = take((size_t)p.rows_max * d * e);
+    p.qkv = take((size_t)p.rows_max * 3 * d * e);
+    p.f = take((size_t)p.rows_max * dec->F * e);
+    p.logits = take((size_t)B * logit_max * sizeof(float));
+    p.selws = take(selmax);
+    p.cache_layer_elems = (size_t)B * nmax * T * 2 * d;
+    for (int i = 0; i < 2; i++) p.cache[i] = take((size_t)dec->A * p.cache_layer_elems * e);
+    for (int i = 0; i < 2; i++) p.cum[i] = take((size_t)B * bmax * sizeof(float));
+    p.par = take((size_t)B * bmax * sizeof(int32_t));
+    for (int i = 0; i < 2; i++) p.tok[i] = take((size_t)B * bmax * sizeof(int32_t));
+    for (int i = 0; i < 2; i++) p.sid[i] = take((size_t)B * bmax * T * sizeof(int32_t));
+    p.total = off;
+    return p;
+}
+
+#define HIP_TRY(dec, call)                                                                  \
+    do {                                                                                    \
+        hipError_t e_ = (call);                                                             \
+        if (e_ != hipSuccess) return fail(dec, GR4AD_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+#define OP_TRY(dec, call, what)                                                  \
+    do {                                                                         \
+        int s_ = (call);                                                         \
+        if (s_ != GR4AD_OK) return fail(dec, s_, "%s failed: %s", what, gr4ad_strerror(s_)); \
+    } while (0)
+
+int dev_alloc(gr4ad_decoder *dec, void **out, size_t bytes) {
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes ? bytes : 256);
+    if (e != hipSuccess) return fail(dec, e == hipErrorOutOfMemory ? GR4AD_ENOMEM : GR4AD_EHIP, "hipMalloc(%zu): %s", bytes, hipGetErrorString(e));
+    dec->allocs.push_back(p);
+    *out = p;
+    return GR4AD_OK;
+}
+
+int dev_clone(gr4ad_decoder *dec, void **out, const void *src, size_t bytes) {
+    int s = dev_alloc(dec, out, bytes);
+    if (s) return s;
+    HIP_TRY(dec, hipMemcpy(*out, src, bytes, hipMemcpyDeviceToDevice));
+    return GR4AD_OK;
+}
+
+// rows of several [r_i, d] matrices stacked into one [sum r_i, d] matrix
+int dev_stack(gr4ad_decoder *dec, void **out, const void *const *srcs, int count, size_t bytes_each) {
+    int s = dev_alloc(dec, out, bytes_each * count);
+    if (s) return s;
+    for (int i = 0; i < count; i++) HIP_TRY(dec, hipMemcpy((char *)*out + i * bytes_each, srcs[i], bytes_each, hipMemcpyDeviceToDevice));
+    return GR4AD_OK;
+}
+
+GemmEpilogue plain_epilogue(void *C, int64_t ldc);
+GemmEpilogue f32_epilogue(void *C, int64_t ldc) {
+    GemmEpilogue e = plain_epilogue(C, ldc);
+    e.out_f32 = 1;
+    return e;
+}
+
+GemmEpilogue plain_epilogue(void *C, int64_t ldc) {
+    GemmEpilogue e;
+    memset(&e, 0, sizeof(e));
+    e.C = C;
+    e.ldc = ldc;
+    return e;
+}
+
+int validate_desc(const gr4ad_model_desc *ds) {
+    if (!ds) return fail(nullptr, GR4AD_EINVAL, "desc is NULL");
+    if (!ds->codebook || !ds->max_beam) return fail(nullptr, GR4AD_EINVAL, "codebook/max_beam is NULL");
+    if (ds->d_model <= 0 || ds->n_heads <= 0 || ds->d_ffn <= 0 || ds->n_layers <= 0 || ds->max_batch <= 0 || ds->max_ctx <= 0)
+        return fail(nullptr, GR4AD_EINVAL, "sizes must be positive");
+    if (ds->d_model % ds->n_heads) return fail(nullptr, GR4AD_EINVAL, "d_model %d not divisible by n_heads %d", ds->d_model, ds->n_heads);
+    if (ds->n_lazy < 0 || ds->n_lazy >= ds->n_layers) return fail(nullptr, GR4AD_EINVAL, "n_lazy %d outside [0, n_layers=%d)", ds->n_lazy, ds->n_layers);
+    if (ds->n_levels < 1 || ds->n_levels > GR4AD_MAX_LEVELS) return fail(nullptr, GR4AD_EINVAL, "n_levels %d outside [1,%d]", ds->n_levels, GR4AD_MAX_LEVELS);
+    if (ds->dtype != GR4AD_F32 && ds->dtype != GR4AD_BF16) return fail(nullptr, GR4AD_EINVAL, "unknown dtype %d", (int)ds->dtype);
+    if (!(ds->rms_eps >= 0.0f)) return fail(nullptr, GR4AD_EINVAL, "rms_eps must be >= 0");
+    for (int t = 0; t < ds->n_levels; t++) {
+        if (ds->codebook[t] < 1 || ds->max_beam[t] < 1) return fail(nullptr, GR4AD_EINVAL, "codebook/max_beam of level %d must be >= 1", t + 1);
+        if (ds->codebook[t] > GR4AD_MAX_CODEBOOK) return fail(nullptr, GR4AD_EUNSUPPORTED, "codebook %d of level %d exceeds %d", ds->codebook[t], t + 1, GR4AD_MAX_CODEBOOK);
+        if (ds->max_beam[t] > GR4AD_MAX_BEAM) return fail(nullptr, GR4AD_EUNSUPPORTED, "max_beam %d of level %d exceeds %d", ds->max_beam[t], t + 1, GR4AD_MAX_BEAM);
+    }
+    const int dh = ds->d_model / ds->n_heads;
+    if (dh != 16 && dh != 32 && dh != 64 && dh != 128) return fail(nullptr, GR4AD_EUNSUPPORTED, "head width %d not in {16,32,64,128}", dh);
+    if (ds->d_model % 8 || ds->d_ffn % 8) return fail(nullptr, GR4AD_EUNSUPPORTED, "d_model and d_ffn must be multiples of 8");
+    return GR4AD_OK;
+}
+
+int validate_weights(const gr4ad_model_desc *ds, const gr4ad_weights *w) {
+    if (!w) return fail(nullptr, GR4AD_EINVAL, "weights is NULL");
+    if (!w->pos_dev || !w->bos_dev || !w->w_g_dev || !w->w_f_dev || !w->layers || !w->ln_out_dev || !w->cls_dev)
+        return fail(nullptr, GR4AD_EINVAL, "a weight pointer is NULL");
+    if (ds->n_levels > 1 && !w->emb_dev) return fail(nullptr, GR4AD_EINVAL, "emb_dev is NULL");
+    for (int t = 0; t + 1 < ds->n_levels; t++)
+        if (!w->emb_dev[t]) return fail(nullptr, GR4AD_EINVAL, "emb_dev[%d] is NULL", t);
+    for (int t = 0; t < ds->n_levels; t++)
+        if (!w->cls_dev[t]) return fail(nullptr, GR4AD_EINVAL, "cls_dev[%d] is NULL", t);
+    for (int l = 0; l < ds->n_layers; l++) {
+        const gr4ad_layer_weights *x = &w->layers[l];
+        const void *all[] = {x->ln_x, x->wq_x, x->wk_x, x->wv_x, x->wo_x, x->ln_s, x->wq_s, x->wk_s, x->wv_s, x->wo_s, x->ln_f, x->w1, x->w2};
+        for (const void *p : all)
+            if (!p) return fail(nullptr, GR4AD_EINVAL, "a weight pointer of layer %d is NULL", l);
+    }
+    return GR4AD_OK;
+}
+
+int init_impl(gr4ad_decoder *dec, const gr4ad_model_desc *ds, const gr4ad_weights *w) {
+    const size_t e = dec->esz, d = dec->d, F = dec->F;
+    HIP_TRY(dec, hipGetDevice(&dec->device));
+    int s;
+    if ((s = dev_clone(dec, &dec->pos, w->pos_dev, dec->T * d * e))) return s;
+    if ((s = dev_clone(dec, &dec->ln_out, w->ln_out_dev, d * e))) return s;
+    for (int t = 0; t < dec->T; t++) {
+        if ((s = dev_clone(dec, &dec->cls[t], w->cls_dev[t], (size_t)dec->V[t] * d * e))) return s;
+        dec->cls_bias[t] = nullptr;
+        if (w->cls_bias_dev && w->cls_bias_dev[t])
+            if ((s = dev_clone(dec, (void **)&dec->cls_bias[t], w->cls_bias_dev[t], (size_t)dec->V[t] * sizeof(float)))) return s;
+    }
+    dec->layers.resize(dec->L);
+    for (int l = 0; l < dec->L; l++) {
+        const gr4ad_layer_weights *x = &w->layers[l];
+        LayerPacked &p = dec->layers[l];
+        if ((s = dev_clone(dec, &p.ln_x, x->ln_x, d * e))) return s;
+        if ((s = dev_clone(dec, &p.wq_x, x->wq_x, d * d * e))) return s;
+        const void *kv[2] = {x->wk_x, x->wv_x};
+        if ((s = dev_stack(dec, &p.wkv_x, kv, 2, d * d * e))) return s;
+        if ((s = dev_clone(dec, &p.wo_x, x->wo_x, d * d * e))) return s;
+        if ((s = dev_clone(dec, &p.ln_s, x->ln_s, d * e))) return s;
+        const void *qkv[3] = {x->wq_s, x->wk_s, x->wv_s};
+        if ((s = dev_stack(dec, &p.wqkv_s, qkv, 3, d * d * e))) return s;
+        if ((s = dev_clone(dec, &p.wo_s, x->wo_s, d * d * e))) return s;
+        if ((s = dev_clone(dec, &p.ln_f, x->ln_f, d * e))) return s;
+        if ((s = dev_clone(dec, &p.w1, x->w1, F * d * e))) return s;
+        if ((s = dev_clone(dec, &p.w2, x->w2, d * F * e))) return s;
+    }
+    // Fuse (eq. fuse) is linear in the token embedding s: W_f [m*(W_g s); s] = W_f[:, :d] (m * (W_g s)) + W_f[:, d:] s.
+    // Split W_f and tabulate W_g s and W_f[:, d:] s for BOS and for every token of every level.
+    void *wf2 = nullptr, *wg = nullptr;
+    if ((s = dev_alloc(dec, &dec->wf1, d * d * e))) return s;
+    if ((s = dev_alloc(dec, &wf2, d * d * e))) return s;
+    if ((s = dev_clone(dec, &wg, w->w_g_dev, d * d * e))) return s;
+    HIP_TRY(dec, hipMemcpy2D(dec->wf1, d * e, w->w_f_dev, 2 * d * e, d * e, d, hipMemcpyDeviceToDevice));
+    HIP_TRY(dec, hipMemcpy2D(wf2, d * e, (const char *)w->w_f_dev + d * e, 2 * d * e, d * e, d, hipMemcpyDeviceToDevice));
+    for (int t = 0; t < dec->T; t++) {
+        const void *emb = t == 0 ? w->bos_dev : w->emb_dev[t - 1];
+        const int64_t rows = t == 0 ? 1 : dec->V[t - 1];
+        if ((s = dev_alloc(dec, &dec->G[t], rows * d * sizeof(float)))) return s;
+        if ((s = dev_alloc(dec, &dec->P[t], rows * d * sizeof(float)))) return s;
+        OP_TRY(dec, launch_gemm(dec->dtype, emb, d, wg, d, rows, (int)d, (int)d, f32_epilogue(dec->G[t], d), 0), "Fuse gate table");
+        OP_TRY(dec, launch_gemm(dec->dtype, emb, d, wf2, d, rows, (int)d, (int)d, f32_epilogue(dec->P[t], d), 0), "Fuse token table");
+    }
+    HIP_TRY(dec, hipDeviceSynchronize());
+    return GR4AD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *gr4ad_strerror(int status) {
+    switch (status) {
+        case GR4AD_OK: return "ok";
+        case GR4AD_EINVAL: return "invalid argument";
+        case GR4AD_EUNSUPPORTED: return "unsupported configuration";
+        case GR4AD_EWORKSPACE: return "workspace too small or misaligned";
+        case GR4AD_EHIP: return "HIP runtime error";
+        case GR4AD_ENOMEM: return "out of memory";
+        default: return "unknown status";
+    }
+}
+
+const char *gr4ad_last_error(const gr4ad_decoder *dec) { return dec ? dec->err : g_init_error; }
+
+int gr4ad_decode_init(const gr4ad_model_desc *ds, const gr4ad_weights *w, gr4ad_decoder **out) {
+    g_init_error[0] = 0;
+    if (!out) return fail(nullptr, GR4AD_EINVAL, "out is NULL");
+    int s = validate_desc(ds);
+    if (s) return s;
+    if ((s = validate_weights(ds, w))) return s;
+    gr4ad_decoder *dec = new (std::nothrow) gr4ad_decoder();
+    if (!dec) return fail(nullptr, GR4AD_ENOMEM, "host allocation failed");
+    dec->d = ds->d_model; dec->H = ds->n_heads; dec->F = ds->d_ffn; dec->L = ds->n_layers; dec->K = ds->n_lazy;
+    dec->T = ds->n_levels; dec->A = dec->L - dec->K; dec->max_batch = ds->max_batch; dec->max_ctx = ds->max_ctx;
+    dec->dtype = ds->dtype; dec->esz = ds->dtype == GR4AD_BF16 ? 2 : 4; dec->eps = ds->rms_eps;
+    dec->trace = false; dec->err[0] = 0;
+    for (int t = 0; t < dec->T; t++) { dec->V[t] = ds->codebook[t]; dec->max_beam[t] = ds->max_beam[t]; }
+    s = init_impl(dec, ds, w);
+    if (s) {
+        snprintf(g_init_error, sizeof(g_init_error), "%s", dec->err);
+        gr4ad_decode_free(dec);
+        return s;
+    }
+    *out = dec;
+    return GR4AD_OK;
+}
+
+void gr4ad_decode_free(gr4ad_decoder *dec) {
+    if (!dec) return;
+    for (void *p : dec->allocs) (void)hipFree(p);
+    delete dec;
+}
+
+size_t gr4ad_decode_workspace_bytes(const gr4ad_decoder *dec, int32_t B, int32_t S, const int32_t *beam) {
+    if (!dec || !beam || B < 1 || S < 1 || B > dec->max_batch || S > dec->max_ctx || !beams_ok(dec, beam)) return 0;
+    return make_plan(dec, B, S, beam).total;
+}
+
+int gr4ad_decode_set_trace(gr4ad_decoder *dec, int32_t *const *parent_dev, int32_t *const *tok_dev, float *const *score_dev) {
+    if (!dec) return GR4AD_EINVAL;
+    dec->trace = parent_dev || tok_dev || score_dev;
+    for (int t = 0; t < dec->T; t++) {
+        dec->tr_parent[t] = parent_dev ? parent_dev[t] : nullptr;
+        dec->tr_tok[t] = tok_dev ? tok_dev[t] : nullptr;
+        dec->tr_score[t] = score_dev ? score_dev[t] : nullptr;
+    }
+    return GR4AD_OK;
+}
+
+int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_len, int32_t B, int32_t S, const int32_t *beam,
+                       void *workspace, size_t workspace_bytes, int32_t *out_sid, float *out_logprob, void *hip_stream) {
+    if (!dec) return GR4AD_EINVAL;
+    dec->err[0] = 0;
+    if (!ctx || !beam || !out_sid || !out_logprob) return fail(dec, GR4AD_EINVAL, "a required pointer is NULL");
+    if (B < 1 || B > dec->max_batch) return fail(dec, GR4AD_EINVAL, "B=%d outside [1, max_batch=%d]", B, dec->max_batch);
+    if (S < 1 || S > dec->max_ctx) return fail(dec, GR4AD_EINVAL, "S=%d outside [1, max_ctx=%d]", S, dec->max_ctx);
+    if (!beams_ok(dec, beam)) return fail(dec, GR4AD_EINVAL, "beam schedule invalid: need 1 <= b_t <= max_beam[t] and b_t <= b_{t-1}*V_t");
+    const Plan p = make_plan(dec, B, S, beam);
+    if (!workspace || workspace_bytes < p.total) return fail(dec, GR4AD_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, p.total);
+    if ((uintptr_t)workspace % 256) return fail(dec, GR4AD_EWORKSPACE, "workspace must be 256-byte aligned");
+    if ((uintptr_t)ctx % 16) return fail(dec, GR4AD_EINVAL, "ctx_dev must be 16-byte aligned");
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    const gr4ad_dtype dt = dec->dtype;
+    const size_t e = dec->esz;
+    const int d = dec->d, F = dec->F, T = dec->T, H = dec->H, A = dec->A, K = dec->K;
+    char *ws = (char *)workspace;
+    void *h = ws + p.h, *xn = ws + p.xn, *q = ws + p.q, *o = ws + p.o, *qkv = ws + p.qkv, *f = ws + p.f, *trunk = ws + p.trunk;
+    float *logits = (float *)(ws + p.logits);
+    auto kv_ar = [&](int a) { return (void *)(ws + p.kv_ar + (size_t)a * B * S * 2 * d * e); };
+    auto cache = [&](int i, int a) { return (void *)(ws + p.cache[i] + (size_t)a * p.cache_layer_elems * e); };
+
+    auto gemm = [&](const void *Ain, int64_t M, const void *W, int N, int Kdim, const GemmEpilogue &epi) {
+        return launch_gemm(dt, Ain, Kdim, W, Kdim, M, N, Kdim, epi, st);
+    };
+    auto resid_epi = [&](void *x, int64_t ld) { GemmEpilogue g = plain_epilogue(x, ld); g.resid = (const float *)x; g.ldr = ld; g.out_f32 = 1; return g; };
+    auto silu_epi = [&](void *x, int64_t ld) { GemmEpilogue g = plain_epilogue(x, ld); g.act = ACT_SILU; return g; };
+
+    // cross-attention + its residual; x is the residual stream [rows,d]
+    auto cross_block = [&](const LayerPacked &lw, void *x, int64_t rows, int n, const void *kvbuf) -> int {
+        int s;
+        if ((s = launch_rmsnorm(dt, x, lw.ln_x, xn, rows, d, dec->eps, st))) return s;
+        if ((s = gemm(xn, rows, lw.wq_x, d, d, plain_epilogue(q, d)))) return s;
+        if ((s = launch_cross_attention(dt, q, d, kvbuf, ctx_len, o, d, B, n, S, d, H, st))) return s;
+        return gemm(o, rows, lw.wo_x, d, d, resid_epi(x, d));
+    };
+    auto ffn_block = [&](const LayerPacked &lw, void *x, int64_t rows) -> int {
+        int s;
+        if ((s = launch_rmsnorm(dt, x, lw.ln_f, xn, rows, d, dec->eps, st))) return s;
+        if ((s = gemm(xn, rows, lw.w1, F, d, silu_epi(f, F)))) return s;
+        return gemm(f, rows, lw.w2, d, F, resid_epi(x, d));
+    };
+
+    // ---- step 0: context keys/values of the autoregressive layers, once per request ----
+    for (int a = 0; a < A; a++)
+        OP_TRY(dec, gemm(ctx, (int64_t)B * S, dec->layers[K + a].wkv_x, 2 * d, d, plain_epilogue(kv_ar(a), 2 * d)), "context K/V projection");
+
+    // ---- step 1: lazy pass (eq. trunk): all T levels at once, no beam dimension ----
+    OP_TRY(dec, launch_broadcast_rows(dt, dec->pos, trunk, B, T, d, st), "trunk input");
+    for (int l = 0; l < K; l++) {
+        const LayerPacked &lw = dec->layers[l];
+        void *kvl = ws + p.kv_lazy;
+        const int64_t rows = (int64_t)B * T;
+        OP_TRY(dec, gemm(ctx, (int64_t)B * S, lw.wkv_x, 2 * d, d, plain_epilogue(kvl, 2 * d)), "lazy context K/V projection");
+        OP_TRY(dec, cross_block(lw, trunk, rows, T, kvl), "lazy cross-attention");
+        OP_TRY(dec, launch_rmsnorm(dt, trunk, lw.ln_s, xn, rows, d, dec->eps, st), "lazy norm");
+        OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, plain_epilogue(qkv, 3 * d)), "lazy qkv");
+        OP_TRY(dec, launch_trunk_self_attention(dt, qkv, o, B, T, d, H, st), "lazy self-attention");
+        OP_TRY(dec, gemm(o, rows, lw.wo_s, d, d, resid_epi(trunk, d)), "lazy self-attention output");
+        OP_TRY(dec, ffn_block(lw, trunk, rows), "lazy FFN");
+    }
+
+    // ---- level loop (eq. fuse, eq. head, classifier, selection, reorder) ----
+    int n = 1, cur = 0;
+    for (int t = 0; t < T; t++) {
+        const int64_t rows = (int64_t)B * n;
+        const int bt = beam[t];
+        const int32_t *tok_prev = t == 0 ? nullptr : (const int32_t *)(ws + p.tok[cur]);
+        OP_TRY(dec, launch_fuse_gate(dt, (const float *)trunk + (size_t)t * d, (int64_t)T * d, dec->G[t], tok_prev, xn, B, n, d, st), "Fuse gate");
+        {
+            GemmEpilogue g = plain_epilogue(h, d);
+            g.out_f32 = 1;
+            g.table = (const float *)dec->P[t];
+            g.tok = tok_prev;
+            OP_TRY(dec, gemm(xn, rows, dec->wf1, d, d, g), "Fuse projection");
+        }
+        for (int a = 0; a < A; a++) {
+            const LayerPacked &lw = dec->layers[K + a];
+            OP_TRY(dec, cross_block(lw, h, rows, n, kv_ar(a)), "cross-attention");
+            OP_TRY(dec, launch_rmsnorm(dt, h, lw.ln_s, xn, rows, d, dec->eps, st), "self-attention norm");
+            OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, plain_epilogue(qkv, 3 * d)), "self-attention qkv");
+            OP_TRY(dec, launch_self_attention_step(dt, qkv, cache(cur, a), o, rows, t, T, d, H, st), "self-attention");
+            OP_TRY(dec, gemm(o, rows, lw.wo_s, d, d, resid_epi(h, d)), "self-attention output");
+            OP_TRY(dec, ffn_block(lw, h, rows), "FFN");
+        }
+        OP_TRY(dec, launch_rmsnorm(dt, h, dec->ln_out, xn, rows, d, dec->eps, st), "final norm");
+        {
+            GemmEpilogue g = plain_epilogue(logits, dec->V[t]);
+            g.out_f32 = 1;
+            g.bias = dec->cls_bias[t];
+            OP_TRY(dec, gemm(xn, rows, dec->cls[t], dec->V[t], d, g), "classifier");
+        }
+        const bool last = t == T - 1;
+        int32_t *par = (int32_t *)(ws + p.par), *tok_new = (int32_t *)(ws + p.tok[cur ^ 1]);
+        float *score_new = last ? out_logprob : (float *)(ws + p.cum[cur ^ 1]);
+        int32_t *sid_new = last ? out_sid : (int32_t *)(ws + p.sid[cur ^ 1]);
+        OP_TRY(dec, launch_select(logits, t == 0 ? nullptr : (const float *)(ws + p.cum[cur]), B, n, dec->V[t], bt, ws + p.selws,
+                                  select_workspace_bytes(B, n, dec->V[t], bt), par, tok_new, score_new, (const int32_t *)(ws + p.sid[cur]),
+                                  sid_new, T, t, st),
+               "selection");
+        if (dec->trace) {
+            const size_t nb = (size_t)B * bt * 4;
+            if (dec->tr_parent[t]) HIP_TRY(dec, hipMemcpyAsync(dec->tr_parent[t], par, nb, hipMemcpyDeviceToDevice, st));
+            if (dec->tr_tok[t]) HIP_TRY(dec, hipMemcpyAsync(dec->tr_tok[t], tok_new, nb, hipMemcpyDeviceToDevice, st));
+            if (dec->tr_score[t]) HIP_TRY(dec, hipMemcpyAsync(dec->tr_score[t], score_new, nb, hipMemcpyDeviceToDevice, st));
+        }
+        if (!last)
+            for (int a = 0; a < A; a++)
+                OP_TRY(dec, launch_gather_rows(dt, cache(cur, a), par, cache(cur ^ 1, a), B, n, bt, (int64_t)(t + 1) * 2 * d, (int64_t)T * 2 * d, st),
+                       "beam reorder");
+        cur ^= 1;
+        n = bt;
+    }
+    return GR4AD_OK;
+}
+
+// ---- single-operation entry points ------------------------------------------
+int gr4ad_op_linear(gr4ad_dtype dtype, const void *A, const void *W, const float *bias, void *C, int32_t M, int32_t N, int32_t K,
+                    int32_t out_f32, void *hip_stream) {
+    if (!A || !W || !C || M < 1 || N < 1 || K < 1 || (dtype != GR4AD_F32 && dtype != GR4AD_BF16)) return GR4AD_EINVAL;
+    GemmEpilogue e = plain_epilogue(C, N);
+    e.bias = bias;
+    e.out_f32 = out_f32 ? 1 : 0;
+    return launch_gemm(dtype, A, K, W, K, M, N, K, e, (hipStream_t)hip_stream);
+}
+
+size_t gr4ad_op_select_workspace_bytes(int32_t B, int32_t n, int32_t V, int32_t k) {
+    if (B < 1 || n < 1 || V < 1 || k < 1) return 0;
+    return select_workspace_bytes(B, n, V, k);
+}
+
+int gr4ad_op_select(const float *logits, const float *cum, int32_t B, int32_t n, int32_t V, int32_t k, void *ws, size_t ws_bytes,
+                    int32_t *parent, int32_t *tok, float *score, void *hip_stream) {
+    if (!logits || !ws || !parent || !tok || !score) return GR4AD_EINVAL;
+    return launch_select(logits, cum, B, n, V, k, ws, ws_bytes, parent, tok, score, nullptr, nullptr, 0, 0, (hipStream_t)hip_stream);
+}
+
+int gr4ad_op_cross_attention(gr4ad_dtype dtype, const void *q, const void *kv, const int32_t *ctx_len, void *out, int32_t B, int32_t n,
+                             int32_t S, int32_t d, int32_t H, void *hip_stream) {
+    if (!q || !kv || !out || (dtype != GR4AD_F32 && dtype != GR4AD_BF16)) return GR4AD_EINVAL;
+    return launch_cross_attention(dtype, q, d, kv, ctx_len, out, d, B, n, S, d, H, (hipStream_t)hip_stream);
+}
+
+int gr4ad_op_gather_rows(gr4ad_dtype dtype, const void *src, const int32_t *parent, void *dst, int32_t B, int32_t n, int32_t k,
+                         int64_t row_elems, int64_t row_stride, void *hip_stream) {
+    if (!src || !parent || !dst || B < 1 || n < 1 || k < 1 || row_elems < 1 || row_stride < row_elems) return GR4AD_EINVAL;
+    return launch_gather_rows(dtype, src, parent, dst, B, n, k, row_elems, row_stride, (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

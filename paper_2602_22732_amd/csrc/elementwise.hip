@@ -1,0 +1,181 @@
+// Row-wise HBM-bound kernels: RMSNorm, the gate half of Fuse, trunk input
+// broadcast, and the beam reorder (row gather).  All move 16-byte vectors with
+// consecutive lanes on consecutive addresses.
+#include "common.h"
+
+template <typename T> struct Vec16;  // 16 bytes of T
+template <> struct Vec16<float> { static constexpr int N = 4; };
+template <> struct Vec16<bf16> { static constexpr int N = 8; };
+
+template <typename T> __device__ __forceinline__ void load16(const T *p, float *out) {
+    uint4 raw = *(const uint4 *)p;
+    const T *e = (const T *)&raw;
+#pragma unroll
+    for (int i = 0; i < Vec16<T>::N; i++) out[i] = to_f(e[i]);
+}
+template <typename T> __device__ __forceinline__ void store16(T *p, const float *in) {
+    uint4 raw;
+    T *e = (T *)&raw;
+#pragma unroll
+    for (int i = 0; i < Vec16<T>::N; i++) e[i] = from_f<T>(in[i]);
+    *(uint4 *)p = raw;
+}
+
+// ---------------------------------------------------------------------------
+// RMSNorm (pre-norm of every sub-layer and the final norm, section 3.2):
+// one wavefront per row, the row is read once and kept in registers.
+// ---------------------------------------------------------------------------
+template <typename T, int MAXV>  // MAXV: 16-byte vectors per lane
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ x, const T *__restrict__ g, T *__restrict__ y,
+                                                      int64_t rows, int d, float eps) {
+    constexpr int N = Vec16<T>::N;
+    const int lane = threadIdx.x % 64;
+    const int64_t row = (int64_t)blockIdx.x * 4 + threadIdx.x / 64;
+    if (row >= rows) return;
+    const int nvec = d / N;
+    float v[MAXV][N];
+    float ss = 0.0f;
+#pragma unroll
+    for (int i = 0; i < MAXV; i++) {
+        int c = lane + i * 64;
+        if (c < nvec) {
+#pragma unroll
+            for (int e = 0; e < N; e += 4) load16<float>(x + row * d + (int64_t)c * N + e, &v[i][e]);
+#pragma unroll
+            for (int e = 0; e < N; e++) ss += v[i][e] * v[i][e];
+        }
+    }
+    ss = wave_sum(ss);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int i = 0; i < MAXV; i++) {
+        int c = lane + i * 64;
+        if (c < nvec) {
+            float gg[N];
+            load16<T>(g + (int64_t)c * N, gg);
+#pragma unroll
+            for (int e = 0; e < N; e++) v[i][e] = gg[e] * v[i][e] * inv;
+            store16<T>(y + row * d + (int64_t)c * N, v[i]);
+        }
+    }
+}
+
+int launch_rmsnorm(gr4ad_dtype dtype, const void *x, const void *g, void *y, int64_t rows, int d, float eps, hipStream_t st) {
+    if (rows <= 0) return GR4AD_OK;
+    int64_t grid = ceil_div64(rows, 4);
+    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    ProfScope ps(KC_RMSNORM, st);
+    if (dtype == GR4AD_BF16) {
+        int nvec = d / 8;
+        if (d % 8) return GR4AD_EUNSUPPORTED;
+        if (nvec <= 128)
+            hipLaunchKernelGGL((rmsnorm_kernel<bf16, 2>), dim3((unsigned)grid), dim3(256), 0, st, (const float *)x, (const bf16 *)g, (bf16 *)y, rows, d, eps);
+        else if (nvec <= 512)
+            hipLaunchKernelGGL((rmsnorm_kernel<bf16, 8>), dim3((unsigned)grid), dim3(256), 0, st, (const float *)x, (const bf16 *)g, (bf16 *)y, rows, d, eps);
+        else
+            return GR4AD_EUNSUPPORTED;
+    } else {
+        int nvec = d / 4;
+        if (d % 4) return GR4AD_EUNSUPPORTED;
+        if (nvec <= 128)
+            hipLaunchKernelGGL((rmsnorm_kernel<float, 2>), dim3((unsigned)grid), dim3(256), 0, st, (const float *)x, (const float *)g, (float *)y, rows, d, eps);
+        else if (nvec <= 1024)
+            hipLaunchKernelGGL((rmsnorm_kernel<float, 16>), dim3((unsigned)grid), dim3(256), 0, st, (const float *)x, (const float *)g, (float *)y, rows, d, eps);
+        else
+            return GR4AD_EUNSUPPORTED;
+    }
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Gate half of Fuse (eq. fuse): a[row,:] = m_t[request,:] * (W_g s)[token,:],
+// with W_g s read from the per-token table built at init.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void fuse_gate_kernel(const float *__restrict__ m, int64_t m_req_stride, const float *__restrict__ G,
+                                                        const int32_t *__restrict__ tok, T *__restrict__ a, int64_t rows, int n, int d) {
+    constexpr int N = Vec16<T>::N;
+    const int nvec = d / N;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * nvec) return;
+    const int64_t row = idx / nvec;
+    const int c = (int)(idx % nvec);
+    const int64_t b = row / n;
+    const int64_t t = tok ? (int64_t)tok[row] : 0;
+    float mv[N], gv[N];
+#pragma unroll
+    for (int e = 0; e < N; e += 4) load16<float>(m + b * m_req_stride + (int64_t)c * N + e, &mv[e]);
+#pragma unroll
+    for (int e = 0; e < N; e += 4) load16<float>(G + t * d + (int64_t)c * N + e, &gv[e]);
+#pragma unroll
+    for (int e = 0; e < N; e++) mv[e] *= gv[e];
+    store16<T>(a + row * d + (int64_t)c * N, mv);
+}
+
+int launch_fuse_gate(gr4ad_dtype dtype, const void *m, int64_t m_req_stride, const void *G, const int32_t *tok, void *a, int B, int n,
+                     int d, hipStream_t st) {
+    const int N = dtype == GR4AD_BF16 ? 8 : 4;
+    int64_t rows = (int64_t)B * n, total = rows * (d / N);
+    int64_t grid = ceil_div64(total, 256);
+    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    ProfScope ps(KC_FUSE_GATE, st);
+    if (dtype == GR4AD_BF16)
+        hipLaunchKernelGGL(fuse_gate_kernel<bf16>, dim3((unsigned)grid), dim3(256), 0, st, (const float *)m, m_req_stride, (const float *)G, tok, (bf16 *)a, rows, n, d);
+    else
+        hipLaunchKernelGGL(fuse_gate_kernel<float>, dim3((unsigned)grid), dim3(256), 0, st, (const float *)m, m_req_stride, (const float *)G, tok, (float *)a, rows, n, d);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Trunk input (eq. trunk): m^(0)_t = p_t for every request.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void broadcast_rows_kernel(const T *__restrict__ pos, float *__restrict__ dst, int64_t total, int per_req) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    dst[idx] = to_f(pos[idx % per_req]);
+}
+
+int launch_broadcast_rows(gr4ad_dtype dtype, const void *pos, void *dst, int B, int T, int d, hipStream_t st) {
+    int per_req = T * d;
+    int64_t total = (int64_t)B * per_req;
+    int64_t grid = ceil_div64(total, 256);
+    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    ProfScope ps(KC_BROADCAST, st);
+    if (dtype == GR4AD_BF16)
+        hipLaunchKernelGGL(broadcast_rows_kernel<bf16>, dim3((unsigned)grid), dim3(256), 0, st, (const bf16 *)pos, (float *)dst, total, per_req);
+    else
+        hipLaunchKernelGGL(broadcast_rows_kernel<float>, dim3((unsigned)grid), dim3(256), 0, st, (const float *)pos, (float *)dst, total, per_req);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Beam reorder: survivors inherit their parent's self-attention K/V rows
+// (KV caching, appendix A.2).  Pure copy: dst[b,j,:] = src[b,parent[b,j],:].
+// One workgroup moves one row with 16-byte lanes; grid = B*k rows.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *__restrict__ src, const int32_t *__restrict__ parent,
+                                                          uint4 *__restrict__ dst, int n, int k, int64_t row_vec, int64_t stride_vec) {
+    const int64_t r = blockIdx.x;  // b*k + j
+    const int64_t b = r / k;
+    const int64_t p = parent[r];
+    const uint4 *s = src + (b * n + p) * stride_vec;
+    uint4 *o = dst + r * stride_vec;
+    for (int64_t i = threadIdx.x; i < row_vec; i += 256) o[i] = s[i];
+}
+
+int launch_gather_rows(gr4ad_dtype dtype, const void *src, const int32_t *parent, void *dst, int B, int n, int k, int64_t row_elems,
+                       int64_t row_stride, hipStream_t st) {
+    const int N = dtype == GR4AD_BF16 ? 8 : 4;
+    if (row_elems % N || row_stride % N || ((uintptr_t)src % 16) || ((uintptr_t)dst % 16)) return GR4AD_EUNSUPPORTED;
+    int64_t rows = (int64_t)B * k;
+    if (rows <= 0 || row_elems <= 0) return GR4AD_OK;
+    if (rows > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    ProfScope ps(KC_GATHER, st);
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)rows), dim3(256), 0, st, (const uint4 *)src, parent, (uint4 *)dst, n, k, row_elems / N, row_stride / N);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}

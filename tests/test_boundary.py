@@ -1,0 +1,97 @@
+"""CPU checks of the C-ABI boundary: the library loads, exports every function
+include/gr4ad.h declares, and rejects bad arguments before touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2602_22732_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "gr4ad.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gr4ad_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    L = binding.lib()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_strerror_and_null_handling():
+    L = binding.lib()
+    assert L.gr4ad_strerror(0) == b"ok"
+    assert L.gr4ad_strerror(-1) == b"invalid argument"
+    assert L.gr4ad_strerror(-3).startswith(b"workspace")
+    assert L.gr4ad_strerror(-99) == b"unknown status"
+    L.gr4ad_decode_free(None)  # no-op
+    beam = (C.c_int32 * 3)(1, 1, 1)
+    assert L.gr4ad_decode_workspace_bytes(None, 1, 1, beam) == 0
+    assert L.gr4ad_decode_batch(None, None, None, 1, 1, beam, None, 0, None, None, None) == -1
+    assert L.gr4ad_decode_set_trace(None, None, None, None) == -1
+
+
+def _desc(**over):
+    kw = dict(d_model=64, n_heads=2, d_ffn=128, n_layers=3, n_lazy=1, n_levels=3, max_batch=4, max_ctx=16, dtype=0, rms_eps=1e-6)
+    kw.update(over)
+    V = np.array(kw.pop("codebook", [8, 8, 8]), np.int32)
+    mb = np.array(kw.pop("max_beam", [4, 4, 4]), np.int32)
+    d = binding.ModelDesc(codebook=V.ctypes.data_as(binding._IP), max_beam=mb.ctypes.data_as(binding._IP), **kw)
+    d._keep = (V, mb)
+    return d
+
+
+@pytest.mark.parametrize("over,status,needle", [
+    (dict(n_lazy=3), -1, "n_lazy"),
+    (dict(n_lazy=-1), -1, "n_lazy"),
+    (dict(n_heads=3), -1, "divisible"),
+    (dict(n_levels=0), -1, "n_levels"),
+    (dict(n_levels=9, codebook=[8] * 9, max_beam=[4] * 9), -1, "n_levels"),
+    (dict(d_model=0), -1, "positive"),
+    (dict(dtype=7), -1, "dtype"),
+    (dict(codebook=[8, 0, 8]), -1, "codebook"),
+    (dict(d_model=48, n_heads=2), -2, "head width"),
+    (dict(max_beam=[4, 5000, 4]), -2, "max_beam"),
+    (dict(codebook=[8, 8, 20000]), -2, "codebook"),
+])
+def test_init_rejects_bad_descriptions_without_a_gpu(over, status, needle):
+    L = binding.lib()
+    out = C.c_void_p(0xDEAD)
+    w = binding.Weights()
+    rc = L.gr4ad_decode_init(C.byref(_desc(**over)), C.byref(w), C.byref(out))
+    assert rc == status
+    assert needle in L.gr4ad_last_error(None).decode()
+    assert out.value == 0xDEAD  # untouched on failure
+
+
+def test_init_rejects_null_pointers():
+    L = binding.lib()
+    out = C.c_void_p()
+    assert L.gr4ad_decode_init(None, None, C.byref(out)) == -1
+    assert L.gr4ad_decode_init(C.byref(_desc()), None, C.byref(out)) == -1
+    assert L.gr4ad_decode_init(C.byref(_desc()), C.byref(binding.Weights()), C.byref(out)) == -1  # all weight pointers NULL
+    assert "NULL" in L.gr4ad_last_error(None).decode()
+    assert L.gr4ad_decode_init(C.byref(_desc()), C.byref(binding.Weights()), None) == -1
+
+
+def test_select_workspace_formula():
+    L = binding.lib()
+    assert L.gr4ad_op_select_workspace_bytes(3, 5, 100, 7) == ((3 * 5 * 7 * 8 + 255) // 256) * 256
+    assert L.gr4ad_op_select_workspace_bytes(3, 5, 4, 7) == ((3 * 5 * 4 * 8 + 255) // 256) * 256
+    assert L.gr4ad_op_select_workspace_bytes(0, 5, 4, 7) == 0
+
+
+def test_ops_reject_bad_arguments_without_a_gpu():
+    L = binding.lib()
+    assert L.gr4ad_op_linear(0, None, None, None, None, 1, 1, 1, 0, None) == -1
+    assert L.gr4ad_op_select(None, None, 1, 1, 1, 1, None, 0, None, None, None, None) == -1
+    assert L.gr4ad_op_cross_attention(0, None, None, None, None, 1, 1, 1, 8, 1, None) == -1
+    assert L.gr4ad_op_gather_rows(0, None, None, None, 1, 1, 1, 8, 8, None) == -1
