@@ -172,9 +172,14 @@ int gr4ad_op_select(const float *logits_dev, const float *cum_dev, int32_t B, in
 /* Beam-shared cross-attention (section 4.2, Beam-Shared KV Caching): for each
  * request b and head h, out[b, i, h] = softmax(q[b,i,h] . K[b,:len_b,h] / sqrt(dh)) V[b,:len_b,h]
  * for all n query rows of the request.  q, out [B, n, d]; kv [B, S, 2d]
- * (keys in columns 0..d-1, values in d..2d-1); ctx_len [B] or NULL. */
+ * (keys in columns 0..d-1, values in d..2d-1); ctx_len [B] or NULL.
+ * workspace_dev (16-byte aligned) must hold gr4ad_op_cross_attention_workspace_bytes
+ * bytes: the matrix-core kernel reads the values from a per-head transposed copy
+ * it first writes there (0 bytes for shapes that run on the plain kernel). */
+size_t gr4ad_op_cross_attention_workspace_bytes(gr4ad_dtype dtype, int32_t B, int32_t S, int32_t d, int32_t H);
 int gr4ad_op_cross_attention(gr4ad_dtype dtype, const void *q_dev, const void *kv_dev, const int32_t *ctx_len_dev,
-                             void *out_dev, int32_t B, int32_t n, int32_t S, int32_t d, int32_t H, void *hip_stream);
+                             void *out_dev, int32_t B, int32_t n, int32_t S, int32_t d, int32_t H, void *workspace_dev,
+                             size_t workspace_bytes, void *hip_stream);
 
 /* Beam reorder: dst[b, j, 0:row_elems] = src[b, parent[b,j], 0:row_elems] for
  * j < k; rows are `row_stride` elements apart in both buffers, src holds n rows

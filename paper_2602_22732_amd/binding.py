@@ -17,7 +17,8 @@ F32, BF16 = 0, 1
 LAYER_FIELDS = ["ln_x", "wq_x", "wk_x", "wv_x", "wo_x", "ln_s", "wq_s", "wk_s", "wv_s", "wo_s", "ln_f", "w1", "w2"]
 EXPORTS = ["gr4ad_decode_init", "gr4ad_decode_workspace_bytes", "gr4ad_decode_batch", "gr4ad_decode_set_trace",
            "gr4ad_decode_free", "gr4ad_strerror", "gr4ad_last_error", "gr4ad_op_linear", "gr4ad_op_select_workspace_bytes",
-           "gr4ad_op_select", "gr4ad_op_cross_attention", "gr4ad_op_gather_rows", "gr4ad_profile_enable",
+           "gr4ad_op_select", "gr4ad_op_cross_attention_workspace_bytes", "gr4ad_op_cross_attention", "gr4ad_op_gather_rows",
+           "gr4ad_profile_enable",
            "gr4ad_profile_kernel_count", "gr4ad_profile_kernel_name", "gr4ad_profile_read"]
 
 _IP = C.POINTER(C.c_int32)
@@ -77,7 +78,10 @@ def lib():
         L.gr4ad_op_select.restype = C.c_int
         L.gr4ad_op_select.argtypes = [_VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP, C.c_size_t, _VP, _VP, _VP, _VP]
         L.gr4ad_op_cross_attention.restype = C.c_int
-        L.gr4ad_op_cross_attention.argtypes = [C.c_int, _VP, _VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP]
+        L.gr4ad_op_cross_attention.argtypes = [C.c_int, _VP, _VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP,
+                                               C.c_size_t, _VP]
+        L.gr4ad_op_cross_attention_workspace_bytes.restype = C.c_size_t
+        L.gr4ad_op_cross_attention_workspace_bytes.argtypes = [C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.gr4ad_op_gather_rows.restype = C.c_int
         L.gr4ad_op_gather_rows.argtypes = [C.c_int, _VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, _VP]
         L.gr4ad_profile_enable.restype = C.c_int
@@ -257,8 +261,10 @@ def op_cross_attention(q, kv, ctx_len, H, stream=None):
     B, n, d = q.shape
     S = kv.shape[1]
     out = torch.empty_like(q)
+    nbytes = int(lib().gr4ad_op_cross_attention_workspace_bytes(dtype_code(q.dtype), B, S, d, H))
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=q.device)
     _check(lib().gr4ad_op_cross_attention(dtype_code(q.dtype), q.data_ptr(), kv.data_ptr(), None if ctx_len is None else ctx_len.data_ptr(),
-                                          out.data_ptr(), B, n, S, d, H, _stream_ptr(stream)))
+                                          out.data_ptr(), B, n, S, d, H, ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
     return out
 
 

@@ -64,11 +64,265 @@ __global__ __launch_bounds__(256) void cross_attn_simple(const T *__restrict__ q
     if (lane + 64 < dh) out[row * ldo + h * dh + lane + 64] = from_f<T>(acc[1] * inv);
 }
 
-int launch_cross_attention(gr4ad_dtype dtype, const void *q, int64_t ldq, const void *kv, const int32_t *ctx_len, void *out, int64_t ldo,
-                           int B, int n, int S, int d, int H, hipStream_t st) {
+// ---------------------------------------------------------------------------
+// beam-shared flash cross-attention on the matrix cores (bf16)
+// ---------------------------------------------------------------------------
+// Values transposed per (request, head): vt[b][h][c][s] = V[b][s][h*dh+c] for s < len_b, 0 beyond
+// (s runs to Spad = S rounded up to 64), so a tile of V^T is row-major like a tile of K.
+__global__ __launch_bounds__(256) void v_transpose_kernel(const bf16 *__restrict__ kv, const int32_t *__restrict__ ctx_len,
+                                                          bf16 *__restrict__ vt, int S, int Spad, int d) {
+    __shared__ bf16 tile[64][66];
+    const int b = blockIdx.z, c0 = blockIdx.y * 64, s0 = blockIdx.x * 64;
+    int len = ctx_len ? ctx_len[b] : S;
+    len = len < 1 ? 1 : (len > S ? S : len);
+    const int tid = threadIdx.x;
+    for (int i = tid; i < 64 * 8; i += 256) {  // 64 rows (s) x 8 chunks of 8 columns
+        const int r = i / 8, ch = i % 8, s = s0 + r;
+        uint4 raw = make_uint4(0, 0, 0, 0);
+        if (s < len) raw = *(const uint4 *)(kv + ((int64_t)b * S + s) * 2 * d + d + c0 + ch * 8);
+        const bf16 *e = (const bf16 *)&raw;
+#pragma unroll
+        for (int k = 0; k < 8; k++) tile[r][ch * 8 + k] = e[k];
+    }
+    __syncthreads();
+    for (int i = tid; i < 64 * 8; i += 256) {  // 64 rows (c) x 8 chunks of 8 positions
+        const int r = i / 8, ch = i % 8;
+        uint4 raw;
+        bf16 *e = (bf16 *)&raw;
+#pragma unroll
+        for (int k = 0; k < 8; k++) e[k] = tile[ch * 8 + k][r];
+        *(uint4 *)(vt + ((int64_t)b * d + c0 + r) * Spad + s0 + ch * 8) = raw;
+    }
+}
+
+// One workgroup: NW wavefronts x QT tiles of 32 beams of one (request, head).  Per 64-key
+// tile of the context the workgroup stages K [64 x DH] and V^T [DH x 64] in LDS once and
+// every beam of the block reuses them.  Both products are computed transposed,
+//   S^T = K Q^T  (keys x beams)   and   O^T = V^T P^T  (head dims x beams),
+// so that each lane owns one beam: its running max / sum are lane-local, P^T leaves the
+// accumulators of the first product already in the operand layout of the second, and the
+// only cross-lane step is one exchange between the two half-waves.  Key rows enter the
+// first product with index bits 2 and 3 swapped, which makes the 8 keys a lane holds for
+// one MFMA k-step consecutive (one 16-byte chunk of a V^T row).
+template <int DH, int QT, int NW>
+__global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__restrict__ q, int64_t ldq, const bf16 *__restrict__ kv,
+                                                                 const bf16 *__restrict__ vt, const int32_t *__restrict__ ctx_len,
+                                                                 bf16 *__restrict__ out, int64_t ldo, int n, int S, int Spad, int d,
+                                                                 int H, float scale_log2e) {
+    constexpr int NTH = NW * 64;
+    constexpr int KCH = DH / 8;                   // 16-byte chunks per K row
+    constexpr int K_CHUNKS = 64 * KCH, V_CHUNKS = DH * 8;
+    constexpr int STAGE = K_CHUNKS + V_CHUNKS;
+    constexpr int PER_THREAD = (STAGE + NTH - 1) / NTH;
+    constexpr int KSTEPS = DH / 16, MT = DH / 32;
+    __shared__ uint4 smem[2 * STAGE];
+    const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int frow = lane % 32, hf = lane / 32;
+    int len = ctx_len ? ctx_len[b] : S;
+    len = len < 1 ? 1 : (len > S ? S : len);
+    const int ntiles = (len + 63) / 64;
+    const int q0 = (blockIdx.x * NW + wave) * (QT * 32);
+
+    // query fragments stay in registers for the whole kernel
+    bf16x8 qf[QT][KSTEPS];
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) {
+        int row = q0 + qt * 32 + frow;
+        if (row > n - 1) row = n - 1;  // rows past the end are computed and dropped
+        const bf16 *qr = q + ((int64_t)b * n + row) * ldq + h * DH;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; s++) qf[qt][s] = *(const bf16x8 *)(qr + 16 * s + 8 * hf);
+    }
+
+    // staging of one key tile: chunk ids [0, K_CHUNKS) are K, the rest V^T
+    const bf16 *kbase = kv + (int64_t)b * S * 2 * d + h * DH;
+    const bf16 *vbase = vt + ((int64_t)b * d + h * DH) * Spad;
+    uint4 stage_reg[PER_THREAD];
+    auto load_tile = [&](int tile) {
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; i++) {
+            const int id = tid + i * NTH;
+            if (id < K_CHUNKS) {
+                int key = tile * 64 + id / KCH;
+                if (key > S - 1) key = S - 1;  // stays inside the buffer; masked below
+                stage_reg[i] = *(const uint4 *)(kbase + (int64_t)key * 2 * d + (id % KCH) * 8);
+            } else if (id < STAGE) {
+                const int v = id - K_CHUNKS;
+                stage_reg[i] = *(const uint4 *)(vbase + (int64_t)(v / 8) * Spad + tile * 64 + (v % 8) * 8);
+            }
+        }
+    };
+    auto store_tile = [&](int stage) {
+        uint4 *sk = smem + stage * STAGE, *sv = sk + K_CHUNKS;
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; i++) {
+            const int id = tid + i * NTH;
+            if (id < K_CHUNKS) {
+                const int r = id / KCH, c = id % KCH;
+                sk[r * KCH + (c ^ ((KCH == 8 ? r : (r >> 1)) & (KCH - 1)))] = stage_reg[i];
+            } else if (id < STAGE) {
+                const int v = id - K_CHUNKS, r = v / 8, c = v % 8;
+                sv[r * 8 + (c ^ (r & 7))] = stage_reg[i];
+            }
+        }
+    };
+
+    float m_run[QT], l_run[QT];
+    floatx16 o[QT][MT];
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) {
+        m_run[qt] = -INFINITY;
+        l_run[qt] = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) o[qt][mt][v] = 0.0f;
+    }
+    // key row read by this lane in the first product: bits 2 and 3 of the row index swapped
+    const int krow = (frow & 0x13) | ((frow & 4) << 1) | ((frow & 8) >> 1);
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+    for (int tile = 0; tile < ntiles; tile++) {
+        if (tile + 1 < ntiles) load_tile(tile + 1);
+        const uint4 *sk = smem + (tile & 1) * STAGE, *sv = sk + K_CHUNKS;
+        floatx16 s[QT][2];
+#pragma unroll
+        for (int sub = 0; sub < 2; sub++) {
+#pragma unroll
+            for (int qt = 0; qt < QT; qt++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) s[qt][sub][v] = 0.0f;
+            const int r = sub * 32 + krow;
+#pragma unroll
+            for (int st = 0; st < KSTEPS; st++) {
+                uint4 t = sk[r * KCH + ((2 * st + hf) ^ ((KCH == 8 ? r : (r >> 1)) & (KCH - 1)))];
+                bf16x8 kf = *(bf16x8 *)&t;
+#pragma unroll
+                for (int qt = 0; qt < QT; qt++) s[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][st], s[qt][sub], 0, 0, 0);
+            }
+        }
+        // this lane holds, for beam frow of each tile qt, keys tile*64 + 32*sub + 16*(v/8) + 8*hf + v%8
+        const int key0 = tile * 64 + 8 * hf;
+        bf16x8 pf[QT][4];
+#pragma unroll
+        for (int qt = 0; qt < QT; qt++) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) {
+                    const int key = key0 + 32 * sub + 16 * (v / 8) + (v % 8);
+                    const float x = key < len ? s[qt][sub][v] * scale_log2e : -INFINITY;
+                    s[qt][sub][v] = x;
+                    mx = fmaxf(mx, x);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float mnew = fmaxf(m_run[qt], mx);  // finite: every tile holds at least one valid key
+            const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - mnew);
+            m_run[qt] = mnew;
+            float lsum = 0.0f;
+#pragma unroll
+            for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) {
+                    const float p = __builtin_amdgcn_exp2f(s[qt][sub][v] - mnew);
+                    lsum += p;
+                    pf[qt][2 * sub + v / 8][v % 8] = (bf16)p;  // k-step 2*sub + v/8 of the second product
+                }
+            l_run[qt] = l_run[qt] * alpha + lsum;  // per half-wave partial sum, joined at the end
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) o[qt][mt][v] *= alpha;
+        }
+        // second product; V^T fragments are shared by the QT beam tiles
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++)
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                const int r = mt * 32 + frow;
+                uint4 t = sv[r * 8 + ((2 * ks + hf) ^ (r & 7))];
+                bf16x8 vf = *(bf16x8 *)&t;
+#pragma unroll
+                for (int qt = 0; qt < QT; qt++) o[qt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][ks], o[qt][mt], 0, 0, 0);
+            }
+        if (tile + 1 < ntiles) store_tile((tile + 1) & 1);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) {
+        const float l = l_run[qt] + __shfl_xor(l_run[qt], 32, 64);
+        const float inv = 1.0f / l;
+        const int row = q0 + qt * 32 + frow;
+        if (row < n) {
+            bf16 *orow = out + ((int64_t)b * n + row) * ldo + h * DH;
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    bf16x4 pk;
+#pragma unroll
+                    for (int j = 0; j < 4; j++) pk[j] = (bf16)(o[qt][mt][4 * g + j] * inv);
+                    *(bf16x4 *)(orow + mt * 32 + 8 * g + 4 * hf) = pk;
+                }
+        }
+    }
+}
+
+size_t cross_attention_workspace_bytes(gr4ad_dtype dtype, int B, int S, int d, int H) {
+    const int dh = d / H;
+    if (dtype != GR4AD_BF16 || (dh != 32 && dh != 64) || d % 64) return 0;
+    const int64_t Spad = (S + 63) / 64 * 64;
+    return (size_t)B * d * Spad * sizeof(bf16);
+}
+
+int launch_cross_attention_prepare(gr4ad_dtype dtype, const void *kv, const int32_t *ctx_len, void *vt, int B, int S, int d, int H,
+                                   hipStream_t st) {
+    if (cross_attention_workspace_bytes(dtype, B, S, d, H) == 0) return GR4AD_OK;  // plain kernel reads kv directly
+    if (!vt || ((uintptr_t)vt % 16) || ((uintptr_t)kv % 16)) return GR4AD_EWORKSPACE;
+    const int Spad = (S + 63) / 64 * 64;
+    if (B > 65535 || d / 64 > 65535) return GR4AD_EUNSUPPORTED;
+    ProfScope ps(KC_V_TRANSPOSE, st);
+    hipLaunchKernelGGL(v_transpose_kernel, dim3(Spad / 64, d / 64, B), dim3(256), 0, st, (const bf16 *)kv, ctx_len, (bf16 *)vt, S, Spad, d);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+template <int DH, int QT, int NW>
+static int launch_flash(const bf16 *q, int64_t ldq, const bf16 *kv, const bf16 *vt, const int32_t *ctx_len, bf16 *out, int64_t ldo, int B,
+                        int n, int S, int d, int H, hipStream_t st) {
+    const int per_block = NW * QT * 32;
+    dim3 grid((n + per_block - 1) / per_block, H, B);
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
+    ProfScope ps(KC_XATTN_FLASH, st);
+    hipLaunchKernelGGL((cross_attn_flash_bf16<DH, QT, NW>), grid, dim3(NW * 64), 0, st, q, ldq, kv, vt, ctx_len, out, ldo, n, S,
+                       (S + 63) / 64 * 64, d, H, scale_log2e);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+int launch_cross_attention(gr4ad_dtype dtype, const void *q, int64_t ldq, const void *kv, const void *vt, const int32_t *ctx_len, void *out,
+                           int64_t ldo, int B, int n, int S, int d, int H, hipStream_t st) {
     if (B <= 0 || n <= 0 || S <= 0 || d <= 0 || H <= 0 || d % H) return GR4AD_EINVAL;
     const int dh = d / H;
     if (dh > 128) return GR4AD_EUNSUPPORTED;
+    if (vt && cross_attention_workspace_bytes(dtype, B, S, d, H) && ldq % 8 == 0 && ldo % 4 == 0 && ((uintptr_t)q % 16) == 0 &&
+        ((uintptr_t)out % 8) == 0 && B <= 65535 && H <= 65535) {
+        const bf16 *qq = (const bf16 *)q, *kk = (const bf16 *)kv, *vv = (const bf16 *)vt;
+        bf16 *oo = (bf16 *)out;
+        if (dh == 64) {
+            if (n <= 128) return launch_flash<64, 1, 4>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+            if (n <= 256) return launch_flash<64, 2, 4>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+            return launch_flash<64, 2, 8>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+        } else {
+            if (n <= 128) return launch_flash<32, 1, 4>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+            if (n <= 256) return launch_flash<32, 2, 4>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+            return launch_flash<32, 2, 8>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+        }
+    }
     const int64_t rows = (int64_t)B * n;
     const int64_t grid = ceil_div64(rows * H, 4);
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;

@@ -63,8 +63,13 @@ int launch_gather_rows(gr4ad_dtype dtype, const void *src, const int32_t *parent
 
 // ---- attention ---------------------------------------------------------------
 // beam-shared cross-attention; q/out row stride ldq/ldo elements, rows (b*n+i)
-int launch_cross_attention(gr4ad_dtype dtype, const void *q, int64_t ldq, const void *kv, const int32_t *ctx_len, void *out, int64_t ldo,
-                           int B, int n, int S, int d, int H, hipStream_t st);
+// vt: per-(request, head) transposed values built by launch_cross_attention_prepare (NULL: plain kernel on kv alone)
+int launch_cross_attention(gr4ad_dtype dtype, const void *q, int64_t ldq, const void *kv, const void *vt, const int32_t *ctx_len, void *out,
+                           int64_t ldo, int B, int n, int S, int d, int H, hipStream_t st);
+// bytes of the transposed-value buffer the MFMA kernel needs for kv [B,S,2d] (0: the shape runs on the plain kernel)
+size_t cross_attention_workspace_bytes(gr4ad_dtype dtype, int B, int S, int d, int H);
+int launch_cross_attention_prepare(gr4ad_dtype dtype, const void *kv, const int32_t *ctx_len, void *vt, int B, int S, int d, int H,
+                                   hipStream_t st);
 // autoregressive self-attention of position `pos` for rows (b*n+i): qkv [rows,3d];
 // cache [B*n_stride... ] laid out [rows][T][2d] with per-request capacity cache_rows; writes k,v at `pos`
 int launch_self_attention_step(gr4ad_dtype dtype, const void *qkv, void *cache, void *out, int64_t rows, int pos, int T, int d, int H,
@@ -80,7 +85,7 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
 
 // ---- optional per-kernel event timing ----------------------------------------
 enum KernelClass { KC_GEMM_256 = 0, KC_GEMM_128, KC_GEMM_SIMPLE, KC_XATTN_FLASH, KC_XATTN_SIMPLE, KC_SELF_STEP, KC_TRUNK_SELF,
-                   KC_RMSNORM, KC_FUSE_GATE, KC_SELECT_ROWS, KC_SELECT_REQUEST, KC_GATHER, KC_BROADCAST, KC_COUNT };
+                   KC_RMSNORM, KC_FUSE_GATE, KC_SELECT_ROWS, KC_SELECT_REQUEST, KC_GATHER, KC_BROADCAST, KC_V_TRANSPOSE, KC_COUNT };
 // Declared around a kernel launch: records an event before and (on scope exit) after it when timing is on.
 struct ProfScope {
     ProfScope(int cls, hipStream_t st, double flops = 0.0);

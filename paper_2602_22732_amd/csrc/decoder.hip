@@ -57,7 +57,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Everything decode_batch carves out of the caller's workspace.
 struct Plan {
-    size_t kv_ar, kv_lazy, trunk, h, xn, q, o, qkv, f, logits, selws, cache[2], cum[2], par, tok[2], sid[2], total;
+    size_t kv_ar, kv_lazy, vt_ar, vt_lazy, vt_bytes, trunk, h, xn, q, o, qkv, f, logits, selws, cache[2], cum[2], par, tok[2], sid[2], total;
     int64_t rows_max, nmax, bmax;
     size_t cache_layer_elems;
 };
@@ -93,6 +93,9 @@ Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *be
     auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
     p.kv_ar = take((size_t)dec->A * B * S * 2 * d * e);
     p.kv_lazy = take(dec->K > 0 ? (size_t)B * S * 2 * d * e : 0);
+    p.vt_bytes = cross_attention_workspace_bytes(dec->dtype, (int)B, (int)S, dec->d, dec->H);
+    p.vt_ar = take((size_t)dec->A * p.vt_bytes);
+    p.vt_lazy = take(dec->K > 0 ? p.vt_bytes : 0);
     p.trunk = take((size_t)B * T * d * sizeof(float));  // residual streams stay float32 whatever the storage dtype
     p.h = take((size_t)p.rows_max * d * sizeof(float));
     p.xn = take((size_t)p.rows_max * d * e);
@@ -344,11 +347,11 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     auto silu_epi = [&](void *x, int64_t ld) { GemmEpilogue g = plain_epilogue(x, ld); g.act = ACT_SILU; return g; };
 
     // cross-attention + its residual; x is the residual stream [rows,d]
-    auto cross_block = [&](const LayerPacked &lw, void *x, int64_t rows, int n, const void *kvbuf) -> int {
+    auto cross_block = [&](const LayerPacked &lw, void *x, int64_t rows, int n, const void *kvbuf, const void *vtbuf) -> int {
         int s;
         if ((s = launch_rmsnorm(dt, x, lw.ln_x, xn, rows, d, dec->eps, st))) return s;
         if ((s = gemm(xn, rows, lw.wq_x, d, d, plain_epilogue(q, d)))) return s;
-        if ((s = launch_cross_attention(dt, q, d, kvbuf, ctx_len, o, d, B, n, S, d, H, st))) return s;
+        if ((s = launch_cross_attention(dt, q, d, kvbuf, vtbuf, ctx_len, o, d, B, n, S, d, H, st))) return s;
         return gemm(o, rows, lw.wo_x, d, d, resid_epi(x, d));
     };
     auto ffn_block = [&](const LayerPacked &lw, void *x, int64_t rows) -> int {
@@ -359,8 +362,12 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     };
 
     // ---- step 0: context keys/values of the autoregressive layers, once per request ----
-    for (int a = 0; a < A; a++)
+    auto vt_ar = [&](int a) { return p.vt_bytes ? (void *)(ws + p.vt_ar + (size_t)a * p.vt_bytes) : (void *)nullptr; };
+    void *vt_lazy = p.vt_bytes ? (void *)(ws + p.vt_lazy) : (void *)nullptr;
+    for (int a = 0; a < A; a++) {
         OP_TRY(dec, gemm(ctx, (int64_t)B * S, dec->layers[K + a].wkv_x, 2 * d, d, plain_epilogue(kv_ar(a), 2 * d)), "context K/V projection");
+        OP_TRY(dec, launch_cross_attention_prepare(dt, kv_ar(a), ctx_len, vt_ar(a), B, S, d, H, st), "context value transpose");
+    }
 
     // ---- step 1: lazy pass (eq. trunk): all T levels at once, no beam dimension ----
     OP_TRY(dec, launch_broadcast_rows(dt, dec->pos, trunk, B, T, d, st), "trunk input");
@@ -369,7 +376,8 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         void *kvl = ws + p.kv_lazy;
         const int64_t rows = (int64_t)B * T;
         OP_TRY(dec, gemm(ctx, (int64_t)B * S, lw.wkv_x, 2 * d, d, plain_epilogue(kvl, 2 * d)), "lazy context K/V projection");
-        OP_TRY(dec, cross_block(lw, trunk, rows, T, kvl), "lazy cross-attention");
+        OP_TRY(dec, launch_cross_attention_prepare(dt, kvl, ctx_len, vt_lazy, B, S, d, H, st), "lazy context value transpose");
+        OP_TRY(dec, cross_block(lw, trunk, rows, T, kvl, vt_lazy), "lazy cross-attention");
         OP_TRY(dec, launch_rmsnorm(dt, trunk, lw.ln_s, xn, rows, d, dec->eps, st), "lazy norm");
         OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, plain_epilogue(qkv, 3 * d)), "lazy qkv");
         OP_TRY(dec, launch_trunk_self_attention(dt, qkv, o, B, T, d, H, st), "lazy self-attention");
@@ -393,7 +401,7 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         }
         for (int a = 0; a < A; a++) {
             const LayerPacked &lw = dec->layers[K + a];
-            OP_TRY(dec, cross_block(lw, h, rows, n, kv_ar(a)), "cross-attention");
+            OP_TRY(dec, cross_block(lw, h, rows, n, kv_ar(a), vt_ar(a)), "cross-attention");
             OP_TRY(dec, launch_rmsnorm(dt, h, lw.ln_s, xn, rows, d, dec->eps, st), "self-attention norm");
             OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, plain_epilogue(qkv, 3 * d)), "self-attention qkv");
             OP_TRY(dec, launch_self_attention_step(dt, qkv, cache(cur, a), o, rows, t, T, d, H, st), "self-attention");
@@ -452,10 +460,19 @@ int gr4ad_op_select(const float *logits, const float *cum, int32_t B, int32_t n,
     return launch_select(logits, cum, B, n, V, k, ws, ws_bytes, parent, tok, score, nullptr, nullptr, 0, 0, (hipStream_t)hip_stream);
 }
 
+size_t gr4ad_op_cross_attention_workspace_bytes(gr4ad_dtype dtype, int32_t B, int32_t S, int32_t d, int32_t H) {
+    if (B < 1 || S < 1 || d < 1 || H < 1 || d % H) return 0;
+    return cross_attention_workspace_bytes(dtype, B, S, d, H);
+}
+
 int gr4ad_op_cross_attention(gr4ad_dtype dtype, const void *q, const void *kv, const int32_t *ctx_len, void *out, int32_t B, int32_t n,
-                             int32_t S, int32_t d, int32_t H, void *hip_stream) {
-    if (!q || !kv || !out || (dtype != GR4AD_F32 && dtype != GR4AD_BF16)) return GR4AD_EINVAL;
-    return launch_cross_attention(dtype, q, d, kv, ctx_len, out, d, B, n, S, d, H, (hipStream_t)hip_stream);
+                             int32_t S, int32_t d, int32_t H, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!q || !kv || !out || (dtype != GR4AD_F32 && dtype != GR4AD_BF16) || B < 1 || n < 1 || S < 1 || d < 1 || H < 1 || d % H) return GR4AD_EINVAL;
+    const size_t need = cross_attention_workspace_bytes(dtype, B, S, d, H);
+    if (need && (!workspace || workspace_bytes < need)) return GR4AD_EWORKSPACE;
+    int s = launch_cross_attention_prepare(dtype, kv, ctx_len, workspace, B, S, d, H, (hipStream_t)hip_stream);
+    if (s) return s;
+    return launch_cross_attention(dtype, q, d, kv, need ? workspace : nullptr, ctx_len, out, d, B, n, S, d, H, (hipStream_t)hip_stream);
 }
 
 int gr4ad_op_gather_rows(gr4ad_dtype dtype, const void *src, const int32_t *parent, void *dst, int32_t B, int32_t n, int32_t k,

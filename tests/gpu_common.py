@@ -8,10 +8,10 @@ from paper_2602_22732_amd import binding, synth
 
 TOL_LOGPROB = {"f32": 1e-4, "bf16": 2e-2}
 # Score gap above which SID indices must agree exactly.  fp32 path: 1e-3.  The bf16 path is
-# allowed a log-probability error of 2e-2, which can legitimately swap candidates closer than
-# that, so its indices are held exact only beyond 2e-2; how often the 1e-3 rule also holds is
-# reported by judge_decode ("strict_ok").
-MARGIN = {"f32": 1e-3, "bf16": 2e-2}
+# allowed a log-probability error of 2e-2 per candidate, so two candidates closer than twice
+# that can legitimately swap: its indices are held exact beyond 4e-2.  How often the 1e-3 rule
+# also holds is reported by judge_decode ("strict_ok").
+MARGIN = {"f32": 1e-3, "bf16": 4e-2}
 STRICT_MARGIN = 1e-3
 
 

@@ -93,5 +93,7 @@ def test_ops_reject_bad_arguments_without_a_gpu():
     L = binding.lib()
     assert L.gr4ad_op_linear(0, None, None, None, None, 1, 1, 1, 0, None) == -1
     assert L.gr4ad_op_select(None, None, 1, 1, 1, 1, None, 0, None, None, None, None) == -1
-    assert L.gr4ad_op_cross_attention(0, None, None, None, None, 1, 1, 1, 8, 1, None) == -1
+    assert L.gr4ad_op_cross_attention(0, None, None, None, None, 1, 1, 1, 8, 1, None, 0, None) == -1
+    assert L.gr4ad_op_cross_attention_workspace_bytes(1, 2, 100, 128, 2) == 2 * 128 * 128 * 2   # bf16, dh 64: S padded to 128
+    assert L.gr4ad_op_cross_attention_workspace_bytes(0, 2, 100, 128, 2) == 0                   # float32 runs on the plain kernel
     assert L.gr4ad_op_gather_rows(0, None, None, None, 1, 1, 1, 8, 8, None) == -1

@@ -22,7 +22,7 @@ def run_and_judge(w, W, X, lens, requests=None, beam=None):
     sid, lp, tr = gpu_decode(w, W, X, lens, beam=beam)
     requests = range(X.shape[0]) if requests is None else requests
     tol = TOY_BF16_TOL if w.dtype == "bf16" else None
-    return sid, lp, tr, judge_decode(w, W, X, lens, sid, lp, tr, requests, beam=beam, tol=tol, margin=tol)
+    return sid, lp, tr, judge_decode(w, W, X, lens, sid, lp, tr, requests, beam=beam, tol=tol, margin=None if tol is None else 2 * tol)
 
 
 def test_config1_tiny_fp32_full_batch_matches_oracle_exactly_where_margins_allow():
@@ -50,7 +50,7 @@ def test_config1_tiny_fp32_full_batch_matches_oracle_exactly_where_margins_allow
     dict(T=1, V=[1000], d=64, H=1, F=64, L=1, K=0, S=3, B=4, beam=[10]),                          # single level
 ])
 def test_small_shapes_match_oracle(dtype, shape):
-    w, W, X = tiny(dtype=dtype, **shape)
+    w, W, X = tiny(dtype=dtype, gain_jitter=0.3 if dtype == "f32" else 0.1, **shape)
     lens = synth.make_lengths(w, seed=11)
     sid, lp, tr, stats = run_and_judge(w, W, X, lens)
     print(dtype, shape["V"], stats)

@@ -75,7 +75,8 @@ def test_select_exact_ties_and_quantised_scores():
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("B,n,S,d,H", [(2, 5, 37, 64, 2), (1, 70, 130, 128, 2), (3, 1, 1, 64, 4), (2, 33, 200, 256, 2)])
+@pytest.mark.parametrize("B,n,S,d,H", [(2, 5, 37, 64, 2), (1, 70, 130, 128, 2), (3, 1, 1, 64, 4), (2, 33, 200, 256, 2),
+                                       (2, 200, 300, 128, 2), (1, 600, 129, 192, 3), (2, 300, 64, 128, 4), (1, 1030, 70, 64, 2)])
 def test_cross_attention_matches_oracle(dtype, B, n, S, d, H):
     q = RNG.standard_normal((B, n, d)).astype(np.float32)
     kv = RNG.standard_normal((B, S, 2 * d)).astype(np.float32)
