@@ -115,7 +115,7 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
     constexpr int STAGE = K_CHUNKS + V_CHUNKS;
     constexpr int PER_THREAD = (STAGE + NTH - 1) / NTH;
     constexpr int KSTEPS = DH / 16, MT = DH / 32;
-    __shared__ uint4 smem[2 * STAGE];
+    __shared__ bf16x8 smem[2 * STAGE];
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int b = blockIdx.z, h = blockIdx.y;
     const int frow = lane % 32, hf = lane / 32;
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
     // staging of one key tile: chunk ids [0, K_CHUNKS) are K, the rest V^T
     const bf16 *kbase = kv + (int64_t)b * S * 2 * d + h * DH;
     const bf16 *vbase = vt + ((int64_t)b * d + h * DH) * Spad;
-    uint4 stage_reg[PER_THREAD];
+    bf16x8 stage_reg[PER_THREAD];
     auto load_tile = [&](int tile) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; i++) {
@@ -146,15 +146,15 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
             if (id < K_CHUNKS) {
                 int key = tile * 64 + id / KCH;
                 if (key > S - 1) key = S - 1;  // stays inside the buffer; masked below
-                stage_reg[i] = *(const uint4 *)(kbase + (int64_t)key * 2 * d + (id % KCH) * 8);
+                stage_reg[i] = *(const bf16x8 *)(kbase + (int64_t)key * 2 * d + (id % KCH) * 8);
             } else if (id < STAGE) {
                 const int v = id - K_CHUNKS;
-                stage_reg[i] = *(const uint4 *)(vbase + (int64_t)(v / 8) * Spad + tile * 64 + (v % 8) * 8);
+                stage_reg[i] = *(const bf16x8 *)(vbase + (int64_t)(v / 8) * Spad + tile * 64 + (v % 8) * 8);
             }
         }
     };
     auto store_tile = [&](int stage) {
-        uint4 *sk = smem + stage * STAGE, *sv = sk + K_CHUNKS;
+        bf16x8 *sk = smem + stage * STAGE, *sv = sk + K_CHUNKS;
 #pragma unroll
         for (int i = 0; i < PER_THREAD; i++) {
             const int id = tid + i * NTH;
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
     __syncthreads();
     for (int tile = 0; tile < ntiles; tile++) {
         if (tile + 1 < ntiles) load_tile(tile + 1);
-        const uint4 *sk = smem + (tile & 1) * STAGE, *sv = sk + K_CHUNKS;
+        const bf16x8 *sk = smem + (tile & 1) * STAGE, *sv = sk + K_CHUNKS;
         floatx16 s[QT][2];
 #pragma unroll
         for (int sub = 0; sub < 2; sub++) {
@@ -198,8 +198,7 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
             const int r = sub * 32 + krow;
 #pragma unroll
             for (int st = 0; st < KSTEPS; st++) {
-                uint4 t = sk[r * KCH + ((2 * st + hf) ^ ((KCH == 8 ? r : (r >> 1)) & (KCH - 1)))];
-                bf16x8 kf = *(bf16x8 *)&t;
+                const bf16x8 kf = sk[r * KCH + ((2 * st + hf) ^ ((KCH == 8 ? r : (r >> 1)) & (KCH - 1)))];
 #pragma unroll
                 for (int qt = 0; qt < QT; qt++) s[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][st], s[qt][sub], 0, 0, 0);
             }
@@ -244,8 +243,7 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
 #pragma unroll
             for (int mt = 0; mt < MT; mt++) {
                 const int r = mt * 32 + frow;
-                uint4 t = sv[r * 8 + ((2 * ks + hf) ^ (r & 7))];
-                bf16x8 vf = *(bf16x8 *)&t;
+                const bf16x8 vf = sv[r * 8 + ((2 * ks + hf) ^ (r & 7))];
 #pragma unroll
                 for (int qt = 0; qt < QT; qt++) o[qt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][ks], o[qt][mt], 0, 0, 0);
             }

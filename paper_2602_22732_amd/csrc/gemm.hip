@@ -13,14 +13,14 @@
 #include "common.h"
 
 // ---------------------------------------------------------------------------
-// epilogue shared by both kernels (one element)
+// epilogue of one element (plain kernel)
 // ---------------------------------------------------------------------------
 template <typename T>
 __device__ __forceinline__ void epilogue_store(const GemmEpilogue &e, int64_t row, int col, int N, float v) {
     if (e.bias) v += e.bias[col];
     if (e.table) {
         int64_t tr = e.tok ? (int64_t)e.tok[row] : 0;
-        v += ((const float *)e.table)[tr * N + col];
+        v += e.table[tr * N + col];
     }
     if (e.act == ACT_SILU) v = v / (1.0f + __expf(-v));
     if (e.resid) v += e.resid[row * e.ldr + col];
@@ -79,9 +79,12 @@ __global__ __launch_bounds__(256) void gemm_simple(const T *__restrict__ A, int6
 // ---------------------------------------------------------------------------
 // Block tile BM x BN, wave tile WM x WN, BK = 64 (one 128-byte row of bf16 per
 // tile row = 8 chunks of 16 bytes).  LDS holds two stages of (BM + BN) rows.
-// Chunk c of row r sits at slot c ^ (r & 7), so the 32 rows a wave touches in
-// one fragment read are spread over all banks.
-template <int BM, int BN, int WM, int WN>
+// Chunk c of row r sits at slot c ^ (r & 7), so the rows a wave touches in one
+// fragment read are spread over all banks.  The next K tile travels
+// global -> registers while the current one is multiplied, then registers -> LDS.
+enum { EPI_STORE = 0, EPI_SILU, EPI_F32, EPI_F32_RESID, EPI_F32_TABLE };
+
+template <int BM, int BN, int WM, int WN, int KIND>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(const bf16 *__restrict__ A, int64_t lda,
                                                                              const bf16 *__restrict__ W, int64_t ldw, int64_t M,
                                                                              int N, int K, int64_t tiles_m, int tiles_n,
@@ -89,11 +92,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(con
     constexpr int WAVES_N = BN / WN;
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int ROWS_PER_PASS = NT / 8;
-    constexpr int A_PASSES = BM / ROWS_PER_PASS, W_PASSES = BN / ROWS_PER_PASS;
+    constexpr int RPP = NT / 8;  // tile rows covered by one pass of all threads (8 threads per 128-byte row)
+    constexpr int A_PASSES = BM / RPP, W_PASSES = BN / RPP;
     constexpr int STAGE_CHUNKS = (BM + BN) * 8;
-    static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile/threads mismatch");
-    extern __shared__ uint4 smem[];
+    static_assert(BM % RPP == 0 && BN % RPP == 0, "tile/threads mismatch");
+    extern __shared__ bf16x8 smem[];  // native vectors: arrays of them stay in registers
 
     // XCD-aware order: consecutive workgroup ids land on different XCDs (each with
     // its own L2), so give every XCD a contiguous range of tiles; inside the range
@@ -109,40 +112,27 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(con
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int lc = tid % 8, lr = tid / 8;
 
-    const bf16 *a_ptr[A_PASSES];
-    const bf16 *w_ptr[W_PASSES];
+    // global source of this thread's chunks (rows past the end re-read the last row; never stored)
+    const bf16 *a_src[A_PASSES];
+    const bf16 *w_src[W_PASSES];
 #pragma unroll
     for (int i = 0; i < A_PASSES; i++) {
-        int64_t r = m0 + lr + i * ROWS_PER_PASS;
-        if (r > M - 1) r = M - 1;
-        a_ptr[i] = A + r * lda + lc * 8;
+        int64_t r = m0 + lr + i * RPP;
+        a_src[i] = A + (r < M ? r : M - 1) * lda + lc * 8;
     }
 #pragma unroll
     for (int i = 0; i < W_PASSES; i++) {
-        int64_t r = (int64_t)n0 + lr + i * ROWS_PER_PASS;
-        if (r > N - 1) r = N - 1;
-        w_ptr[i] = W + r * ldw + lc * 8;
+        int64_t r = (int64_t)n0 + lr + i * RPP;
+        w_src[i] = W + (r < N ? r : N - 1) * ldw + lc * 8;
     }
-    uint4 a_reg[A_PASSES], w_reg[W_PASSES];
-    auto load_global = [&](int k0) {
+    // LDS slot of this thread's chunks (same for every stage): row r, chunk lc ^ (r & 7); RPP is a multiple of 8
+    const int st_slot = lr * 8 + (lc ^ (lr & 7));
+
+    bf16x8 a_reg[A_PASSES], w_reg[W_PASSES];
 #pragma unroll
-        for (int i = 0; i < A_PASSES; i++) a_reg[i] = *(const uint4 *)(a_ptr[i] + k0);
+    for (int i = 0; i < A_PASSES; i++) a_reg[i] = *(const bf16x8 *)(a_src[i]);
 #pragma unroll
-        for (int i = 0; i < W_PASSES; i++) w_reg[i] = *(const uint4 *)(w_ptr[i] + k0);
-    };
-    auto store_lds = [&](int stage) {
-        uint4 *sa = smem + stage * STAGE_CHUNKS, *sw = sa + BM * 8;
-#pragma unroll
-        for (int i = 0; i < A_PASSES; i++) {
-            int r = lr + i * ROWS_PER_PASS;
-            sa[r * 8 + (lc ^ (r & 7))] = a_reg[i];
-        }
-#pragma unroll
-        for (int i = 0; i < W_PASSES; i++) {
-            int r = lr + i * ROWS_PER_PASS;
-            sw[r * 8 + (lc ^ (r & 7))] = w_reg[i];
-        }
-    };
+    for (int i = 0; i < W_PASSES; i++) w_reg[i] = *(const bf16x8 *)(w_src[i]);
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -152,58 +142,111 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(con
 #pragma unroll
             for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
 
-    const int KT = K / 64;
-    load_global(0);
-    store_lds(0);
+    {
+        bf16x8 *sa = smem, *sw = smem + BM * 8;
+#pragma unroll
+        for (int i = 0; i < A_PASSES; i++) sa[st_slot + i * RPP * 8] = a_reg[i];
+#pragma unroll
+        for (int i = 0; i < W_PASSES; i++) sw[st_slot + i * RPP * 8] = w_reg[i];
+    }
     __syncthreads();
+
     const int frow = lane % 32, fhalf = lane / 32;
+    // fragment read slots: row r = base + frow, chunk (2*kk + fhalf) ^ (r & 7); tile bases are multiples of 32
+    int a_slot[TM], w_slot[TN];
+#pragma unroll
+    for (int i = 0; i < TM; i++) a_slot[i] = (wm * WM + i * 32 + frow) * 8;
+#pragma unroll
+    for (int j = 0; j < TN; j++) w_slot[j] = (BM + wn * WN + j * 32 + frow) * 8;
+    const int fx = frow & 7;
+
+    const int KT = K / 64;
     for (int kt = 0; kt < KT; kt++) {
-        if (kt + 1 < KT) load_global((kt + 1) * 64);
-        const uint4 *sa = smem + (kt & 1) * STAGE_CHUNKS, *sw = sa + BM * 8;
+        const bool more = kt + 1 < KT;
+        if (more) {
+            const int k0 = (kt + 1) * 64;
+#pragma unroll
+            for (int i = 0; i < A_PASSES; i++) a_reg[i] = *(const bf16x8 *)(a_src[i] + k0);
+#pragma unroll
+            for (int i = 0; i < W_PASSES; i++) w_reg[i] = *(const bf16x8 *)(w_src[i] + k0);
+        }
+        const bf16x8 *s = smem + (kt & 1) * STAGE_CHUNKS;
 #pragma unroll
         for (int kk = 0; kk < 4; kk++) {
+            const int ch = (2 * kk + fhalf) ^ fx;
             bf16x8 af[TM], wf[TN];
 #pragma unroll
             for (int i = 0; i < TM; i++) {
-                int r = wm * WM + i * 32 + frow;
-                uint4 t = sa[r * 8 + ((2 * kk + fhalf) ^ (r & 7))];
-                af[i] = *(bf16x8 *)&t;
+                af[i] = s[a_slot[i] + ch];
             }
 #pragma unroll
             for (int j = 0; j < TN; j++) {
-                int r = wn * WN + j * 32 + frow;
-                uint4 t = sw[r * 8 + ((2 * kk + fhalf) ^ (r & 7))];
-                wf[j] = *(bf16x8 *)&t;
+                wf[j] = s[w_slot[j] + ch];
             }
 #pragma unroll
             for (int i = 0; i < TM; i++)
 #pragma unroll
                 for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < KT) store_lds((kt + 1) & 1);
+        if (more) {
+            bf16x8 *sa = smem + ((kt + 1) & 1) * STAGE_CHUNKS, *sw = sa + BM * 8;
+#pragma unroll
+            for (int i = 0; i < A_PASSES; i++) sa[st_slot + i * RPP * 8] = a_reg[i];
+#pragma unroll
+            for (int i = 0; i < W_PASSES; i++) sw[st_slot + i * RPP * 8] = w_reg[i];
+        }
         __syncthreads();
     }
 
-    // accumulator layout of the 32x32 MFMA: lane -> column lane%32, register v -> row 8*(v/4) + 4*(lane/32) + v%4
+    // Accumulator layout of the 32x32 MFMA: lane -> column lane%32, register v -> row 8*(v/4) + 4*(lane/32) + v%4.
+    // For one register the 32 lanes of a half-wave write 32 consecutive columns of one row.
+    const int64_t row_base = m0 + wm * WM + 4 * fhalf;
+    const int col_base = n0 + wn * WN + frow;
 #pragma unroll
     for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int j = 0; j < TN; j++) {
-            int col = n0 + wn * WN + j * 32 + frow;
+            const int col = col_base + j * 32;
+            if (col >= N) continue;
+            const float bias = (KIND == EPI_F32 && epi.bias) ? epi.bias[col] : 0.0f;
 #pragma unroll
             for (int v = 0; v < 16; v++) {
-                int64_t row = m0 + wm * WM + i * 32 + 8 * (v / 4) + 4 * fhalf + (v % 4);
-                if (row < M && col < N) epilogue_store<bf16>(epi, row, col, N, acc[i][j][v]);
+                const int64_t row = row_base + i * 32 + 8 * (v / 4) + (v % 4);
+                if (row >= M) continue;
+                float x = acc[i][j][v];
+                if (KIND == EPI_STORE) {
+                    ((bf16 *)epi.C)[row * epi.ldc + col] = (bf16)x;
+                } else if (KIND == EPI_SILU) {
+                    ((bf16 *)epi.C)[row * epi.ldc + col] = (bf16)(x / (1.0f + __expf(-x)));
+                } else if (KIND == EPI_F32) {
+                    ((float *)epi.C)[row * epi.ldc + col] = x + bias;
+                } else if (KIND == EPI_F32_RESID) {
+                    ((float *)epi.C)[row * epi.ldc + col] = x + epi.resid[row * epi.ldr + col];
+                } else {
+                    const int64_t tr = epi.tok ? (int64_t)epi.tok[row] : 0;
+                    ((float *)epi.C)[row * epi.ldc + col] = x + epi.table[tr * N + col];
+                }
             }
         }
 }
 
-template <int BM, int BN, int WM, int WN>
-static int launch_mfma(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, int64_t M, int N, int K, const GemmEpilogue &epi,
-                       hipStream_t st) {
+// Which fused epilogues the MFMA kernel covers; anything else runs on the plain kernel.
+static int epilogue_kind(const GemmEpilogue &e) {
+    const bool extra = e.bias || e.table || e.resid || e.act != ACT_NONE;
+    if (!e.out_f32 && !extra) return EPI_STORE;
+    if (!e.out_f32 && e.act == ACT_SILU && !e.bias && !e.table && !e.resid) return EPI_SILU;
+    if (e.out_f32 && !e.table && !e.resid && e.act == ACT_NONE) return EPI_F32;
+    if (e.out_f32 && e.resid && !e.bias && !e.table && e.act == ACT_NONE) return EPI_F32_RESID;
+    if (e.out_f32 && e.table && !e.bias && !e.resid && e.act == ACT_NONE) return EPI_F32_TABLE;
+    return -1;
+}
+
+template <int BM, int BN, int WM, int WN, int KIND>
+static int launch_mfma_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, int64_t M, int N, int K, const GemmEpilogue &epi,
+                            hipStream_t st) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     constexpr size_t smem = 2 * (size_t)(BM + BN) * 128;
-    auto kern = gemm_bf16_mfma<BM, BN, WM, WN>;
+    auto kern = gemm_bf16_mfma<BM, BN, WM, WN, KIND>;
     static bool attr_done = false;  // one attribute call per instantiation is enough (value never changes)
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) return GR4AD_EHIP;
@@ -222,7 +265,20 @@ static int launch_mfma(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, i
     return GR4AD_OK;
 }
 
-static int g_gemm_mode = -1;  // 0 auto, 1 force plain FMA kernel, 2 force 128x128 MFMA tiles, 3 force 256x256 (8 waves)
+template <int BM, int BN, int WM, int WN>
+static int launch_mfma(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, int64_t M, int N, int K, int kind, const GemmEpilogue &epi,
+                       hipStream_t st) {
+    switch (kind) {
+        case EPI_STORE: return launch_mfma_kind<BM, BN, WM, WN, EPI_STORE>(A, lda, W, ldw, M, N, K, epi, st);
+        case EPI_SILU: return launch_mfma_kind<BM, BN, WM, WN, EPI_SILU>(A, lda, W, ldw, M, N, K, epi, st);
+        case EPI_F32: return launch_mfma_kind<BM, BN, WM, WN, EPI_F32>(A, lda, W, ldw, M, N, K, epi, st);
+        case EPI_F32_RESID: return launch_mfma_kind<BM, BN, WM, WN, EPI_F32_RESID>(A, lda, W, ldw, M, N, K, epi, st);
+        default: return launch_mfma_kind<BM, BN, WM, WN, EPI_F32_TABLE>(A, lda, W, ldw, M, N, K, epi, st);
+    }
+}
+
+// 0 auto, 1 plain FMA kernel, 2 128x128 tiles, 3 256x256 tiles with 8 wavefronts, 4 256x256 tiles with 4 wavefronts
+static int g_gemm_mode = -1;
 static int gemm_mode() {
     if (g_gemm_mode < 0) {
         const char *e = getenv("GR4AD_GEMM_MODE");
@@ -235,12 +291,14 @@ int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, in
                 const GemmEpilogue &epi, hipStream_t st) {
     if (M <= 0 || N <= 0 || K <= 0) return GR4AD_EINVAL;
     const int mode = gemm_mode();
-    if (dtype == GR4AD_BF16 && mode != 1 && K % 64 == 0 && lda % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)A % 16) == 0 &&
+    const int kind = epilogue_kind(epi);
+    if (dtype == GR4AD_BF16 && mode != 1 && kind >= 0 && K % 64 == 0 && lda % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)A % 16) == 0 &&
         ((uintptr_t)W % 16) == 0) {
+        const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
         const bool big = (M >= 8192 && N >= 256);
-        if ((mode == 0 && big) || mode == 3)
-            return launch_mfma<256, 256, 128, 64>((const bf16 *)A, lda, (const bf16 *)W, ldw, M, N, K, epi, st);
-        return launch_mfma<128, 128, 64, 64>((const bf16 *)A, lda, (const bf16 *)W, ldw, M, N, K, epi, st);
+        if (mode == 4) return launch_mfma<256, 256, 128, 128>(a, lda, w, ldw, M, N, K, kind, epi, st);
+        if ((mode == 0 && big) || mode == 3) return launch_mfma<256, 256, 128, 64>(a, lda, w, ldw, M, N, K, kind, epi, st);
+        return launch_mfma<128, 128, 64, 64>(a, lda, w, ldw, M, N, K, kind, epi, st);
     }
     dim3 grid((unsigned)ceil_div64(M, 64), (unsigned)((N + 63) / 64));
     if (ceil_div64(M, 64) > 0x7fffffffLL || grid.y > 65535) return GR4AD_EUNSUPPORTED;
