@@ -160,10 +160,10 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
             const int id = tid + i * NTH;
             if (id < K_CHUNKS) {
                 const int r = id / KCH, c = id % KCH;
-                sk[r * KCH + (c ^ ((KCH == 8 ? r : (r >> 1)) & (KCH - 1)))] = stage_reg[i];
+                sk[r * KCH + (c ^ ((KCH == 8 ? (r >> 1) : (r >> 2)) & (KCH - 1)))] = stage_reg[i];
             } else if (id < STAGE) {
                 const int v = id - K_CHUNKS, r = v / 8, c = v % 8;
-                sv[r * 8 + (c ^ (r & 7))] = stage_reg[i];
+                sv[r * 8 + (c ^ ((r >> 1) & 7))] = stage_reg[i];
             }
         }
     };
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
             const int r = sub * 32 + krow;
 #pragma unroll
             for (int st = 0; st < KSTEPS; st++) {
-                const bf16x8 kf = sk[r * KCH + ((2 * st + hf) ^ ((KCH == 8 ? r : (r >> 1)) & (KCH - 1)))];
+                const bf16x8 kf = sk[r * KCH + ((2 * st + hf) ^ ((KCH == 8 ? (r >> 1) : (r >> 2)) & (KCH - 1)))];
 #pragma unroll
                 for (int qt = 0; qt < QT; qt++) s[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][st], s[qt][sub], 0, 0, 0);
             }
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
 #pragma unroll
             for (int mt = 0; mt < MT; mt++) {
                 const int r = mt * 32 + frow;
-                const bf16x8 vf = sv[r * 8 + ((2 * ks + hf) ^ (r & 7))];
+                const bf16x8 vf = sv[r * 8 + ((2 * ks + hf) ^ ((r >> 1) & 7))];
 #pragma unroll
                 for (int qt = 0; qt < QT; qt++) o[qt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][ks], o[qt][mt], 0, 0, 0);
             }
@@ -338,45 +338,75 @@ int launch_cross_attention(gr4ad_dtype dtype, const void *q, int64_t ldq, const 
 // ---------------------------------------------------------------------------
 // qkv [rows,3d]; cache [rows][T][2d] (keys then values per position); the new
 // position's k,v are appended at `pos` and the query attends to 0..pos.
+// One thread owns 8 consecutive channels of one row (16-byte accesses in bf16); the
+// dh/8 threads of a head are neighbouring lanes and join their partial dot products
+// with xor-shuffles, so every access of a wavefront is one contiguous stretch.
+template <typename T> struct Chunk8;
+template <> struct Chunk8<bf16> {
+    static __device__ __forceinline__ void load(const bf16 *p, float *o) {
+        const bf16x8 v = *(const bf16x8 *)p;
+#pragma unroll
+        for (int i = 0; i < 8; i++) o[i] = (float)v[i];
+    }
+    static __device__ __forceinline__ void store(bf16 *p, const float *o) {
+        bf16x8 v;
+#pragma unroll
+        for (int i = 0; i < 8; i++) v[i] = (bf16)o[i];
+        *(bf16x8 *)p = v;
+    }
+};
+template <> struct Chunk8<float> {
+    static __device__ __forceinline__ void load(const float *p, float *o) {
+        const floatx4 a = *(const floatx4 *)p, b = *(const floatx4 *)(p + 4);
+#pragma unroll
+        for (int i = 0; i < 4; i++) { o[i] = a[i]; o[4 + i] = b[i]; }
+    }
+    static __device__ __forceinline__ void store(float *p, const float *o) {
+        floatx4 a, b;
+#pragma unroll
+        for (int i = 0; i < 4; i++) { a[i] = o[i]; b[i] = o[4 + i]; }
+        *(floatx4 *)p = a;
+        *(floatx4 *)(p + 4) = b;
+    }
+};
+
 template <typename T>
 __global__ __launch_bounds__(256) void self_attn_step(const T *__restrict__ qkv, T *__restrict__ cache, T *__restrict__ out,
                                                       int64_t rows, int pos, int Tlev, int d, int H) {
-    const int lane = threadIdx.x % 64, wv = threadIdx.x / 64;
-    const int64_t wid = (int64_t)blockIdx.x * 4 + wv;
-    if (wid >= rows * H) return;
-    const int64_t row = wid / H;
-    const int h = (int)(wid % H);
-    const int dh = d / H;
-    const float scale = 1.0f / sqrtf((float)dh);
-    const T *qr = qkv + row * 3 * d + h * dh;
-    T *cr = cache + row * (int64_t)Tlev * 2 * d + h * dh;
-    float qv[2], kn[2], vn[2];
-#pragma unroll
-    for (int e = 0; e < 2; e++) {
-        const int c = lane + 64 * e;
-        const bool ok = c < dh;
-        qv[e] = ok ? to_f(qr[c]) : 0.0f;
-        T kt = ok ? qr[d + c] : from_f<T>(0.0f), vt = ok ? qr[2 * d + c] : from_f<T>(0.0f);
-        kn[e] = to_f(kt);
-        vn[e] = to_f(vt);
-        if (ok) {
-            cr[(int64_t)pos * 2 * d + c] = kt;
-            cr[(int64_t)pos * 2 * d + d + c] = vt;
-        }
+    const int cpr = d / 8;        // chunks per row
+    const int lph = (d / H) / 8;  // lanes per head: 2, 4, 8 or 16
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool live = gid < rows * cpr;
+    const int64_t row = live ? gid / cpr : rows - 1;  // idle lanes shadow the last row and store nothing
+    const int ch = live ? (int)(gid % cpr) : 0;
+    const float scale = 1.0f / sqrtf((float)(d / H));
+    const T *qr = qkv + row * 3 * d + ch * 8;
+    T *cr = cache + row * (int64_t)Tlev * 2 * d + ch * 8;
+    float qv[8], kn[8], vn[8];
+    Chunk8<T>::load(qr, qv);
+    Chunk8<T>::load(qr + d, kn);
+    Chunk8<T>::load(qr + 2 * d, vn);
+    if (live) {
+        Chunk8<T>::store(cr + (int64_t)pos * 2 * d, kn);
+        Chunk8<T>::store(cr + (int64_t)pos * 2 * d + d, vn);
     }
     float s[GR4AD_MAX_LEVELS];
     float mx = -INFINITY;
 #pragma unroll
     for (int p = 0; p < GR4AD_MAX_LEVELS; p++) {
         if (p <= pos) {
+            float kk[8];
+            if (p == pos) {
+#pragma unroll
+                for (int i = 0; i < 8; i++) kk[i] = kn[i];
+            } else {
+                Chunk8<T>::load(cr + (int64_t)p * 2 * d, kk);
+            }
             float part = 0.0f;
 #pragma unroll
-            for (int e = 0; e < 2; e++) {
-                const int c = lane + 64 * e;
-                float kk = (p == pos) ? kn[e] : (c < dh ? to_f(cr[(int64_t)p * 2 * d + c]) : 0.0f);
-                part = fmaf(qv[e], kk, part);
-            }
-            s[p] = wave_sum(part) * scale;
+            for (int i = 0; i < 8; i++) part = fmaf(qv[i], kk[i], part);
+            for (int o = 1; o < lph; o <<= 1) part += __shfl_xor(part, o, 64);
+            s[p] = part * scale;
             mx = fmaxf(mx, s[p]);
         }
     }
@@ -385,30 +415,32 @@ __global__ __launch_bounds__(256) void self_attn_step(const T *__restrict__ qkv,
     for (int p = 0; p < GR4AD_MAX_LEVELS; p++)
         if (p <= pos) { s[p] = __expf(s[p] - mx); den += s[p]; }
     const float inv = 1.0f / den;
-    float o[2] = {0.0f, 0.0f};
+    float o8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int p = 0; p < GR4AD_MAX_LEVELS; p++) {
         if (p <= pos) {
+            float vv[8];
+            if (p == pos) {
 #pragma unroll
-            for (int e = 0; e < 2; e++) {
-                const int c = lane + 64 * e;
-                float vv = (p == pos) ? vn[e] : (c < dh ? to_f(cr[(int64_t)p * 2 * d + d + c]) : 0.0f);
-                o[e] = fmaf(s[p] * inv, vv, o[e]);
+                for (int i = 0; i < 8; i++) vv[i] = vn[i];
+            } else {
+                Chunk8<T>::load(cr + (int64_t)p * 2 * d + d, vv);
             }
+            const float w = s[p] * inv;
+#pragma unroll
+            for (int i = 0; i < 8; i++) o8[i] = fmaf(w, vv[i], o8[i]);
         }
     }
-#pragma unroll
-    for (int e = 0; e < 2; e++) {
-        const int c = lane + 64 * e;
-        if (c < dh) out[row * d + h * dh + c] = from_f<T>(o[e]);
-    }
+    if (live) Chunk8<T>::store(out + row * d + ch * 8, o8);
 }
 
 int launch_self_attention_step(gr4ad_dtype dtype, const void *qkv, void *cache, void *out, int64_t rows, int pos, int T, int d, int H,
                                hipStream_t st) {
     if (rows <= 0 || pos < 0 || pos >= T || T > GR4AD_MAX_LEVELS || d % H) return GR4AD_EINVAL;
-    if (d / H > 128) return GR4AD_EUNSUPPORTED;
-    const int64_t grid = ceil_div64(rows * H, 4);
+    const int dh = d / H;
+    if (dh != 16 && dh != 32 && dh != 64 && dh != 128) return GR4AD_EUNSUPPORTED;
+    if (((uintptr_t)qkv % 32) || ((uintptr_t)cache % 32) || ((uintptr_t)out % 32)) return GR4AD_EUNSUPPORTED;
+    const int64_t grid = ceil_div64(rows * (d / 8), 256);
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
     ProfScope ps(KC_SELF_STEP, st);
     if (dtype == GR4AD_BF16)

@@ -79,8 +79,9 @@ __global__ __launch_bounds__(256) void gemm_simple(const T *__restrict__ A, int6
 // ---------------------------------------------------------------------------
 // Block tile BM x BN, wave tile WM x WN, BK = 64 (one 128-byte row of bf16 per
 // tile row = 8 chunks of 16 bytes).  LDS holds two stages of (BM + BN) rows.
-// Chunk c of row r sits at slot c ^ (r & 7), so the rows a wave touches in one
-// fragment read are spread over all banks.  The next K tile travels
+// Chunk c of row r sits at slot c ^ ((r >> 1) & 7): the LDS serves 16 lanes x 16 bytes
+// per cycle from 64 banks, and the 16 rows such a group of lanes reads (or the 2 rows it
+// writes) then fall on 16 different 16-byte slots.  The next K tile travels
 // global -> registers while the current one is multiplied, then registers -> LDS.
 enum { EPI_STORE = 0, EPI_SILU, EPI_F32, EPI_F32_RESID, EPI_F32_TABLE };
 
@@ -125,8 +126,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(con
         int64_t r = (int64_t)n0 + lr + i * RPP;
         w_src[i] = W + (r < N ? r : N - 1) * ldw + lc * 8;
     }
-    // LDS slot of this thread's chunks (same for every stage): row r, chunk lc ^ (r & 7); RPP is a multiple of 8
-    const int st_slot = lr * 8 + (lc ^ (lr & 7));
+    // LDS slot of this thread's chunks (same for every stage): row r, chunk lc ^ ((r >> 1) & 7); RPP is a multiple of 16
+    const int st_slot = lr * 8 + (lc ^ ((lr >> 1) & 7));
 
     bf16x8 a_reg[A_PASSES], w_reg[W_PASSES];
 #pragma unroll
@@ -152,13 +153,13 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(con
     __syncthreads();
 
     const int frow = lane % 32, fhalf = lane / 32;
-    // fragment read slots: row r = base + frow, chunk (2*kk + fhalf) ^ (r & 7); tile bases are multiples of 32
+    // fragment read slots: row r = base + frow, chunk (2*kk + fhalf) ^ ((r >> 1) & 7); tile bases are multiples of 32
     int a_slot[TM], w_slot[TN];
 #pragma unroll
     for (int i = 0; i < TM; i++) a_slot[i] = (wm * WM + i * 32 + frow) * 8;
 #pragma unroll
     for (int j = 0; j < TN; j++) w_slot[j] = (BM + wn * WN + j * 32 + frow) * 8;
-    const int fx = frow & 7;
+    const int fx = (frow >> 1) & 7;
 
     const int KT = K / 64;
     for (int kt = 0; kt < KT; kt++) {

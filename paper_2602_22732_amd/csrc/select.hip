@@ -42,93 +42,252 @@ __device__ __forceinline__ int block_scan_256(int v, int *wave_tot /*[4] LDS*/) 
 // ---------------------------------------------------------------------------
 // stage A: one workgroup per beam row
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void select_rows(const float *__restrict__ logits, const float *__restrict__ cum, int n, int V, int m,
-                                                   unsigned long long *__restrict__ cand) {
-    extern __shared__ uint32_t skey[];  // [V] logits, then keys
-    __shared__ float red[4];
-    __shared__ int hist[256];
-    __shared__ int wave_tot[4];
-    __shared__ int sel_digit, sel_krem, sel_cnt, out_gt, out_eq;
+// The row (V logits) is read once and stays in registers: ITEMS values per thread,
+// token v = j*256 + tid.  After the log-sum-exp, the row's min(b_t, V_t) best scores
+// are cut out with about two dozen vector operations per logit, so the kernel stays
+// bound by the HBM read of the logits:
+//   1. a histogram of the scores over ROW_BINS equal-width bins between the row's
+//      minimum and maximum (LDS atomics, spread over the bins by the values themselves),
+//   2. a scan from the top bin finds the bin T that holds the m-th best score,
+//   3. everything above bin T is a candidate; the few scores inside bin T are ranked
+//      exactly against each other (64-bit keys, so ties go to the lowest token).
+// If bin T is crowded (degenerate rows, e.g. all logits equal) the row falls back to an
+// exact radix selection on the score keys that walks two bits at a time and only counts.
+#define ROW_BINS 1024
+#define ROW_LIST 1024
+
+struct RowShared {
+    float f[3][4];
+    uint32_t u[2][4][2];
+    int wave_tot[4];
+    int scan_base, out_gt, out_eq, sel_bin, sel_krem, sel_cnt, list_n;
+    int hist[ROW_BINS];
+    unsigned long long list[ROW_LIST];
+};
+
+__device__ __forceinline__ float block_max_256(float v, RowShared &sh, int slot) {
+    v = wave_max(v);
+    if (threadIdx.x % 64 == 0) sh.f[slot][threadIdx.x / 64] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(sh.f[slot][0], sh.f[slot][1]), fmaxf(sh.f[slot][2], sh.f[slot][3]));
+}
+__device__ __forceinline__ float block_sum_256(float v, RowShared &sh, int slot) {
+    v = wave_sum(v);
+    if (threadIdx.x % 64 == 0) sh.f[slot][threadIdx.x / 64] = v;
+    __syncthreads();
+    return (sh.f[slot][0] + sh.f[slot][1]) + (sh.f[slot][2] + sh.f[slot][3]);
+}
+
+__device__ __forceinline__ unsigned long long pack_candidate(float score, uint32_t flat) {
+    return ((unsigned long long)score_key(score) << 32) | (0xFFFFFFFFu - flat);
+}
+
+// Exact fallback: radix selection on the order-preserving keys of the scores held in
+// sc[] (padding slots hold -inf and are skipped by the v < V test).
+template <int ITEMS>
+__device__ __noinline__ void select_row_radix(const float (&sc)[ITEMS], int V, int m, uint32_t flat0, unsigned long long *dst,
+                                              RowShared &sh) {
     const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
-    const int64_t row = blockIdx.x;
-    const float *z = logits + row * (int64_t)V;
-    float *sz = (float *)skey;
-    const float c = cum ? cum[row] : 0.0f;
-
-    float mx = -INFINITY;
-    for (int v = tid; v < V; v += 256) {
-        float x = z[v];
-        sz[v] = x;
-        mx = fmaxf(mx, x);
+    uint32_t k_and = 0xFFFFFFFFu, k_or = 0u;
+#pragma unroll
+    for (int j = 0; j < ITEMS; j++)
+        if (j * 256 + tid < V) { const uint32_t k = score_key(sc[j]); k_and &= k; k_or |= k; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        k_and &= __shfl_xor(k_and, o, 64);
+        k_or |= __shfl_xor(k_or, o, 64);
     }
-    mx = wave_max(mx);
-    if (lane == 0) red[wv] = mx;
     __syncthreads();
-    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    if (lane == 0) { sh.u[0][wv][0] = k_and; sh.u[0][wv][1] = k_or; }
+    if (tid == 0) { sh.out_gt = 0; sh.out_eq = 0; }
     __syncthreads();
-    float sum = 0.0f;
-    for (int v = tid; v < V; v += 256) sum += __expf(sz[v] - mx);
-    sum = wave_sum(sum);
-    if (lane == 0) red[wv] = sum;
-    __syncthreads();
-    const float lse = mx + __logf((red[0] + red[1]) + (red[2] + red[3]));
-    for (int v = tid; v < V; v += 256) skey[v] = score_key(c + (sz[v] - lse));  // each thread rewrites only its own slots
-    if (tid == 0) { sel_krem = m; out_gt = 0; }
-    __syncthreads();
-
-    // radix select of the m-th largest key: 4 passes of 8 bits, most significant first
-    uint32_t prefix = 0;
-    int krem = m, cnt_eq = V;
-    if (m < V) {
-        for (int pass = 0; pass < 4; pass++) {
-            const int shift = 24 - 8 * pass;
-            hist[tid] = 0;
-            __syncthreads();
-            for (int v = tid; v < V; v += 256) {
-                uint32_t k = skey[v];
-                if (pass == 0 || (k >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(k >> shift) & 255], 1);
+    k_and = sh.u[0][0][0] & sh.u[0][1][0] & sh.u[0][2][0] & sh.u[0][3][0];
+    k_or = sh.u[0][0][1] | sh.u[0][1][1] | sh.u[0][2][1] | sh.u[0][3][1];
+    // decided: bits already fixed in `prefix`; a key is still active while (key & decided) == prefix
+    const uint32_t diff = k_and ^ k_or;
+    uint32_t decided = 0xFFFFFFFFu, prefix = k_and;
+    int krem = m, active = V;
+    if (diff != 0) {
+        const int top = 31 - __clz(diff);
+        decided = ~((2u << top) - 1u);  // top == 31 gives 0
+        prefix = k_and & decided;
+        int slot = 1;
+        for (int shb = top & ~1; shb >= 0; shb -= 2) {
+            uint32_t c12 = 0, c3 = 0;  // active keys with digit >= 1 (low half), >= 2 (high half), >= 3
+#pragma unroll
+            for (int j = 0; j < ITEMS; j++) {
+                const uint32_t k = score_key(sc[j]);
+                const uint32_t d = (k >> shb) & 3u;
+                const uint32_t act = (((k ^ prefix) & decided) == 0u && (j * 256 + tid) < V) ? 1u : 0u;
+                c12 += (d >= 1u ? act : 0u) + (d >= 2u ? (act << 16) : 0u);
+                c3 += d >= 3u ? act : 0u;
             }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                c12 += __shfl_xor(c12, o, 64);
+                c3 += __shfl_xor(c3, o, 64);
+            }
+            if (lane == 0) { sh.u[slot][wv][0] = c12; sh.u[slot][wv][1] = c3; }
             __syncthreads();
-            const int own = hist[255 - tid];  // thread t owns digit 255-t: scan runs from the top digit down
-            const int incl = block_scan_256(own, wave_tot);
-            if (incl >= krem && incl - own < krem) { sel_digit = 255 - tid; sel_krem = krem - (incl - own); sel_cnt = own; }
-            __syncthreads();
-            prefix |= (uint32_t)sel_digit << shift;
-            krem = sel_krem;
-            cnt_eq = sel_cnt;
-            __syncthreads();
+            c12 = sh.u[slot][0][0] + sh.u[slot][1][0] + sh.u[slot][2][0] + sh.u[slot][3][0];
+            c3 = sh.u[slot][0][1] + sh.u[slot][1][1] + sh.u[slot][2][1] + sh.u[slot][3][1];
+            slot ^= 1;  // the next step writes the other slot, so one barrier per step is enough
+            const int C1 = (int)(c12 & 0xFFFFu), C2 = (int)(c12 >> 16), C3 = (int)c3;
+            uint32_t dsel;
+            if (C3 >= krem) { dsel = 3; active = C3; }
+            else if (C2 >= krem) { dsel = 2; krem -= C3; active = C2 - C3; }
+            else if (C1 >= krem) { dsel = 1; krem -= C2; active = C1 - C2; }
+            else { dsel = 0; krem -= C1; active = active - C1; }
+            prefix |= dsel << shb;
+            decided |= 3u << shb;
+            if (active == krem) break;  // every key still active is taken
         }
     }
-    // keys > prefix go first (any order), then krem of the cnt_eq keys == prefix, lowest token first
-    unsigned long long *dst = cand + row * (int64_t)m;
-    const uint32_t flat0 = (uint32_t)((row % n) * (int64_t)V);
+    // (key & decided) > prefix: above the threshold; == prefix: `active` keys tie at it, krem of them are taken
     const int n_gt = m - krem;
-    if (tid == 0) out_eq = 0;
-    __syncthreads();
-    if (m >= V || cnt_eq == krem) {
-        for (int v = tid; v < V; v += 256) {
-            uint32_t k = skey[v];
-            if (m >= V || k >= prefix) {
-                int p = (m >= V) ? v : ((k > prefix) ? atomicAdd(&out_gt, 1) : n_gt + atomicAdd(&out_eq, 1));
-                dst[p] = ((unsigned long long)k << 32) | (0xFFFFFFFFu - (flat0 + (uint32_t)v));
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    if (active == krem) {
+#pragma unroll
+        for (int j = 0; j < ITEMS; j++) {
+            const int v = j * 256 + tid;
+            const uint32_t kk = score_key(sc[j]) & decided;
+            const bool gt = v < V && kk > prefix, eq = v < V && kk == prefix;
+            const unsigned long long mg = __ballot(gt), me = __ballot(eq);
+            int bg = 0, be = 0;
+            if (lane == 0) {
+                if (mg) bg = atomicAdd(&sh.out_gt, __popcll(mg));
+                if (me) be = atomicAdd(&sh.out_eq, __popcll(me));
             }
+            bg = __shfl(bg, 0, 64);
+            be = __shfl(be, 0, 64);
+            if (gt) dst[bg + __popcll(mg & lt_mask)] = pack_candidate(sc[j], flat0 + (uint32_t)v);
+            if (eq) dst[n_gt + be + __popcll(me & lt_mask)] = pack_candidate(sc[j], flat0 + (uint32_t)v);
         }
     } else {
-        int base = 0;  // equal keys taken so far, in token order
-        for (int v0 = 0; v0 < V; v0 += 256) {
-            const int v = v0 + tid;
-            const uint32_t k = v < V ? skey[v] : 0u;
-            const int flag = (v < V && k == prefix) ? 1 : 0;
-            const int incl = block_scan_256(flag, wave_tot);
-            if (v < V && k > prefix) dst[atomicAdd(&out_gt, 1)] = ((unsigned long long)k << 32) | (0xFFFFFFFFu - (flat0 + (uint32_t)v));
+        // more keys tie at the threshold than are needed: take the lowest tokens, in token order
+        int base = 0;
+#pragma unroll
+        for (int j = 0; j < ITEMS; j++) {
+            const int v = j * 256 + tid;
+            const uint32_t kk = score_key(sc[j]) & decided;
+            const bool gt = v < V && kk > prefix;
+            const int flag = (v < V && kk == prefix) ? 1 : 0;
+            const int incl = block_scan_256(flag, sh.wave_tot);
+            if (gt) dst[atomicAdd(&sh.out_gt, 1)] = pack_candidate(sc[j], flat0 + (uint32_t)v);
             const int rank = base + incl - flag;
-            if (flag && rank < krem) dst[n_gt + rank] = ((unsigned long long)k << 32) | (0xFFFFFFFFu - (flat0 + (uint32_t)v));
-            if (tid == 255) sel_cnt = base + incl;
+            if (flag && rank < krem) dst[n_gt + rank] = pack_candidate(sc[j], flat0 + (uint32_t)v);
+            if (tid == 255) sh.scan_base = base + incl;
             __syncthreads();
-            base = sel_cnt;
+            base = sh.scan_base;
             __syncthreads();
         }
     }
+}
+
+template <int ITEMS>
+__global__ __launch_bounds__(256) void select_rows(const float *__restrict__ logits, const float *__restrict__ cum, int n, int V, int m,
+                                                   unsigned long long *__restrict__ cand) {
+    __shared__ RowShared sh;
+    extern __shared__ unsigned long long out_stage[];  // m candidates, gathered here and written out in one coalesced sweep
+    const int tid = threadIdx.x;
+    const int64_t row = blockIdx.x;
+    const float *z = logits + row * (int64_t)V;
+    const float c = cum ? cum[row] : 0.0f;
+    for (int i = tid; i < ROW_BINS; i += 256) sh.hist[i] = 0;
+    if (tid == 0) { sh.out_gt = 0; sh.list_n = 0; }
+
+    float x[ITEMS];
+    float mx = -INFINITY, mn = INFINITY;
+#pragma unroll
+    for (int j = 0; j < ITEMS; j++) {
+        const int v = j * 256 + tid;
+        x[j] = v < V ? z[v] : -INFINITY;
+        mx = fmaxf(mx, x[j]);
+        if (v < V) mn = fminf(mn, x[j]);
+    }
+    mx = block_max_256(mx, sh, 0);
+    mn = -block_max_256(-mn, sh, 1);
+    float sum = 0.0f;
+#pragma unroll
+    for (int j = 0; j < ITEMS; j++) sum += __expf(x[j] - mx);  // exp(-inf) = 0 for the padding
+    const float lse = mx + __logf(block_sum_256(sum, sh, 2));
+#pragma unroll
+    for (int j = 0; j < ITEMS; j++) x[j] = c + (x[j] - lse);  // scores from here on (padding stays -inf)
+
+    unsigned long long *dst = cand + row * (int64_t)m;
+    const uint32_t flat0 = (uint32_t)((row % n) * (int64_t)V);
+    if (m >= V) {  // nothing to cut: every token is a candidate
+#pragma unroll
+        for (int j = 0; j < ITEMS; j++) {
+            const int v = j * 256 + tid;
+            if (v < V) dst[v] = pack_candidate(x[j], flat0 + (uint32_t)v);
+        }
+        return;
+    }
+    // 1. histogram over equal-width bins of [lo, hi]; the bin index is monotone in the score
+    const float lo = c + (mn - lse), hi = c + (mx - lse);
+    const float inv_w = (hi > lo) ? (float)ROW_BINS / (hi - lo) : 0.0f;
+    int bin[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; j++) {
+        int bi = (int)((x[j] - lo) * inv_w);
+        bi = bi < 0 ? 0 : (bi > ROW_BINS - 1 ? ROW_BINS - 1 : bi);
+        bin[j] = bi;
+        if (j * 256 + tid < V) atomicAdd(&sh.hist[bi], 1);
+    }
+    __syncthreads();
+    // 2. thread t owns bins 1023-4t .. 1020-4t; inclusive scan from the top bin down
+    {
+        const int b0 = ROW_BINS - 1 - 4 * tid;
+        const int h0 = sh.hist[b0], h1 = sh.hist[b0 - 1], h2 = sh.hist[b0 - 2], h3 = sh.hist[b0 - 3];
+        const int incl = block_scan_256(h0 + h1 + h2 + h3, sh.wave_tot);
+        int above = incl - (h0 + h1 + h2 + h3);  // scores in bins above this thread's four
+        if (above < m && incl >= m) {
+            int bsel = b0, cnt = h0;
+            if (above + h0 < m) { above += h0; bsel = b0 - 1; cnt = h1;
+                if (above + h1 < m) { above += h1; bsel = b0 - 2; cnt = h2;
+                    if (above + h2 < m) { above += h2; bsel = b0 - 3; cnt = h3; } } }
+            sh.sel_bin = bsel;
+            sh.sel_krem = m - above;
+            sh.sel_cnt = cnt;
+        }
+    }
+    __syncthreads();
+    const int T = sh.sel_bin, krem = sh.sel_krem, cntT = sh.sel_cnt;
+    if (cntT > ROW_LIST) {  // crowded threshold bin: exact radix selection over the whole row
+        float sc[ITEMS];  // a copy, so that only this branch keeps the scores in addressable memory
+#pragma unroll
+        for (int j = 0; j < ITEMS; j++) sc[j] = x[j];
+        select_row_radix<ITEMS>(sc, V, m, flat0, dst, sh);
+        return;
+    }
+    // 3. bins above T are candidates; bin T goes to the list for exact ranking.  One scan of the
+    //    per-thread counts (low half: above T, high half: inside T) gives every thread its slots.
+    const int n_gt = m - krem;
+    int mine = 0;
+#pragma unroll
+    for (int j = 0; j < ITEMS; j++) {
+        const bool ok = j * 256 + tid < V;
+        mine += (ok && bin[j] > T ? 1 : 0) + (ok && bin[j] == T ? (1 << 16) : 0);
+    }
+    const int incl = block_scan_256(mine, sh.wave_tot);
+    int pos_gt = (incl - mine) & 0xFFFF, pos_eq = (incl - mine) >> 16;
+#pragma unroll
+    for (int j = 0; j < ITEMS; j++) {
+        const int v = j * 256 + tid;
+        if (v < V && bin[j] > T) out_stage[pos_gt++] = pack_candidate(x[j], flat0 + (uint32_t)v);
+        if (v < V && bin[j] == T) sh.list[pos_eq++] = pack_candidate(x[j], flat0 + (uint32_t)v);
+    }
+    __syncthreads();
+    // rank every listed candidate among the cntT listed ones; the krem best go out
+    for (int i = tid; i < cntT; i += 256) {
+        const unsigned long long mine = sh.list[i];
+        int rank = 0;
+        for (int q = 0; q < cntT; q++) rank += sh.list[q] > mine ? 1 : 0;
+        if (rank < krem) out_stage[n_gt + rank] = mine;
+    }
+    __syncthreads();
+    for (int i = tid; i < m; i += 256) dst[i] = out_stage[i];
 }
 
 // ---------------------------------------------------------------------------
@@ -257,14 +416,18 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
     const int m = k < V ? k : V;
     const int64_t rows = (int64_t)B * n;
     if (rows > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
-    static bool attr_done = false;  // rows of up to GR4AD_MAX_CODEBOOK floats exceed the default dynamic LDS limit
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void *)select_rows, hipFuncAttributeMaxDynamicSharedMemorySize, GR4AD_MAX_CODEBOOK * 4) != hipSuccess) return GR4AD_EHIP;
-        attr_done = true;
-    }
     {
         ProfScope ps(KC_SELECT_ROWS, st);
-        hipLaunchKernelGGL(select_rows, dim3((unsigned)rows), dim3(256), (size_t)V * 4, st, logits, cum, n, V, m, (unsigned long long *)ws);
+        unsigned long long *cand = (unsigned long long *)ws;
+        const size_t stage_bytes = (size_t)m * sizeof(unsigned long long);  // <= 32 KB (GR4AD_MAX_BEAM)
+        if (V <= 1024)
+            hipLaunchKernelGGL(select_rows<4>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
+        else if (V <= 4096)
+            hipLaunchKernelGGL(select_rows<16>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
+        else if (V <= 8192)
+            hipLaunchKernelGGL(select_rows<32>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
+        else
+            hipLaunchKernelGGL(select_rows<64>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
     }
     GR4AD_LAUNCH_CHECK();
     ProfScope ps(KC_SELECT_REQUEST, st);
