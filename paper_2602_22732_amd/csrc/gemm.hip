@@ -231,6 +231,235 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(con
         }
 }
 
+// ---------------------------------------------------------------------------
+// MFMA kernel with a four-stage LDS pipeline fed by direct global->LDS loads
+// ---------------------------------------------------------------------------
+// 256x256 block tile, 8 wavefronts (wave tile 128x64), BK = 32: a K tile is 512 rows
+// of 64 bytes (4 chunks of 16 bytes; chunk c of row r at slot c ^ ((r >> 2) & 3), which
+// keeps fragment reads conflict-free).  Four stages of 32 KB sit in LDS.  A K tile is
+// fetched by global_load_lds_dwordx4: every lane moves 16 bytes straight into LDS (no
+// staging registers, no ds_write); one wave instruction fills 64 consecutive slots
+// = 16 tile rows, and the swizzle is applied on the global side (which chunk a lane
+// fetches).  Loads run three tiles ahead of the math; the wave waits on its own loads
+// with s_waitcnt vmcnt(n) and the workgroup meets at a bare s_barrier (a full fence
+// would wait for every load in flight).  The first fragments of the next tile are read
+// before the barrier, so the MFMA stream continues across it.
+// After the last tile the stages are reused to transpose the accumulators, so that C
+// leaves in 16-byte pieces along rows (128 or 256 contiguous bytes per row).
+#define PIPE_STAGES 4
+#define PIPE_STAGE_CHUNKS 2048  // 512 rows x 4 chunks
+#define PIPE_LDS_BYTES (8 * 64 * 288)  // epilogue staging (8 waves x 64 rows x 288 B) >= 4 stages x 32 KB
+
+__device__ __forceinline__ void dma16(const bf16 *g, bf16x8 *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)g,
+                                     (void __attribute__((address_space(3))) *)lds_wave_base, 16, 0, 0);
+}
+
+template <int KIND>
+__global__ __launch_bounds__(512) void gemm_bf16_pipe(const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ W, int64_t ldw,
+                                                      int64_t M, int N, int K, int64_t tiles_m, int tiles_n, GemmEpilogue epi) {
+    extern __shared__ bf16x8 smem[];
+    const int64_t total = tiles_m * tiles_n;
+    const int64_t per_xcd = (total + 7) / 8;
+    const int64_t logical = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (logical >= total) return;
+    const int64_t m0 = (logical / tiles_n) * 256;
+    const int n0 = (int)(logical % tiles_n) * 256;
+    const int tid = threadIdx.x, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int wm = wave / 4, wn = wave % 4;  // 2 x 4 waves, wave tile 128 x 64
+    const int frow = lane % 32, fhalf = lane / 32;
+
+    // DMA sources: load j of this wave covers tile rows (wave*4 + j)*16 .. +15, lane -> row + lane/4, slot lane%4
+    const bf16 *src[4];
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        const int r = (wave * 4 + j) * 16 + lane / 4;  // 0..255: A rows, 256..511: W rows
+        const int c = (lane % 4) ^ ((r >> 2) & 3);     // logical chunk that lives in this slot
+        if (r < 256) {
+            int64_t gr = m0 + r;
+            src[j] = A + (gr < M ? gr : M - 1) * lda + c * 8;
+        } else {
+            int64_t gr = (int64_t)n0 + (r - 256);
+            src[j] = W + (gr < N ? gr : N - 1) * ldw + c * 8;
+        }
+    }
+    const int KT = K / 32;
+    auto issue = [&](int kt) {  // tile kt -> stage kt % 4
+        bf16x8 *base = smem + (kt & 3) * PIPE_STAGE_CHUNKS + wave * 256;
+#pragma unroll
+        for (int j = 0; j < 4; j++) dma16(src[j] + (int64_t)kt * 32, base + j * 64);
+    };
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
+
+    // fragment slots inside a stage: row r, k-step kk: chunk (2*kk + fhalf) ^ ((r >> 2) & 3)
+    int a_slot[4], w_slot[2];
+#pragma unroll
+    for (int i = 0; i < 4; i++) a_slot[i] = (wm * 128 + i * 32 + frow) * 4;
+#pragma unroll
+    for (int j = 0; j < 2; j++) w_slot[j] = (256 + wn * 64 + j * 32 + frow) * 4;
+    const int fx = (frow >> 2) & 3;
+    const int ch0 = fhalf ^ fx, ch1 = (2 + fhalf) ^ fx;
+
+    // prologue: three tiles in flight, the first two landed before the first barrier
+    issue(0);
+    if (KT > 1) issue(1);
+    if (KT > 2) issue(2);
+    if (KT > 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    bf16x8 af0[4], wf0[2], af1[4], wf1[2];
+#pragma unroll
+    for (int i = 0; i < 4; i++) af0[i] = smem[a_slot[i] + ch0];
+#pragma unroll
+    for (int j = 0; j < 2; j++) wf0[j] = smem[w_slot[j] + ch0];
+
+    for (int kt = 0; kt < KT; kt++) {
+        const bf16x8 *s = smem + (kt & 3) * PIPE_STAGE_CHUNKS;
+        // first k-step: its fragments were read before the barrier, so the MFMAs start at once
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af0[i], wf0[j], acc[i][j], 0, 0, 0);
+        // while they run: fragments of the second k-step, and the loads of tile kt+3
+#pragma unroll
+        for (int i = 0; i < 4; i++) af1[i] = s[a_slot[i] + ch1];
+#pragma unroll
+        for (int j = 0; j < 2; j++) wf1[j] = s[w_slot[j] + ch1];
+        if (kt + 3 < KT) issue(kt + 3);  // stage of tile kt-1: every wave finished reading it before the last barrier
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i], wf1[j], acc[i][j], 0, 0, 0);
+        if (kt + 1 < KT) {  // tile kt+1 has been visible since the previous barrier
+            const bf16x8 *sn = smem + ((kt + 1) & 3) * PIPE_STAGE_CHUNKS;
+#pragma unroll
+            for (int i = 0; i < 4; i++) af0[i] = sn[a_slot[i] + ch0];
+#pragma unroll
+            for (int j = 0; j < 2; j++) wf0[j] = sn[w_slot[j] + ch0];
+        }
+        // tiles <= kt+2 must have landed before the barrier; only tile kt+3 (4 loads) may stay in flight
+        if (kt + 3 < KT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    }
+
+    // ---- epilogue: accumulators -> this wave's LDS region (row-major, padded) -> 16-byte row pieces ----
+    constexpr bool OUT_F32 = KIND >= EPI_F32;
+    constexpr int PITCH = OUT_F32 ? 288 : 144;        // bytes per staged row of 64 columns
+    constexpr int ROWS_PER_PASS = OUT_F32 ? 64 : 128;  // 18 KB per wave and pass
+    constexpr int PASSES = 128 / ROWS_PER_PASS;
+    constexpr int LANES_PER_ROW = OUT_F32 ? 16 : 8;    // 16-byte pieces per staged row
+    char *stage = (char *)smem + wave * (64 * 288);
+    const int64_t wrow0 = m0 + wm * 128;
+    const int wcol0 = n0 + wn * 64;
+#pragma unroll
+    for (int pass = 0; pass < PASSES; pass++) {
+        // MFMA layout: lane -> column lane%32 of the 32x32 tile, register v -> row 8*(v/4) + 4*(lane/32) + v%4
+#pragma unroll
+        for (int ii = 0; ii < ROWS_PER_PASS / 32; ii++) {
+            const int i = pass * (ROWS_PER_PASS / 32) + ii;
+#pragma unroll
+            for (int j = 0; j < 2; j++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) {
+                    const int r = ii * 32 + 8 * (v / 4) + 4 * fhalf + (v % 4), c = j * 32 + frow;
+                    if (OUT_F32) *(float *)(stage + r * PITCH + c * 4) = acc[i][j][v];
+                    else *(bf16 *)(stage + r * PITCH + c * 2) = (bf16)(KIND == EPI_SILU ? acc[i][j][v] / (1.0f + __expf(-acc[i][j][v])) : acc[i][j][v]);
+                }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // wave-private region: no barrier needed
+#pragma unroll
+        for (int it = 0; it < ROWS_PER_PASS / (64 / LANES_PER_ROW); it++) {
+            const int r = it * (64 / LANES_PER_ROW) + lane / LANES_PER_ROW;
+            const int piece = lane % LANES_PER_ROW;
+            const int64_t row = wrow0 + pass * ROWS_PER_PASS + r;
+            const int col = wcol0 + piece * (OUT_F32 ? 4 : 8);
+            if (row >= M || col >= N) continue;
+            if (OUT_F32) {
+                floatx4 x = *(const floatx4 *)(stage + r * PITCH + piece * 16);
+                if (col + 3 < N) {
+                    floatx4 add = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (KIND == EPI_F32 && epi.bias) add = *(const floatx4 *)(epi.bias + col);
+                    if (KIND == EPI_F32_RESID) add = *(const floatx4 *)(epi.resid + row * epi.ldr + col);
+                    if (KIND == EPI_F32_TABLE) add = *(const floatx4 *)(epi.table + (epi.tok ? (int64_t)epi.tok[row] : 0) * N + col);
+                    *(floatx4 *)((float *)epi.C + row * epi.ldc + col) = x + add;
+                } else {
+                    for (int e = 0; e < 4 && col + e < N; e++) {
+                        float y = x[e];
+                        if (KIND == EPI_F32 && epi.bias) y += epi.bias[col + e];
+                        if (KIND == EPI_F32_RESID) y += epi.resid[row * epi.ldr + col + e];
+                        if (KIND == EPI_F32_TABLE) y += epi.table[(epi.tok ? (int64_t)epi.tok[row] : 0) * N + col + e];
+                        ((float *)epi.C)[row * epi.ldc + col + e] = y;
+                    }
+                }
+            } else {
+                bf16x8 x = *(const bf16x8 *)(stage + r * PITCH + piece * 16);
+                if (col + 7 < N) {
+                    *(bf16x8 *)((bf16 *)epi.C + row * epi.ldc + col) = x;
+                } else {
+                    for (int e = 0; e < 8 && col + e < N; e++) ((bf16 *)epi.C)[row * epi.ldc + col + e] = x[e];
+                }
+            }
+        }
+        if (pass + 1 < PASSES) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
+}
+
+template <int KIND>
+static int launch_pipe_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, int64_t M, int N, int K, const GemmEpilogue &epi,
+                            hipStream_t st) {
+    auto kern = gemm_bf16_pipe<KIND>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, PIPE_LDS_BYTES) != hipSuccess) return GR4AD_EHIP;
+        attr_done = true;
+    }
+    int64_t tiles_m = ceil_div64(M, 256);
+    int tiles_n = (N + 255) / 256;
+    int64_t grid = ceil_div64(tiles_m * tiles_n, 8) * 8;
+    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    {
+        ProfScope ps(KC_GEMM_256, st, 2.0 * (double)M * N * K);
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), PIPE_LDS_BYTES, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, epi);
+    }
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+// The pipelined kernel stores 16-byte pieces: it needs 16-byte aligned rows of C (and of what the epilogue adds).
+static bool pipe_ok(int kind, int N, const GemmEpilogue &e) {
+    const bool f32 = kind >= EPI_F32;
+    if (e.ldc % (f32 ? 4 : 8) || ((uintptr_t)e.C % 16)) return false;
+    if (kind == EPI_F32 && e.bias && ((uintptr_t)e.bias % 16)) return false;
+    if (kind == EPI_F32_RESID && (e.ldr % 4 || ((uintptr_t)e.resid % 16))) return false;
+    if (kind == EPI_F32_TABLE && (N % 4 || ((uintptr_t)e.table % 16))) return false;
+    return true;
+}
+
+static int launch_pipe(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, int64_t M, int N, int K, int kind, const GemmEpilogue &epi,
+                       hipStream_t st) {
+    switch (kind) {
+        case EPI_STORE: return launch_pipe_kind<EPI_STORE>(A, lda, W, ldw, M, N, K, epi, st);
+        case EPI_SILU: return launch_pipe_kind<EPI_SILU>(A, lda, W, ldw, M, N, K, epi, st);
+        case EPI_F32: return launch_pipe_kind<EPI_F32>(A, lda, W, ldw, M, N, K, epi, st);
+        case EPI_F32_RESID: return launch_pipe_kind<EPI_F32_RESID>(A, lda, W, ldw, M, N, K, epi, st);
+        default: return launch_pipe_kind<EPI_F32_TABLE>(A, lda, W, ldw, M, N, K, epi, st);
+    }
+}
+
 // Which fused epilogues the MFMA kernel covers; anything else runs on the plain kernel.
 static int epilogue_kind(const GemmEpilogue &e) {
     const bool extra = e.bias || e.table || e.resid || e.act != ACT_NONE;
@@ -278,7 +507,8 @@ static int launch_mfma(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, i
     }
 }
 
-// 0 auto, 1 plain FMA kernel, 2 128x128 tiles, 3 256x256 tiles with 8 wavefronts, 4 256x256 tiles with 4 wavefronts
+// 0 auto, 1 plain FMA kernel, 2 128x128 tiles, 3 256x256 tiles with 8 wavefronts, 4 256x256 tiles with 4 wavefronts,
+// 5 pipelined 256x256 kernel
 static int g_gemm_mode = -1;
 static int gemm_mode() {
     if (g_gemm_mode < 0) {
@@ -297,6 +527,7 @@ int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, in
         ((uintptr_t)W % 16) == 0) {
         const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
         const bool big = (M >= 8192 && N >= 256);
+        if ((mode == 5 || (mode == 0 && big)) && pipe_ok(kind, N, epi)) return launch_pipe(a, lda, w, ldw, M, N, K, kind, epi, st);
         if (mode == 4) return launch_mfma<256, 256, 128, 128>(a, lda, w, ldw, M, N, K, kind, epi, st);
         if ((mode == 0 && big) || mode == 3) return launch_mfma<256, 256, 128, 64>(a, lda, w, ldw, M, N, K, kind, epi, st);
         return launch_mfma<128, 128, 64, 64>(a, lda, w, ldw, M, N, K, kind, epi, st);
