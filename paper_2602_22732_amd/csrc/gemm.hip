@@ -432,7 +432,7 @@ static int launch_pipe_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
     int64_t grid = ceil_div64(tiles_m * tiles_n, 8) * 8;
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
     {
-        ProfScope ps(KC_GEMM_256, st, 2.0 * (double)M * N * K);
+        ProfScope ps(KC_GEMM_PIPE, st, 2.0 * (double)M * N * K);
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), PIPE_LDS_BYTES, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, epi);
     }
     GR4AD_LAUNCH_CHECK();
