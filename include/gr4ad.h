@@ -193,13 +193,15 @@ int gr4ad_op_gather_rows(gr4ad_dtype dtype, const void *src_dev, const int32_t *
  * the stream the kernel is launched on.  gr4ad_profile_read waits for the
  * recorded events and sums, per kernel class c < gr4ad_profile_kernel_count():
  * elapsed milliseconds ms[c], algorithmic flops flops[c] (2*M*N*K per GEMM
- * launch, 0 for the other kernels) and the number of launches; reset != 0
- * forgets the records afterwards.  Not thread-safe.
+ * launch; 4*n*S*d per request for cross-attention, i.e. counted on the padded
+ * context length S), algorithmic HBM bytes bytes[c] (what the operation must
+ * read and write once: operands, outputs) and the number of launches;
+ * reset != 0 forgets the records afterwards.  Not thread-safe.
  */
 int gr4ad_profile_enable(int on);
 int gr4ad_profile_kernel_count(void);
 const char *gr4ad_profile_kernel_name(int kernel_class);
-int gr4ad_profile_read(double *ms, double *flops, int64_t *launches, int reset);
+int gr4ad_profile_read(double *ms, double *flops, double *bytes, int64_t *launches, int reset);
 
 #ifdef __cplusplus
 }

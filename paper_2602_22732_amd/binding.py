@@ -90,7 +90,7 @@ def lib():
         L.gr4ad_profile_kernel_name.restype = C.c_char_p
         L.gr4ad_profile_kernel_name.argtypes = [C.c_int]
         L.gr4ad_profile_read.restype = C.c_int
-        L.gr4ad_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
+        L.gr4ad_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
         _lib = L
     return _lib
 
@@ -100,12 +100,13 @@ def profile_enable(on):
 
 
 def profile_read(reset=True):
-    """{kernel name: {"ms", "flops", "launches"}} of the launches recorded since the last reset."""
+    """{kernel name: {"ms", "flops", "bytes", "launches"}} of the launches recorded since the last reset."""
     L = lib()
     n = L.gr4ad_profile_kernel_count()
-    ms, fl, cnt = (C.c_double * n)(), (C.c_double * n)(), (C.c_int64 * n)()
-    _check(L.gr4ad_profile_read(ms, fl, cnt, int(reset)))
-    return {L.gr4ad_profile_kernel_name(i).decode(): {"ms": ms[i], "flops": fl[i], "launches": cnt[i]} for i in range(n) if cnt[i]}
+    ms, fl, by, cnt = (C.c_double * n)(), (C.c_double * n)(), (C.c_double * n)(), (C.c_int64 * n)()
+    _check(L.gr4ad_profile_read(ms, fl, by, cnt, int(reset)))
+    return {L.gr4ad_profile_kernel_name(i).decode(): {"ms": ms[i], "flops": fl[i], "bytes": by[i], "launches": cnt[i]}
+            for i in range(n) if cnt[i]}
 
 
 def _check(status, dec=None):

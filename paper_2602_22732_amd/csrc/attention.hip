@@ -283,7 +283,7 @@ int launch_cross_attention_prepare(gr4ad_dtype dtype, const void *kv, const int3
     if (!vt || ((uintptr_t)vt % 16) || ((uintptr_t)kv % 16)) return GR4AD_EWORKSPACE;
     const int Spad = (S + 63) / 64 * 64;
     if (B > 65535 || d / 64 > 65535) return GR4AD_EUNSUPPORTED;
-    ProfScope ps(KC_V_TRANSPOSE, st);
+    ProfScope ps(KC_V_TRANSPOSE, st, 0.0, 2.0 * B * (double)S * d * sizeof(bf16));
     hipLaunchKernelGGL(v_transpose_kernel, dim3(Spad / 64, d / 64, B), dim3(256), 0, st, (const bf16 *)kv, ctx_len, (bf16 *)vt, S, Spad, d);
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
@@ -295,7 +295,8 @@ static int launch_flash(const bf16 *q, int64_t ldq, const bf16 *kv, const bf16 *
     const int per_block = NW * QT * 32;
     dim3 grid((n + per_block - 1) / per_block, H, B);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
-    ProfScope ps(KC_XATTN_FLASH, st);
+    // flops on the padded length S; bytes: queries and outputs once, keys and values once per request (beam-shared)
+    ProfScope ps(KC_XATTN_FLASH, st, 4.0 * B * (double)n * S * d, (2.0 * B * n * d + 2.0 * B * (double)S * d) * sizeof(bf16));
     hipLaunchKernelGGL((cross_attn_flash_bf16<DH, QT, NW>), grid, dim3(NW * 64), 0, st, q, ldq, kv, vt, ctx_len, out, ldo, n, S,
                        (S + 63) / 64 * 64, d, H, scale_log2e);
     GR4AD_LAUNCH_CHECK();
@@ -324,7 +325,7 @@ int launch_cross_attention(gr4ad_dtype dtype, const void *q, int64_t ldq, const 
     const int64_t rows = (int64_t)B * n;
     const int64_t grid = ceil_div64(rows * H, 4);
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
-    ProfScope ps(KC_XATTN_SIMPLE, st);
+    ProfScope ps(KC_XATTN_SIMPLE, st, 4.0 * B * (double)n * S * d, (2.0 * B * n * d + 2.0 * B * (double)S * d) * (dtype == GR4AD_BF16 ? 2 : 4));
     if (dtype == GR4AD_BF16)
         hipLaunchKernelGGL(cross_attn_simple<bf16>, dim3((unsigned)grid), dim3(256), 0, st, (const bf16 *)q, ldq, (const bf16 *)kv, ctx_len, (bf16 *)out, ldo, rows, n, S, d, H);
     else
@@ -442,7 +443,8 @@ int launch_self_attention_step(gr4ad_dtype dtype, const void *qkv, void *cache, 
     if (((uintptr_t)qkv % 32) || ((uintptr_t)cache % 32) || ((uintptr_t)out % 32)) return GR4AD_EUNSUPPORTED;
     const int64_t grid = ceil_div64(rows * (d / 8), 256);
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
-    ProfScope ps(KC_SELF_STEP, st);
+    // reads q,k,v and the pos cached (k,v) pairs, writes the new pair and the output
+    ProfScope ps(KC_SELF_STEP, st, 4.0 * rows * (double)(pos + 1) * d, (double)rows * d * (3 + 2 + 2 * pos + 1) * (dtype == GR4AD_BF16 ? 2 : 4));
     if (dtype == GR4AD_BF16)
         hipLaunchKernelGGL(self_attn_step<bf16>, dim3((unsigned)grid), dim3(256), 0, st, (const bf16 *)qkv, (bf16 *)cache, (bf16 *)out, rows, pos, T, d, H);
     else
@@ -510,7 +512,7 @@ int launch_trunk_self_attention(gr4ad_dtype dtype, const void *qkv, void *out, i
     const int64_t rows = (int64_t)B * T;
     const int64_t grid = ceil_div64(rows * H, 4);
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
-    ProfScope ps(KC_TRUNK_SELF, st);
+    ProfScope ps(KC_TRUNK_SELF, st, 0.0, (double)rows * d * 4 * (dtype == GR4AD_BF16 ? 2 : 4));
     if (dtype == GR4AD_BF16)
         hipLaunchKernelGGL(trunk_self_attn<bf16>, dim3((unsigned)grid), dim3(256), 0, st, (const bf16 *)qkv, (bf16 *)out, rows, T, d, H);
     else

@@ -64,7 +64,7 @@ int launch_rmsnorm(gr4ad_dtype dtype, const void *x, const void *g, void *y, int
     if (rows <= 0) return GR4AD_OK;
     int64_t grid = ceil_div64(rows, 4);
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
-    ProfScope ps(KC_RMSNORM, st);
+    ProfScope ps(KC_RMSNORM, st, 0.0, (double)rows * d * (4 + (dtype == GR4AD_BF16 ? 2 : 4)));
     if (dtype == GR4AD_BF16) {
         int nvec = d / 8;
         if (d % 8) return GR4AD_EUNSUPPORTED;
@@ -119,7 +119,7 @@ int launch_fuse_gate(gr4ad_dtype dtype, const void *m, int64_t m_req_stride, con
     int64_t rows = (int64_t)B * n, total = rows * (d / N);
     int64_t grid = ceil_div64(total, 256);
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
-    ProfScope ps(KC_FUSE_GATE, st);
+    ProfScope ps(KC_FUSE_GATE, st, 0.0, (double)rows * d * (4 + (dtype == GR4AD_BF16 ? 2 : 4)));
     if (dtype == GR4AD_BF16)
         hipLaunchKernelGGL(fuse_gate_kernel<bf16>, dim3((unsigned)grid), dim3(256), 0, st, (const float *)m, m_req_stride, (const float *)G, tok, (bf16 *)a, rows, n, d);
     else
@@ -143,7 +143,7 @@ int launch_broadcast_rows(gr4ad_dtype dtype, const void *pos, void *dst, int B, 
     int64_t total = (int64_t)B * per_req;
     int64_t grid = ceil_div64(total, 256);
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
-    ProfScope ps(KC_BROADCAST, st);
+    ProfScope ps(KC_BROADCAST, st, 0.0, (double)total * 4);
     if (dtype == GR4AD_BF16)
         hipLaunchKernelGGL(broadcast_rows_kernel<bf16>, dim3((unsigned)grid), dim3(256), 0, st, (const bf16 *)pos, (float *)dst, total, per_req);
     else
@@ -174,7 +174,7 @@ int launch_gather_rows(gr4ad_dtype dtype, const void *src, const int32_t *parent
     int64_t rows = (int64_t)B * k;
     if (rows <= 0 || row_elems <= 0) return GR4AD_OK;
     if (rows > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
-    ProfScope ps(KC_GATHER, st);
+    ProfScope ps(KC_GATHER, st, 0.0, 2.0 * rows * (double)row_elems * (dtype == GR4AD_BF16 ? 2 : 4));
     hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)rows), dim3(256), 0, st, (const uint4 *)src, parent, (uint4 *)dst, n, k, row_elems / N, row_stride / N);
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;

@@ -85,6 +85,11 @@ __global__ __launch_bounds__(256) void gemm_simple(const T *__restrict__ A, int6
 // global -> registers while the current one is multiplied, then registers -> LDS.
 enum { EPI_STORE = 0, EPI_SILU, EPI_F32, EPI_F32_RESID, EPI_F32_TABLE };
 
+// bytes a bf16 GEMM must move once: both operands, the output, and the residual it adds
+static double gemm_bytes(int64_t M, int N, int K, bool out_f32, bool resid) {
+    return 2.0 * ((double)M * K + (double)N * K) + (double)M * N * ((out_f32 ? 4 : 2) + (resid ? 4 : 0));
+}
+
 template <int BM, int BN, int WM, int WN, int KIND>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(const bf16 *__restrict__ A, int64_t lda,
                                                                              const bf16 *__restrict__ W, int64_t ldw, int64_t M,
@@ -432,7 +437,7 @@ static int launch_pipe_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
     int64_t grid = ceil_div64(tiles_m * tiles_n, 8) * 8;
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
     {
-        ProfScope ps(KC_GEMM_PIPE, st, 2.0 * (double)M * N * K);
+        ProfScope ps(KC_GEMM_PIPE, st, 2.0 * (double)M * N * K, gemm_bytes(M, N, K, KIND >= EPI_F32, KIND == EPI_F32_RESID));
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), PIPE_LDS_BYTES, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, epi);
     }
     GR4AD_LAUNCH_CHECK();
@@ -488,7 +493,7 @@ static int launch_mfma_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
     int64_t grid = ceil_div64(total, 8) * 8;
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
     {
-        ProfScope ps(BM == 256 ? KC_GEMM_256 : KC_GEMM_128, st, 2.0 * (double)M * N * K);
+        ProfScope ps(BM == 256 ? KC_GEMM_256 : KC_GEMM_128, st, 2.0 * (double)M * N * K, gemm_bytes(M, N, K, KIND >= EPI_F32, KIND == EPI_F32_RESID));
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), smem, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, epi);
     }
     GR4AD_LAUNCH_CHECK();

@@ -6,7 +6,7 @@
 #include "common.h"
 
 namespace {
-struct Record { hipEvent_t start, stop; int cls; double flops; };
+struct Record { hipEvent_t start, stop; int cls; double flops, bytes; };
 bool g_on = false;
 std::vector<Record> g_records;       // events in flight since the last read
 std::vector<Record> g_pool;          // recycled event pairs
@@ -16,7 +16,7 @@ const char *kNames[KC_COUNT] = {"gemm_bf16_mfma_256x256", "gemm_bf16_mfma_128x12
                                 "select_request", "gather_rows", "broadcast_rows", "v_transpose", "gemm_bf16_pipe"};
 }  // namespace
 
-ProfScope::ProfScope(int cls, hipStream_t st, double flops) : idx_(-1), st_(st) {
+ProfScope::ProfScope(int cls, hipStream_t st, double flops, double bytes) : idx_(-1), st_(st) {
     if (!g_on || g_records.size() >= kMaxRecords) return;
     Record r;
     if (!g_pool.empty()) {
@@ -27,6 +27,7 @@ ProfScope::ProfScope(int cls, hipStream_t st, double flops) : idx_(-1), st_(st) 
     }
     r.cls = cls;
     r.flops = flops;
+    r.bytes = bytes;
     (void)hipEventRecord(r.start, st);
     g_records.push_back(r);
     idx_ = (int)g_records.size() - 1;
@@ -47,15 +48,16 @@ int gr4ad_profile_kernel_count(void) { return KC_COUNT; }
 
 const char *gr4ad_profile_kernel_name(int cls) { return (cls >= 0 && cls < KC_COUNT) ? kNames[cls] : ""; }
 
-int gr4ad_profile_read(double *ms, double *flops, int64_t *launches, int reset) {
-    if (!ms || !flops || !launches) return GR4AD_EINVAL;
-    for (int i = 0; i < KC_COUNT; i++) { ms[i] = 0; flops[i] = 0; launches[i] = 0; }
+int gr4ad_profile_read(double *ms, double *flops, double *bytes, int64_t *launches, int reset) {
+    if (!ms || !flops || !bytes || !launches) return GR4AD_EINVAL;
+    for (int i = 0; i < KC_COUNT; i++) { ms[i] = 0; flops[i] = 0; bytes[i] = 0; launches[i] = 0; }
     for (const Record &r : g_records) {
         if (hipEventSynchronize(r.stop) != hipSuccess) return GR4AD_EHIP;
         float t = 0;
         if (hipEventElapsedTime(&t, r.start, r.stop) != hipSuccess) return GR4AD_EHIP;
         ms[r.cls] += t;
         flops[r.cls] += r.flops;
+        bytes[r.cls] += r.bytes;
         launches[r.cls] += 1;
     }
     if (reset) {

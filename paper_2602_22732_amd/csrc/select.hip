@@ -417,7 +417,7 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
     const int64_t rows = (int64_t)B * n;
     if (rows > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
     {
-        ProfScope ps(KC_SELECT_ROWS, st);
+        ProfScope ps(KC_SELECT_ROWS, st, 0.0, (double)rows * V * 4 + (double)rows * (k < V ? k : V) * 8);
         unsigned long long *cand = (unsigned long long *)ws;
         const size_t stage_bytes = (size_t)m * sizeof(unsigned long long);  // <= 32 KB (GR4AD_MAX_BEAM)
         if (V <= 1024)
@@ -430,7 +430,7 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
             hipLaunchKernelGGL(select_rows<64>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
     }
     GR4AD_LAUNCH_CHECK();
-    ProfScope ps(KC_SELECT_REQUEST, st);
+    ProfScope ps(KC_SELECT_REQUEST, st, 0.0, (double)rows * m * 8 + (double)B * k * 12);
     hipLaunchKernelGGL(select_request, dim3((unsigned)B), dim3(SELB_THREADS), 0, st, (const unsigned long long *)ws, (int64_t)n * m, V, k,
                        parent, tok, score, sid_old, sid_new, n, T, level);
     GR4AD_LAUNCH_CHECK();

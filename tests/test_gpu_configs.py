@@ -8,16 +8,30 @@ from paper_2602_22732_amd import synth
 
 pytestmark = pytest.mark.gpu
 
+_weights = {}
+
+
+def weights_of(w):
+    """Weights depend on the configuration's seed and shapes only, not on batch or beam scale."""
+    if w.cfg_id not in _weights:
+        _weights.clear()  # one large model at a time in host memory
+        _weights[w.cfg_id] = synth.make_weights(w)
+    return _weights[w.cfg_id]
+
 
 def run_config(cfg, sample, batch=None, scale=1.0):
     w = synth.workload(cfg, scale=scale, batch=batch)
-    W = synth.make_weights(w)
+    W = weights_of(w)
     lens = synth.make_lengths(w)
     X = synth.make_context(w, lens)
     sid, lp, tr = gpu_decode(w, W, X, lens)
     assert sid.shape == (w.B, w.beam[-1], w.T) and (np.diff(lp, axis=1) <= 0).all()
     for t in range(w.T):
         assert sid[..., t].min() >= 0 and sid[..., t].max() < w.V[t]
+    # properties that hold for every request of the batch, whatever its size
+    assert np.isfinite(lp).all() and (lp <= 0).all()
+    for r in range(0, w.B, max(1, w.B // 64)):
+        assert len({tuple(p) for p in sid[r]}) == w.beam[-1], "returned SIDs of request %d are not distinct" % r
     stats = judge_decode(w, W, X, lens, sid, lp, tr, sample)
     print("config %d (%s): %s" % (cfg, w.name, stats))
     return stats
@@ -29,3 +43,17 @@ def test_config2_small_bf16_full_batch():
 
 def test_config3_medium_bf16_sampled_requests():
     run_config(3, sample=[0, 101, 255])
+
+
+def test_config4_large_bf16_full_batch_sampled_requests():
+    # the workload bench.py times: B=1024, ragged context lengths, beams 256/512/512/1024
+    run_config(4, sample=[3, 1023])
+
+
+@pytest.mark.parametrize("scale,batch,sample", [
+    (0.25, 2048, [2047]),   # full batch at the narrowest schedule
+    (0.5, 96, [5]),         # the wider schedules on a slice of the batch (same model, same per-request work)
+    (1.0, 96, [95]),
+])
+def test_config5_load_adaptive_sweep_with_zipf_bias(scale, batch, sample):
+    run_config(5, sample=sample, batch=batch, scale=scale)
