@@ -85,7 +85,7 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
 
 // ---- optional per-kernel event timing ----------------------------------------
 enum KernelClass { KC_GEMM_256 = 0, KC_GEMM_128, KC_GEMM_SIMPLE, KC_XATTN_FLASH, KC_XATTN_SIMPLE, KC_SELF_STEP, KC_TRUNK_SELF,
-                   KC_RMSNORM, KC_FUSE_GATE, KC_SELECT_ROWS, KC_SELECT_REQUEST, KC_GATHER, KC_BROADCAST, KC_V_TRANSPOSE, KC_GEMM_PIPE, KC_COUNT };
+                   KC_RMSNORM, KC_FUSE_GATE, KC_SELECT_ROWS, KC_SELECT_REQUEST, KC_GATHER, KC_BROADCAST, KC_V_TRANSPOSE, KC_GEMM_RING, KC_COUNT };
 // Declared around a kernel launch: records an event before and (on scope exit) after it when timing is on.
 struct ProfScope {
     ProfScope(int cls, hipStream_t st, double flops = 0.0, double bytes = 0.0);  // algorithmic work of the launch

@@ -10,6 +10,8 @@
 //  * gemm_bf16_mfma<..>  bf16 operands, fp32 accumulation on the matrix cores with
 //                        v_mfma_f32_32x32x16_bf16; LDS double buffering with an
 //                        XOR swizzle of 16-byte chunks; XCD-aware tile order.
+//  * gemm_bf16_ring<..>  the kernel of the large shapes: persistent, 256x256 tiles,
+//                        operands stream global -> LDS without passing registers.
 #include "common.h"
 
 // ---------------------------------------------------------------------------
@@ -237,216 +239,305 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(con
 }
 
 // ---------------------------------------------------------------------------
-// MFMA kernel with a four-stage LDS pipeline fed by direct global->LDS loads
+// Persistent MFMA kernel: 256x256 block tile, BK = 64, ring of five 32 KB half-tiles in LDS
 // ---------------------------------------------------------------------------
-// 256x256 block tile, 8 wavefronts (wave tile 128x64), BK = 32: a K tile is 512 rows
-// of 64 bytes (4 chunks of 16 bytes; chunk c of row r at slot c ^ ((r >> 2) & 3), which
-// keeps fragment reads conflict-free).  Four stages of 32 KB sit in LDS.  A K tile is
-// fetched by global_load_lds_dwordx4: every lane moves 16 bytes straight into LDS (no
-// staging registers, no ds_write); one wave instruction fills 64 consecutive slots
-// = 16 tile rows, and the swizzle is applied on the global side (which chunk a lane
-// fetches).  Loads run three tiles ahead of the math; the wave waits on its own loads
-// with s_waitcnt vmcnt(n) and the workgroup meets at a bare s_barrier (a full fence
-// would wait for every load in flight).  The first fragments of the next tile are read
-// before the barrier, so the MFMA stream continues across it.
-// After the last tile the stages are reused to transpose the accumulators, so that C
-// leaves in 16-byte pieces along rows (128 or 256 contiguous bytes per row).
-#define PIPE_STAGES 4
-#define PIPE_STAGE_CHUNKS 2048  // 512 rows x 4 chunks
-#define PIPE_LDS_BYTES (8 * 64 * 288)  // epilogue staging (8 waves x 64 rows x 288 B) >= 4 stages x 32 KB
+// One workgroup (8 wavefronts, 2 x 4, wave tile 128 x 64) per compute unit walks a list of output tiles.
+// A k-tile is two half-tiles of 256 rows x 128 bytes (one full cache line per row): A(g) and W(g).  The ring holds
+// five half-tiles, filled by global_load_lds_dwordx4 (every lane moves 16 bytes straight into LDS; one wave
+// instruction fills 8 rows; chunk c of row r sits at position c ^ ((r >> 1) & 7), which keeps both the 1 KB
+// writes and the fragment reads conflict-free, and the swizzle is applied on the global side).  In item order
+// A0 W0 A1 W1 A2 ... item q lives in slot q % 5, so after the barrier that ends k-tile g its two slots take
+// W(g+2) and A(g+3): the operand that streams from HBM is requested two k-tiles ahead, the L2-resident weights
+// one k-tile ahead.  The item stream runs on into the next tile of the workgroup, so a tile's first operands
+// arrive while the previous tile is still being multiplied and stored.
+// Per k-tile: four k-steps of 8 MFMAs; the fragments of step s+1 are read while step s multiplies.  Fragment
+// reads are inline assembly so that their waits can be exact (lgkmcnt(6): the six reads just issued may still
+// be in flight); one bare s_barrier per k-tile separates "every wave has read A(g), W(g)" from "everybody's
+// share of A(g+1), W(g+1) has landed" (each wave waits for its own loads with vmcnt first).
+// The MFMA operands are swapped (W fragment first), so a lane owns one row of C and, per group of four
+// accumulator registers, four consecutive columns: the epilogue writes 8/16-byte pieces into the two slots the
+// last k-tile released (8 KB per wave, rows swizzled) and reads them back as full rows, so C leaves in 16-byte
+// pieces with whole cache lines per row.
+#define RING_SLOTS 5
+#define SLOT_CHUNKS 2048  // 256 rows x 8 chunks of 16 bytes
+#define RING_LDS_BYTES (RING_SLOTS * SLOT_CHUNKS * 16)
 
-__device__ __forceinline__ void dma16(const bf16 *g, bf16x8 *lds_wave_base) {
+__device__ __forceinline__ void ring_dma16(const char *g, bf16x8 *lds_wave_base) {
     __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)g,
                                      (void __attribute__((address_space(3))) *)lds_wave_base, 16, 0, 0);
 }
 
+__device__ __forceinline__ float fast_silu(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x)); }
+
 template <int KIND>
-__global__ __launch_bounds__(512) void gemm_bf16_pipe(const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ W, int64_t ldw,
-                                                      int64_t M, int N, int K, int64_t tiles_m, int tiles_n, GemmEpilogue epi) {
+__global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ W, int64_t ldw,
+                                                      int64_t M, int N, int K, int64_t tiles_m, int tiles_n, int group_m, GemmEpilogue epi) {
     extern __shared__ bf16x8 smem[];
-    const int64_t total = tiles_m * tiles_n;
-    const int64_t per_xcd = (total + 7) / 8;
-    const int64_t logical = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (logical >= total) return;
-    const int64_t m0 = (logical / tiles_n) * 256;
-    const int n0 = (int)(logical % tiles_n) * 256;
     const int tid = threadIdx.x, lane = tid % 64;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
-    const int wm = wave / 4, wn = wave % 4;  // 2 x 4 waves, wave tile 128 x 64
-    const int frow = lane % 32, fhalf = lane / 32;
+    const int wm = wave / 4, wn = wave % 4;
+    const int frow = lane % 32, hf = lane / 32;
+    const int KT = K / 64;
 
-    // DMA sources: load j of this wave covers tile rows (wave*4 + j)*16 .. +15, lane -> row + lane/4, slot lane%4
-    const bf16 *src[4];
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-        const int r = (wave * 4 + j) * 16 + lane / 4;  // 0..255: A rows, 256..511: W rows
-        const int c = (lane % 4) ^ ((r >> 2) & 3);     // logical chunk that lives in this slot
-        if (r < 256) {
-            int64_t gr = m0 + r;
-            src[j] = A + (gr < M ? gr : M - 1) * lda + c * 8;
-        } else {
-            int64_t gr = (int64_t)n0 + (r - 256);
-            src[j] = W + (gr < N ? gr : N - 1) * ldw + c * 8;
-        }
-    }
-    const int KT = K / 32;
-    auto issue = [&](int kt) {  // tile kt -> stage kt % 4
-        bf16x8 *base = smem + (kt & 3) * PIPE_STAGE_CHUNKS + wave * 256;
-#pragma unroll
-        for (int j = 0; j < 4; j++) dma16(src[j] + (int64_t)kt * 32, base + j * 64);
+    // ---- tile schedule: every XCD (workgroup id % 8) owns a contiguous range of logical tiles and its workgroups walk it
+    // with stride nslots; inside a group of group_m row blocks the row index runs fastest, so the workgroups of an XCD
+    // share a few A blocks and a few W blocks through their L2 at any time ----
+    const int64_t total = tiles_m * tiles_n;
+    const int nslots = gridDim.x / 8;
+    const int xcd = blockIdx.x % 8, wslot = blockIdx.x / 8;
+    const int64_t per_xcd = (total + 7) / 8;
+    const int64_t xcd_end = (xcd + 1) * per_xcd < total ? (xcd + 1) * per_xcd : total;
+    int64_t L = xcd * per_xcd + wslot;
+    if (L >= xcd_end) return;
+    const int64_t gsz = (int64_t)group_m * tiles_n;
+    auto tile_coords = [&](int64_t l, int64_t &m0, int &n0) {
+        const int64_t grp = l / gsz, in = l % gsz;
+        const int64_t first_m = grp * group_m;
+        const int64_t gm = tiles_m - first_m < group_m ? tiles_m - first_m : group_m;
+        m0 = (first_m + in % gm) * 256;
+        n0 = (int)(in / gm) * 256;
     };
 
+    // ---- loads: load j of this wave fills rows (wave*4+j)*8 .. +7 of a half-tile, lane -> row lane/8, position lane%8.
+    // The chunk that lives at position p of row r is p ^ ((r >> 1) & 7), and (r >> 1) & 7 = 4*(j&1) + (lane/8 >> 1). ----
+    const int dma_row0 = wave * 32 + lane / 8;
+    const uint32_t cb0 = (uint32_t)(((lane % 8) ^ ((lane / 8) >> 1)) * 16), cb1 = cb0 ^ 64u;
+    const uint32_t lda2 = (uint32_t)lda * 2, ldw2 = (uint32_t)ldw * 2;
+    int64_t m0, m0n = 0;
+    int n0, n0n = 0;
+    tile_coords(L, m0, n0);
+    bool has_next = L + nslots < xcd_end;
+    if (has_next) tile_coords(L + nslots, m0n, n0n);
+    // rows past the end of the matrix re-read its last row (never stored)
+    auto issue = [&](const bf16 *P, uint32_t ld2, int64_t row0, int64_t limit, int gk, int slot) {
+        bf16x8 *dst = smem + slot * SLOT_CHUNKS + wave * 256;
+        const char *base = (const char *)P + row0 * ld2 + gk * 128;
+        const int maxr = (int)(limit - 1 - row0 < 255 ? limit - 1 - row0 : 255);
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int r = dma_row0 + j * 8;
+            ring_dma16(base + (uint32_t)(r < maxr ? r : maxr) * ld2 + ((j & 1) ? cb1 : cb0), dst + j * 64);
+        }
+    };
+    // k-tile gk of the current tile (gk < KT) or of the workgroup's next tile (gk >= KT)
+    auto issue_a = [&](int gk, int slot) {
+        if (gk < KT) issue(A, lda2, m0, M, gk, slot);
+        else if (has_next) issue(A, lda2, m0n, M, gk - KT, slot);
+    };
+    auto issue_w = [&](int gk, int slot) {
+        if (gk < KT) issue(W, ldw2, n0, N, gk, slot);
+        else if (has_next) issue(W, ldw2, n0n, N, gk - KT, slot);
+    };
+
+    // ---- fragments: lane reads row frow of a 32-row block, chunk 2s + hf of k-step s, i.e. position (hf ^ fx) ^ 2s ----
+    const int fx = (frow >> 1) & 7;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    const uint32_t a_lane = lds0 + (uint32_t)((wm * 128 + frow) * 8 + (hf ^ fx)) * 16;
+    const uint32_t w_lane = lds0 + (uint32_t)((wn * 64 + frow) * 8 + (hf ^ fx)) * 16;
+    auto read_frags = [&](bf16x8 (&af)[4], bf16x8 (&wf)[2], int slot_a, int slot_w, int s) {
+        const uint32_t pa = (a_lane ^ (uint32_t)(s << 5)) + (uint32_t)slot_a * 32768u;
+        const uint32_t pw = (w_lane ^ (uint32_t)(s << 5)) + (uint32_t)slot_w * 32768u;
+        asm volatile("ds_read_b128 %0, %1" : "=v"(af[0]) : "v"(pa));
+        asm volatile("ds_read_b128 %0, %1 offset:4096" : "=v"(af[1]) : "v"(pa));
+        asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(af[2]) : "v"(pa));
+        asm volatile("ds_read_b128 %0, %1 offset:12288" : "=v"(af[3]) : "v"(pa));
+        asm volatile("ds_read_b128 %0, %1" : "=v"(wf[0]) : "v"(pw));
+        asm volatile("ds_read_b128 %0, %1 offset:4096" : "=v"(wf[1]) : "v"(pw));
+    };
+    // the fragments are operands of the wait, so nothing that uses them can move above it
+    auto wait_frags = [&](bf16x8 (&af)[4], bf16x8 (&wf)[2], bool all) {
+        if (all) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[0]), "+v"(af[1]), "+v"(af[2]), "+v"(af[3]), "+v"(wf[0]), "+v"(wf[1]));
+        else asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(af[0]), "+v"(af[1]), "+v"(af[2]), "+v"(af[3]), "+v"(wf[0]), "+v"(wf[1]));
+    };
     floatx16 acc[4][2];
+    auto mma = [&](const bf16x8 (&af)[4], const bf16x8 (&wf)[2]) {
 #pragma unroll
-    for (int i = 0; i < 4; i++)
+        for (int i = 0; i < 4; i++)
 #pragma unroll
-        for (int j = 0; j < 2; j++)
-#pragma unroll
-            for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
+            for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0);
+    };
 
-    // fragment slots inside a stage: row r, k-step kk: chunk (2*kk + fhalf) ^ ((r >> 2) & 3)
-    int a_slot[4], w_slot[2];
-#pragma unroll
-    for (int i = 0; i < 4; i++) a_slot[i] = (wm * 128 + i * 32 + frow) * 4;
-#pragma unroll
-    for (int j = 0; j < 2; j++) w_slot[j] = (256 + wn * 64 + j * 32 + frow) * 4;
-    const int fx = (frow >> 2) & 3;
-    const int ch0 = fhalf ^ fx, ch1 = (2 + fhalf) ^ fx;
-
-    // prologue: three tiles in flight, the first two landed before the first barrier
-    issue(0);
-    if (KT > 1) issue(1);
-    if (KT > 2) issue(2);
-    if (KT > 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // ---- prologue: A(0) W(0) A(1) W(1) A(2) into slots 0..4 (K >= 192, so all belong to the first tile) ----
+    issue_a(0, 0);
+    issue_w(0, 1);
+    issue_a(1, 2);
+    issue_w(1, 3);
+    issue_a(2, 4);
+    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    bf16x8 fa0[4], fw0[2], fa1[4], fw1[2];
+    int sa = 0;  // slot of A(g); W(g) sits in the next slot
+    read_frags(fa0, fw0, 0, 1, 0);
 
-    bf16x8 af0[4], wf0[2], af1[4], wf1[2];
-#pragma unroll
-    for (int i = 0; i < 4; i++) af0[i] = smem[a_slot[i] + ch0];
-#pragma unroll
-    for (int j = 0; j < 2; j++) wf0[j] = smem[w_slot[j] + ch0];
-
-    for (int kt = 0; kt < KT; kt++) {
-        const bf16x8 *s = smem + (kt & 3) * PIPE_STAGE_CHUNKS;
-        // first k-step: its fragments were read before the barrier, so the MFMAs start at once
+#define SB __builtin_amdgcn_sched_barrier(0)
+    for (;;) {  // tiles of this workgroup
 #pragma unroll
         for (int i = 0; i < 4; i++)
-#pragma unroll
-            for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af0[i], wf0[j], acc[i][j], 0, 0, 0);
-        // while they run: fragments of the second k-step, and the loads of tile kt+3
-#pragma unroll
-        for (int i = 0; i < 4; i++) af1[i] = s[a_slot[i] + ch1];
-#pragma unroll
-        for (int j = 0; j < 2; j++) wf1[j] = s[w_slot[j] + ch1];
-        if (kt + 3 < KT) issue(kt + 3);  // stage of tile kt-1: every wave finished reading it before the last barrier
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-#pragma unroll
-            for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i], wf1[j], acc[i][j], 0, 0, 0);
-        if (kt + 1 < KT) {  // tile kt+1 has been visible since the previous barrier
-            const bf16x8 *sn = smem + ((kt + 1) & 3) * PIPE_STAGE_CHUNKS;
-#pragma unroll
-            for (int i = 0; i < 4; i++) af0[i] = sn[a_slot[i] + ch0];
-#pragma unroll
-            for (int j = 0; j < 2; j++) wf0[j] = sn[w_slot[j] + ch0];
-        }
-        // tiles <= kt+2 must have landed before the barrier; only tile kt+3 (4 loads) may stay in flight
-        if (kt + 3 < KT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-    }
-
-    // ---- epilogue: accumulators -> this wave's LDS region (row-major, padded) -> 16-byte row pieces ----
-    constexpr bool OUT_F32 = KIND >= EPI_F32;
-    constexpr int PITCH = OUT_F32 ? 288 : 144;        // bytes per staged row of 64 columns
-    constexpr int ROWS_PER_PASS = OUT_F32 ? 64 : 128;  // 18 KB per wave and pass
-    constexpr int PASSES = 128 / ROWS_PER_PASS;
-    constexpr int LANES_PER_ROW = OUT_F32 ? 16 : 8;    // 16-byte pieces per staged row
-    char *stage = (char *)smem + wave * (64 * 288);
-    const int64_t wrow0 = m0 + wm * 128;
-    const int wcol0 = n0 + wn * 64;
-#pragma unroll
-    for (int pass = 0; pass < PASSES; pass++) {
-        // MFMA layout: lane -> column lane%32 of the 32x32 tile, register v -> row 8*(v/4) + 4*(lane/32) + v%4
-#pragma unroll
-        for (int ii = 0; ii < ROWS_PER_PASS / 32; ii++) {
-            const int i = pass * (ROWS_PER_PASS / 32) + ii;
 #pragma unroll
             for (int j = 0; j < 2; j++)
 #pragma unroll
-                for (int v = 0; v < 16; v++) {
-                    const int r = ii * 32 + 8 * (v / 4) + 4 * fhalf + (v % 4), c = j * 32 + frow;
-                    if (OUT_F32) *(float *)(stage + r * PITCH + c * 4) = acc[i][j][v];
-                    else *(bf16 *)(stage + r * PITCH + c * 2) = (bf16)(KIND == EPI_SILU ? acc[i][j][v] / (1.0f + __expf(-acc[i][j][v])) : acc[i][j][v]);
-                }
+                for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
+        for (int kt = 0; kt < KT; kt++) {
+            const int sw = sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1;
+            SB; read_frags(fa1, fw1, sa, sw, 1); wait_frags(fa0, fw0, false); SB;
+            mma(fa0, fw0); SB;
+            read_frags(fa0, fw0, sa, sw, 2); wait_frags(fa1, fw1, false); SB;
+            mma(fa1, fw1); SB;
+            read_frags(fa1, fw1, sa, sw, 3); wait_frags(fa0, fw0, false); SB;
+            mma(fa0, fw0); SB;
+            // every read of A(g), W(g) has returned; this wave's share of A(g+1), W(g+1) has landed (only A(g+2) may stay in flight)
+            wait_frags(fa1, fw1, true);
+            if (kt + 2 < KT || has_next) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            const int sa1 = sa + 2 >= RING_SLOTS ? sa + 2 - RING_SLOTS : sa + 2;
+            const int sw1 = sa + 3 >= RING_SLOTS ? sa + 3 - RING_SLOTS : sa + 3;
+            SB; if (kt + 1 < KT || has_next) read_frags(fa0, fw0, sa1, sw1, 0); SB;
+            if (kt + 1 < KT) {  // the two slots just released take W(g+2) and A(g+3); after a tile's last k-tile they first stage C
+                issue_w(kt + 2, sa);
+                issue_a(kt + 3, sw);
+            }
+            SB; mma(fa1, fw1); SB;
+            if (kt + 1 < KT) sa = sa1;
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // wave-private region: no barrier needed
+        // ---- epilogue: slots sa (waves 0..3) and sa+1 (waves 4..7) are free, 8 KB per wave ----
+        const int sw = sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1;
+        {
+            constexpr bool OUT_F32 = KIND >= EPI_F32;
+            char *stage = (char *)(smem + (wave < 4 ? sa : sw) * SLOT_CHUNKS) + (wave % 4) * 8192;
+            const int64_t wrow0 = m0 + wm * 128;
+            const int wcol0 = n0 + wn * 64;
+            if (!OUT_F32) {
+                // two passes of 64 rows x 64 columns: 128-byte rows of 8 chunks, chunk c of row r at position c ^ (r & 7)
 #pragma unroll
-        for (int it = 0; it < ROWS_PER_PASS / (64 / LANES_PER_ROW); it++) {
-            const int r = it * (64 / LANES_PER_ROW) + lane / LANES_PER_ROW;
-            const int piece = lane % LANES_PER_ROW;
-            const int64_t row = wrow0 + pass * ROWS_PER_PASS + r;
-            const int col = wcol0 + piece * (OUT_F32 ? 4 : 8);
-            if (row >= M || col >= N) continue;
-            if (OUT_F32) {
-                floatx4 x = *(const floatx4 *)(stage + r * PITCH + piece * 16);
-                if (col + 3 < N) {
-                    floatx4 add = {0.0f, 0.0f, 0.0f, 0.0f};
-                    if (KIND == EPI_F32 && epi.bias) add = *(const floatx4 *)(epi.bias + col);
-                    if (KIND == EPI_F32_RESID) add = *(const floatx4 *)(epi.resid + row * epi.ldr + col);
-                    if (KIND == EPI_F32_TABLE) add = *(const floatx4 *)(epi.table + (epi.tok ? (int64_t)epi.tok[row] : 0) * N + col);
-                    *(floatx4 *)((float *)epi.C + row * epi.ldc + col) = x + add;
-                } else {
-                    for (int e = 0; e < 4 && col + e < N; e++) {
-                        float y = x[e];
-                        if (KIND == EPI_F32 && epi.bias) y += epi.bias[col + e];
-                        if (KIND == EPI_F32_RESID) y += epi.resid[row * epi.ldr + col + e];
-                        if (KIND == EPI_F32_TABLE) y += epi.table[(epi.tok ? (int64_t)epi.tok[row] : 0) * N + col + e];
-                        ((float *)epi.C)[row * epi.ldc + col + e] = y;
+                for (int pass = 0; pass < 2; pass++) {
+#pragma unroll
+                    for (int ii = 0; ii < 2; ii++) {
+                        const int r = ii * 32 + frow;
+#pragma unroll
+                        for (int j = 0; j < 2; j++)
+#pragma unroll
+                            for (int g = 0; g < 4; g++) {
+                                bf16x4 pk;
+#pragma unroll
+                                for (int e = 0; e < 4; e++) {
+                                    const float x = acc[pass * 2 + ii][j][4 * g + e];
+                                    pk[e] = (bf16)(KIND == EPI_SILU ? fast_silu(x) : x);
+                                }
+                                const int c = j * 4 + g;
+                                *(bf16x4 *)(stage + r * 128 + ((c ^ (r & 7)) * 16) + hf * 8) = pk;
+                            }
                     }
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // wave-private region: no barrier needed
+#pragma unroll 4
+                    for (int it = 0; it < 8; it++) {
+                        const int r = it * 8 + lane / 8, c = lane % 8;
+                        const bf16x8 x = *(const bf16x8 *)(stage + r * 128 + ((c ^ (r & 7)) * 16));
+                        const int64_t row = wrow0 + pass * 64 + r;
+                        const int col = wcol0 + c * 8;
+                        if (row < M && col < N) {
+                            if (col + 7 < N) *(bf16x8 *)((bf16 *)epi.C + row * epi.ldc + col) = x;
+                            else for (int e = 0; e < 8 && col + e < N; e++) ((bf16 *)epi.C)[row * epi.ldc + col + e] = x[e];
+                        }
+                    }
+                    if (pass == 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 }
             } else {
-                bf16x8 x = *(const bf16x8 *)(stage + r * PITCH + piece * 16);
-                if (col + 7 < N) {
-                    *(bf16x8 *)((bf16 *)epi.C + row * epi.ldc + col) = x;
-                } else {
-                    for (int e = 0; e < 8 && col + e < N; e++) ((bf16 *)epi.C)[row * epi.ldc + col + e] = x[e];
+                // four passes of 32 rows x 64 columns: 256-byte rows of 16 chunks, chunk c of row r at position c ^ (r & 15)
+#pragma unroll
+                for (int pass = 0; pass < 4; pass++) {
+                    const int r = frow;
+#pragma unroll
+                    for (int j = 0; j < 2; j++)
+#pragma unroll
+                        for (int g = 0; g < 4; g++) {
+                            floatx4 pk;
+#pragma unroll
+                            for (int e = 0; e < 4; e++) pk[e] = acc[pass][j][4 * g + e];
+                            const int c = j * 8 + g * 2 + hf;
+                            *(floatx4 *)(stage + r * 256 + ((c ^ (r & 15)) * 16)) = pk;
+                        }
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll 4
+                    for (int it = 0; it < 8; it++) {
+                        const int rr = it * 4 + lane / 16, c = lane % 16;
+                        floatx4 x = *(const floatx4 *)(stage + rr * 256 + ((c ^ (rr & 15)) * 16));
+                        const int64_t row = wrow0 + pass * 32 + rr;
+                        const int col = wcol0 + c * 4;
+                        if (row < M && col < N) {
+                            if (col + 3 < N) {
+                                floatx4 add = {0.0f, 0.0f, 0.0f, 0.0f};
+                                if (KIND == EPI_F32 && epi.bias) add = *(const floatx4 *)(epi.bias + col);
+                                if (KIND == EPI_F32_RESID) add = *(const floatx4 *)(epi.resid + row * epi.ldr + col);
+                                if (KIND == EPI_F32_TABLE) add = *(const floatx4 *)(epi.table + (epi.tok ? (int64_t)epi.tok[row] : 0) * N + col);
+                                *(floatx4 *)((float *)epi.C + row * epi.ldc + col) = x + add;
+                            } else {
+                                for (int e = 0; e < 4 && col + e < N; e++) {
+                                    float y = x[e];
+                                    if (KIND == EPI_F32 && epi.bias) y += epi.bias[col + e];
+                                    if (KIND == EPI_F32_RESID) y += epi.resid[row * epi.ldr + col + e];
+                                    if (KIND == EPI_F32_TABLE) y += epi.table[(epi.tok ? (int64_t)epi.tok[row] : 0) * N + col + e];
+                                    ((float *)epi.C)[row * epi.ldc + col + e] = y;
+                                }
+                            }
+                        }
+                    }
+                    if (pass < 3) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 }
             }
         }
-        if (pass + 1 < PASSES) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (!has_next) break;
+        // ---- the next tile becomes current; the staging slots take its W(1) and A(2) ----
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();  // every wave has read its staged rows back before the slots are overwritten
+        asm volatile("" ::: "memory");
+        L += nslots;
+        m0 = m0n; n0 = n0n;
+        has_next = L + nslots < xcd_end;
+        if (has_next) tile_coords(L + nslots, m0n, n0n);
+        issue_w(1, sa);
+        issue_a(2, sw);
+        sa = sa + 2 >= RING_SLOTS ? sa + 2 - RING_SLOTS : sa + 2;
     }
+#undef SB
 }
 
 template <int KIND>
-static int launch_pipe_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, int64_t M, int N, int K, const GemmEpilogue &epi,
+static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, int64_t M, int N, int K, const GemmEpilogue &epi,
                             hipStream_t st) {
-    auto kern = gemm_bf16_pipe<KIND>;
+    auto kern = gemm_bf16_ring<KIND>;
     static bool attr_done = false;
+    static int n_cu = 0;
     if (!attr_done) {
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, PIPE_LDS_BYTES) != hipSuccess) return GR4AD_EHIP;
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, RING_LDS_BYTES) != hipSuccess) return GR4AD_EHIP;
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return GR4AD_EHIP;
+        n_cu = prop.multiProcessorCount;
         attr_done = true;
     }
-    int64_t tiles_m = ceil_div64(M, 256);
-    int tiles_n = (N + 255) / 256;
-    int64_t grid = ceil_div64(tiles_m * tiles_n, 8) * 8;
-    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    const int64_t tiles_m = ceil_div64(M, 256);
+    const int tiles_n = (N + 255) / 256;
+    const int64_t total = tiles_m * tiles_n;
+    // one workgroup per compute unit (the ring takes the whole LDS), a multiple of the 8 XCDs
+    int64_t grid = n_cu / 8 * 8;
+    if (grid < 8) grid = 8;
+    if (total < grid) grid = ceil_div64(total, 8) * 8;
     {
-        ProfScope ps(KC_GEMM_PIPE, st, 2.0 * (double)M * N * K, gemm_bytes(M, N, K, KIND >= EPI_F32, KIND == EPI_F32_RESID));
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), PIPE_LDS_BYTES, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, epi);
+        ProfScope ps(KC_GEMM_RING, st, 2.0 * (double)M * N * K, gemm_bytes(M, N, K, KIND >= EPI_F32, KIND == EPI_F32_RESID));
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), RING_LDS_BYTES, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, 4, epi);
     }
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }
 
-// The pipelined kernel stores 16-byte pieces: it needs 16-byte aligned rows of C (and of what the epilogue adds).
-static bool pipe_ok(int kind, int N, const GemmEpilogue &e) {
+// The persistent kernel stores 16-byte pieces: it needs 16-byte aligned rows of C (and of what the epilogue adds),
+// at least three k-tiles, and row pitches whose byte offsets inside a 256-row block fit 32 bits.
+static bool ring_ok(int kind, int N, int K, int64_t lda, int64_t ldw, const GemmEpilogue &e) {
     const bool f32 = kind >= EPI_F32;
+    if (K < 192 || lda >= (1 << 22) || ldw >= (1 << 22)) return false;
     if (e.ldc % (f32 ? 4 : 8) || ((uintptr_t)e.C % 16)) return false;
     if (kind == EPI_F32 && e.bias && ((uintptr_t)e.bias % 16)) return false;
     if (kind == EPI_F32_RESID && (e.ldr % 4 || ((uintptr_t)e.resid % 16))) return false;
@@ -454,14 +545,14 @@ static bool pipe_ok(int kind, int N, const GemmEpilogue &e) {
     return true;
 }
 
-static int launch_pipe(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, int64_t M, int N, int K, int kind, const GemmEpilogue &epi,
+static int launch_ring(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, int64_t M, int N, int K, int kind, const GemmEpilogue &epi,
                        hipStream_t st) {
     switch (kind) {
-        case EPI_STORE: return launch_pipe_kind<EPI_STORE>(A, lda, W, ldw, M, N, K, epi, st);
-        case EPI_SILU: return launch_pipe_kind<EPI_SILU>(A, lda, W, ldw, M, N, K, epi, st);
-        case EPI_F32: return launch_pipe_kind<EPI_F32>(A, lda, W, ldw, M, N, K, epi, st);
-        case EPI_F32_RESID: return launch_pipe_kind<EPI_F32_RESID>(A, lda, W, ldw, M, N, K, epi, st);
-        default: return launch_pipe_kind<EPI_F32_TABLE>(A, lda, W, ldw, M, N, K, epi, st);
+        case EPI_STORE: return launch_ring_kind<EPI_STORE>(A, lda, W, ldw, M, N, K, epi, st);
+        case EPI_SILU: return launch_ring_kind<EPI_SILU>(A, lda, W, ldw, M, N, K, epi, st);
+        case EPI_F32: return launch_ring_kind<EPI_F32>(A, lda, W, ldw, M, N, K, epi, st);
+        case EPI_F32_RESID: return launch_ring_kind<EPI_F32_RESID>(A, lda, W, ldw, M, N, K, epi, st);
+        default: return launch_ring_kind<EPI_F32_TABLE>(A, lda, W, ldw, M, N, K, epi, st);
     }
 }
 
@@ -513,7 +604,7 @@ static int launch_mfma(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, i
 }
 
 // 0 auto, 1 plain FMA kernel, 2 128x128 tiles, 3 256x256 tiles with 8 wavefronts, 4 256x256 tiles with 4 wavefronts,
-// 5 pipelined 256x256 kernel
+// 5 persistent 256x256 kernel
 static int g_gemm_mode = -1;
 static int gemm_mode() {
     if (g_gemm_mode < 0) {
@@ -532,7 +623,7 @@ int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, in
         ((uintptr_t)W % 16) == 0) {
         const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
         const bool big = (M >= 8192 && N >= 256);
-        if ((mode == 5 || (mode == 0 && big)) && pipe_ok(kind, N, epi)) return launch_pipe(a, lda, w, ldw, M, N, K, kind, epi, st);
+        if ((mode == 5 || (mode == 0 && big)) && ring_ok(kind, N, K, lda, ldw, epi)) return launch_ring(a, lda, w, ldw, M, N, K, kind, epi, st);
         if (mode == 4) return launch_mfma<256, 256, 128, 128>(a, lda, w, ldw, M, N, K, kind, epi, st);
         if ((mode == 0 && big) || mode == 3) return launch_mfma<256, 256, 128, 64>(a, lda, w, ldw, M, N, K, kind, epi, st);
         return launch_mfma<128, 128, 64, 64>(a, lda, w, ldw, M, N, K, kind, epi, st);
