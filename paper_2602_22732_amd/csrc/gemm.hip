@@ -299,7 +299,11 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
     };
 
     // ---- loads: load j of this wave fills rows (wave*4+j)*8 .. +7 of a half-tile, lane -> row lane/8, position lane%8.
-    // The chunk that lives at position p of row r is p ^ ((r >> 1) & 7), and (r >> 1) & 7 = 4*(j&1) + (lane/8 >> 1). ----
+    // The chunk that lives at position p of row r is p ^ ((r >> 1) & 7), and (r >> 1) & 7 = 4*(j&1) + (lane/8 >> 1).
+    // Per tile: a wave-uniform base pointer (row block; a k-tile adds 128 bytes) and per-lane 32-bit offsets (row inside
+    // the block, clamped at the matrix edge so rows past the end re-read the last row, times the pitch, plus the chunk).
+    // A load then costs one scalar add: whatever else sits between the barrier and the MFMAs idles the matrix cores,
+    // because both waves of a SIMD reach it together. ----
     const int dma_row0 = wave * 32 + lane / 8;
     const uint32_t cb0 = (uint32_t)(((lane % 8) ^ ((lane / 8) >> 1)) * 16), cb1 = cb0 ^ 64u;
     const uint32_t lda2 = (uint32_t)lda * 2, ldw2 = (uint32_t)ldw * 2;
@@ -308,25 +312,42 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
     tile_coords(L, m0, n0);
     bool has_next = L + nslots < xcd_end;
     if (has_next) tile_coords(L + nslots, m0n, n0n);
-    // rows past the end of the matrix re-read its last row (never stored)
-    auto issue = [&](const bf16 *P, uint32_t ld2, int64_t row0, int64_t limit, int gk, int slot) {
-        bf16x8 *dst = smem + slot * SLOT_CHUNKS + wave * 256;
-        const char *base = (const char *)P + row0 * ld2 + gk * 128;
-        const int maxr = (int)(limit - 1 - row0 < 255 ? limit - 1 - row0 : 255);
+    typedef uint32_t offvec __attribute__((ext_vector_type(4)));
+    offvec offA, offW, offAn, offWn;
+    const char *baseA, *baseW, *baseAn = nullptr, *baseWn = nullptr;
+    auto tile_sources = [&](int64_t tm0, int tn0, const char *&bA, const char *&bW, offvec &oA, offvec &oW) {
+        bA = (const char *)A + tm0 * lda2;
+        bW = (const char *)W + (int64_t)tn0 * ldw2;
+        const int maxa = (int)(M - 1 - tm0 < 255 ? M - 1 - tm0 : 255), maxw = N - 1 - tn0 < 255 ? N - 1 - tn0 : 255;
 #pragma unroll
         for (int j = 0; j < 4; j++) {
             const int r = dma_row0 + j * 8;
-            ring_dma16(base + (uint32_t)(r < maxr ? r : maxr) * ld2 + ((j & 1) ? cb1 : cb0), dst + j * 64);
+            oA[j] = (uint32_t)(r < maxa ? r : maxa) * lda2 + ((j & 1) ? cb1 : cb0);
+            oW[j] = (uint32_t)(r < maxw ? r : maxw) * ldw2 + ((j & 1) ? cb1 : cb0);
         }
     };
-    // k-tile gk of the current tile (gk < KT) or of the workgroup's next tile (gk >= KT)
+    tile_sources(m0, n0, baseA, baseW, offA, offW);
+    offAn = offA; offWn = offW;
+    if (has_next) tile_sources(m0n, n0n, baseAn, baseWn, offAn, offWn);
+    // k-tile gk of the current tile (gk < KT) or of the workgroup's next tile (gk >= KT).  The offsets of the two tiles are
+    // blended arithmetically: a select between the two variables would make the compiler keep them in scratch memory.
     auto issue_a = [&](int gk, int slot) {
-        if (gk < KT) issue(A, lda2, m0, M, gk, slot);
-        else if (has_next) issue(A, lda2, m0n, M, gk - KT, slot);
+        const bool cur = gk < KT;
+        if (!cur && !has_next) return;
+        const char *base = cur ? baseA + gk * 128 : baseAn + (gk - KT) * 128;
+        const offvec off = offA + (offAn - offA) * (cur ? 0u : 1u);
+        bf16x8 *dst = smem + slot * SLOT_CHUNKS + wave * 256;
+#pragma unroll
+        for (int j = 0; j < 4; j++) ring_dma16(base + off[j], dst + j * 64);
     };
     auto issue_w = [&](int gk, int slot) {
-        if (gk < KT) issue(W, ldw2, n0, N, gk, slot);
-        else if (has_next) issue(W, ldw2, n0n, N, gk - KT, slot);
+        const bool cur = gk < KT;
+        if (!cur && !has_next) return;
+        const char *base = cur ? baseW + gk * 128 : baseWn + (gk - KT) * 128;
+        const offvec off = offW + (offWn - offW) * (cur ? 0u : 1u);
+        bf16x8 *dst = smem + slot * SLOT_CHUNKS + wave * 256;
+#pragma unroll
+        for (int j = 0; j < 4; j++) ring_dma16(base + off[j], dst + j * 64);
     };
 
     // ---- fragments: lane reads row frow of a 32-row block, chunk 2s + hf of k-step s, i.e. position (hf ^ fx) ^ 2s ----
@@ -494,9 +515,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
         __builtin_amdgcn_s_barrier();  // every wave has read its staged rows back before the slots are overwritten
         asm volatile("" ::: "memory");
         L += nslots;
-        m0 = m0n; n0 = n0n;
+        m0 = m0n; n0 = n0n; baseA = baseAn; baseW = baseWn;
+        offA = offAn; offW = offWn;
         has_next = L + nslots < xcd_end;
-        if (has_next) tile_coords(L + nslots, m0n, n0n);
+        if (has_next) {
+            tile_coords(L + nslots, m0n, n0n);
+            tile_sources(m0n, n0n, baseAn, baseWn, offAn, offWn);
+        }
         issue_w(1, sa);
         issue_a(2, sw);
         sa = sa + 2 >= RING_SLOTS ? sa + 2 - RING_SLOTS : sa + 2;
