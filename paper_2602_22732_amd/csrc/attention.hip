@@ -203,39 +203,51 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
                 for (int qt = 0; qt < QT; qt++) s[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][st], s[qt][sub], 0, 0, 0);
             }
         }
-        // this lane holds, for beam frow of each tile qt, keys tile*64 + 32*sub + 16*(v/8) + 8*hf + v%8
+        // this lane holds, for beam frow of each tile qt, keys tile*64 + 32*sub + 16*(v/8) + 8*hf + v%8.
+        // The softmax is the instruction-bound part of the kernel (about three vector instructions per MFMA flop-cycle),
+        // so it is kept lean: scores stay raw and the scale enters through one fused multiply-add per element; only a
+        // partial last tile is masked; and the running maximum is refreshed lazily -- as long as no score exceeds the
+        // maximum in use by more than 2^8 the old one stays, p <= 256 is harmless in fp32 sums and bf16 operands, and
+        // the rescaling of O (one multiply per score element) is skipped.
         const int key0 = tile * 64 + 8 * hf;
+        const bool partial = tile * 64 + 64 > len;
         bf16x8 pf[QT][4];
 #pragma unroll
         for (int qt = 0; qt < QT; qt++) {
+            if (partial) {
+#pragma unroll
+                for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+                    for (int v = 0; v < 16; v++)
+                        if (key0 + 32 * sub + 16 * (v / 8) + (v % 8) >= len) s[qt][sub][v] = -INFINITY;
+            }
             float mx = -INFINITY;
 #pragma unroll
             for (int sub = 0; sub < 2; sub++)
 #pragma unroll
-                for (int v = 0; v < 16; v++) {
-                    const int key = key0 + 32 * sub + 16 * (v / 8) + (v % 8);
-                    const float x = key < len ? s[qt][sub][v] * scale_log2e : -INFINITY;
-                    s[qt][sub][v] = x;
-                    mx = fmaxf(mx, x);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float mnew = fmaxf(m_run[qt], mx);  // finite: every tile holds at least one valid key
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - mnew);
-            m_run[qt] = mnew;
+                for (int v = 0; v < 16; v++) mx = fmaxf(mx, s[qt][sub][v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2e;  // finite: every tile holds at least one valid key
+            if (__builtin_amdgcn_ballot_w64(mx > m_run[qt] + 8.0f) != 0) {  // some beam of the wave outgrew its maximum
+                const float mnew = mx > m_run[qt] + 8.0f ? mx : m_run[qt];
+                const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - mnew);  // m_run = -inf on the first tile gives 0
+                m_run[qt] = mnew;
+                l_run[qt] *= alpha;
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                    for (int v = 0; v < 16; v++) o[qt][mt][v] *= alpha;
+            }
+            const float neg_m = -m_run[qt];
             float lsum = 0.0f;
 #pragma unroll
             for (int sub = 0; sub < 2; sub++)
 #pragma unroll
                 for (int v = 0; v < 16; v++) {
-                    const float p = __builtin_amdgcn_exp2f(s[qt][sub][v] - mnew);
-                    lsum += p;
-                    pf[qt][2 * sub + v / 8][v % 8] = (bf16)p;  // k-step 2*sub + v/8 of the second product
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qt][sub][v], scale_log2e, neg_m));
+                    lsum += pv;
+                    pf[qt][2 * sub + v / 8][v % 8] = (bf16)pv;  // k-step 2*sub + v/8 of the second product
                 }
-            l_run[qt] = l_run[qt] * alpha + lsum;  // per half-wave partial sum, joined at the end
-#pragma unroll
-            for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-                for (int v = 0; v < 16; v++) o[qt][mt][v] *= alpha;
+            l_run[qt] += lsum;  // per half-wave partial sum, joined at the end
         }
         // second product; V^T fragments are shared by the QT beam tiles
 #pragma unroll
