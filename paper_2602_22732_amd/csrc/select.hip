@@ -11,6 +11,8 @@
 //     (order-preserving bits of the fp32 score) << 32 | (0xFFFFFFFF - flat index)
 // so "larger key" means "higher score, then lower flat index i*V + v": equal
 // scores resolve deterministically and the final order is a plain key sort.
+#include <stdlib.h>
+
 #include "common.h"
 
 __device__ __forceinline__ uint32_t score_key(float f) {
@@ -291,6 +293,224 @@ __global__ __launch_bounds__(256) void select_rows(const float *__restrict__ log
 }
 
 // ---------------------------------------------------------------------------
+// stage A, wavefront form: one wavefront per beam row (V <= 8192, V % 4 == 0)
+// ---------------------------------------------------------------------------
+// Same cut as select_rows, but a row never leaves one wavefront: no workgroup barrier anywhere, the V logits sit
+// in VEC*4 registers per lane (lane l holds tokens (j*64 + l)*4 .. +3, read as 16-byte pieces), every reduction
+// is a wave reduction, and the histogram, the threshold-bin list and the staged output live in a private LDS
+// region per wavefront.  The kernel is bound by vector instructions per logit, not by its barriers or its
+// bandwidth, so each pass is a handful of instructions per element: max and min; one exp2; scores written back
+// over the logits; a fused multiply-add and a conversion give the bin for the LDS atomic; the emit pass repeats
+// those two, and compaction costs two mbcnt, an add and an 8-byte LDS write per element.  Score bits are staged
+// raw and turned into sortable keys only for the m survivors on the way out.
+#define WROW_BINS 1024
+#define WROW_LIST 512  // threshold-bin candidates ranked exactly; the list reuses the histogram's 4 KB
+
+__device__ __forceinline__ unsigned long long staged_to_key(unsigned long long st) {
+    return ((unsigned long long)score_key(__uint_as_float((uint32_t)(st >> 32))) << 32) | (st & 0xFFFFFFFFull);
+}
+
+// exact fallback on the registers of one wavefront: radix selection on the score keys, two bits per step
+template <int VEC>
+__device__ __noinline__ void select_row_radix_wave(const float (&sc)[VEC * 4], int V, int m, uint32_t flat0, unsigned long long *stage) {
+    const int lane = threadIdx.x % 64;
+    uint32_t k_and = 0xFFFFFFFFu, k_or = 0u;
+#pragma unroll
+    for (int i = 0; i < VEC * 4; i++)
+        if (((i / 4) * 64 + lane) * 4 < V) { const uint32_t k = score_key(sc[i]); k_and &= k; k_or |= k; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { k_and &= __shfl_xor(k_and, o, 64); k_or |= __shfl_xor(k_or, o, 64); }
+    const uint32_t diff = k_and ^ k_or;
+    uint32_t decided = 0xFFFFFFFFu, prefix = k_and;
+    int krem = m, active = V;
+    if (diff != 0) {
+        const int top = 31 - __clz(diff);
+        decided = ~((2u << top) - 1u);  // top == 31 gives 0
+        prefix = k_and & decided;
+        for (int shb = top & ~1; shb >= 0; shb -= 2) {
+            uint32_t c12 = 0, c3 = 0;  // active keys with digit >= 1 (low half), >= 2 (high half), >= 3
+#pragma unroll
+            for (int i = 0; i < VEC * 4; i++) {
+                const uint32_t k = score_key(sc[i]);
+                const uint32_t d = (k >> shb) & 3u;
+                const uint32_t act = (((k ^ prefix) & decided) == 0u && ((i / 4) * 64 + lane) * 4 < V) ? 1u : 0u;
+                c12 += (d >= 1u ? act : 0u) + (d >= 2u ? (act << 16) : 0u);
+                c3 += d >= 3u ? act : 0u;
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) { c12 += __shfl_xor(c12, o, 64); c3 += __shfl_xor(c3, o, 64); }
+            const int C1 = (int)(c12 & 0xFFFFu), C2 = (int)(c12 >> 16), C3 = (int)c3;
+            uint32_t dsel;
+            if (C3 >= krem) { dsel = 3; active = C3; }
+            else if (C2 >= krem) { dsel = 2; krem -= C3; active = C2 - C3; }
+            else if (C1 >= krem) { dsel = 1; krem -= C2; active = C1 - C2; }
+            else { dsel = 0; krem -= C1; active = active - C1; }
+            prefix |= dsel << shb;
+            decided |= 3u << shb;
+            if (active == krem) break;  // every key still active is taken
+        }
+    }
+    // (key & decided) > prefix: above the threshold; == prefix: `active` keys tie there and the krem lowest tokens are taken.
+    // Tokens ascend with (j, lane, e), so a tie's rank is the count of ties in earlier j, in lower lanes of this j, and in lower e.
+    const int n_gt = m - krem;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    int base_gt = 0, base_eq = 0;
+#pragma unroll
+    for (int j = 0; j < VEC; j++) {
+        int my_eq = 0;
+        bool gt[4], eq[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const bool ok = (j * 64 + lane) * 4 < V;
+            const uint32_t kk = score_key(sc[j * 4 + e]) & decided;
+            gt[e] = ok && kk > prefix;
+            eq[e] = ok && kk == prefix;
+            my_eq += eq[e] ? 1 : 0;
+        }
+        int incl = my_eq;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(incl, o, 64); if (lane >= o) incl += t; }
+        int rank = base_eq + incl - my_eq;
+        base_eq += __shfl(incl, 63, 64);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const unsigned long long mg = __ballot(gt[e]);
+            const uint32_t flat = flat0 + (uint32_t)((j * 64 + lane) * 4 + e);
+            const unsigned long long st = ((unsigned long long)__float_as_uint(sc[j * 4 + e] + 0.0f) << 32) | (0xFFFFFFFFu - flat);
+            if (gt[e]) stage[base_gt + __popcll(mg & lt_mask)] = st;
+            base_gt += __popcll(mg);
+            if (eq[e]) { if (rank < krem) stage[n_gt + rank] = st; rank++; }
+        }
+    }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restrict__ logits, const float *__restrict__ cum, int64_t rows,
+                                                          int n, int V, int m, unsigned long long *__restrict__ cand) {
+    extern __shared__ unsigned long long wave_lds[];  // per wavefront: 512 slots of histogram / list, then m slots of staged output
+    const int lane = threadIdx.x % 64, wv = threadIdx.x / 64;
+    const int64_t row = (int64_t)blockIdx.x * 4 + wv;
+    if (row >= rows) return;  // whole wavefronts leave; nothing below synchronises across wavefronts
+    unsigned long long *list = wave_lds + (size_t)wv * (512 + m);
+    int *hist = (int *)list;
+    unsigned long long *stage = list + 512;
+    const floatx4 *z4 = (const floatx4 *)(logits + row * (int64_t)V);
+    const float c = cum ? cum[row] : 0.0f;
+
+    float x[VEC * 4];
+    float mx = -INFINITY, mn = INFINITY;
+#pragma unroll
+    for (int j = 0; j < VEC; j++) {
+        const int q = j * 64 + lane;
+        floatx4 v = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        if (q * 4 < V) v = z4[q];
+#pragma unroll
+        for (int e = 0; e < 4; e++) x[j * 4 + e] = v[e];
+    }
+#pragma unroll
+    for (int i = 0; i < VEC * 4; i++) {
+        mx = fmaxf(mx, x[i]);
+        mn = fminf(mn, ((i / 4) * 64 + lane) * 4 < V ? x[i] : INFINITY);
+    }
+    mx = wave_max(mx);
+    mn = -wave_max(-mn);
+    const float mxl = mx * 1.4426950408889634f;
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < VEC * 4; i++) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(x[i], 1.4426950408889634f, -mxl));  // padding gives 0
+    const float lse = mx + __logf(wave_sum(sum));
+#pragma unroll
+    for (int i = 0; i < VEC * 4; i++) x[i] = c + (x[i] - lse);  // scores from here on (padding stays -inf)
+
+    unsigned long long *dst = cand + row * (int64_t)m;
+    const uint32_t flat0 = (uint32_t)((row % n) * (int64_t)V);
+    if (m >= V) {  // nothing to cut: every token is a candidate
+#pragma unroll
+        for (int j = 0; j < VEC; j++)
+            if ((j * 64 + lane) * 4 < V) {
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const int v = (j * 64 + lane) * 4 + e;
+                    dst[v] = pack_candidate(x[j * 4 + e], flat0 + (uint32_t)v);
+                }
+            }
+        return;
+    }
+    // 1. histogram of the scores over equal-width bins of [lo, hi]; the bin index is monotone in the score
+    const float lo = c + (mn - lse), hi = c + (mx - lse);
+    const float inv_w = (hi > lo) ? ((float)WROW_BINS - 0.01f) / (hi - lo) : 0.0f;
+    const float k0 = -lo * inv_w;
+#pragma unroll
+    for (int i = 0; i < 4; i++) ((int4 *)hist)[i * 64 + lane] = make_int4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < VEC * 4; i++) {
+        const uint32_t bi = min((uint32_t)__builtin_fmaf(x[i], inv_w, k0), (uint32_t)(WROW_BINS - 1));  // negative and NaN convert to 0
+        if (((i / 4) * 64 + lane) * 4 < V) atomicAdd(&hist[bi], 1);
+    }
+    // 2. lane l owns bins 1023-16l .. 1008-16l; inclusive scan from the top bin down finds the bin T of the m-th best score
+    int h[16];
+    {
+        const int4 *hp = (const int4 *)(hist + WROW_BINS - 16 - 16 * lane);
+#pragma unroll
+        for (int i = 0; i < 4; i++) { const int4 t = hp[i]; h[4 * i] = t.x; h[4 * i + 1] = t.y; h[4 * i + 2] = t.z; h[4 * i + 3] = t.w; }
+    }
+    int mine = 0;
+#pragma unroll
+    for (int i = 0; i < 16; i++) mine += h[i];
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(incl, o, 64); if (lane >= o) incl += t; }
+    int above = incl - mine, selT = 0, selK = 0, selC = 0;
+    const bool owner = above < m && incl >= m;
+    if (owner) {
+#pragma unroll
+        for (int i = 15; i >= 0; i--) {  // h[15] is this lane's top bin
+            if (selC == 0 && above + h[i] >= m) { selT = WROW_BINS - 16 - 16 * lane + i; selK = m - above; selC = h[i]; }
+            if (selC == 0) above += h[i];
+        }
+    }
+    const int src_lane = __ffsll((long long)__ballot(owner)) - 1;
+    const int T = __shfl(selT, src_lane, 64), krem = __shfl(selK, src_lane, 64), cntT = __shfl(selC, src_lane, 64);
+    if (cntT > WROW_LIST) {  // crowded threshold bin (e.g. all logits equal): exact radix selection
+        float sc[VEC * 4];  // a copy, so that only this branch keeps the scores in addressable memory
+#pragma unroll
+        for (int i = 0; i < VEC * 4; i++) sc[i] = x[i];
+        select_row_radix_wave<VEC>(sc, V, m, flat0, stage);
+    } else {
+        // 3. bins above T go straight to the staged output, bin T to the list (over the dead histogram) for exact ranking
+        const int n_gt = m - krem;
+        int base_gt = 0, base_eq = 0;
+        const uint32_t nflat = 0xFFFFFFFFu - flat0 - (uint32_t)lane * 4u;
+        // The bins are recomputed, not kept: opaque copies of the two constants stop the compiler from holding
+        // all VEC*4 bin indices of the histogram pass in registers until here.
+        float inv_w2 = inv_w, k02 = k0;
+        asm volatile("" : "+v"(inv_w2), "+v"(k02));
+#pragma unroll
+        for (int i = 0; i < VEC * 4; i++) {
+            const int bi = (int)min((uint32_t)__builtin_fmaf(x[i], inv_w2, k02), (uint32_t)(WROW_BINS - 1));
+            const bool ok = ((i / 4) * 64 + lane) * 4 < V;
+            const bool gt = ok && bi > T, eq = ok && bi == T;
+            const unsigned long long mg = __ballot(gt), me = __ballot(eq);
+            const unsigned long long st = ((unsigned long long)__float_as_uint(x[i] + 0.0f) << 32) | (nflat - (uint32_t)((i / 4) * 256 + (i % 4)));
+            if (gt) stage[base_gt + __builtin_amdgcn_mbcnt_hi((uint32_t)(mg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mg, 0))] = st;
+            base_gt += __popcll(mg);
+            if (me != 0) {
+                if (eq) list[base_eq + __builtin_amdgcn_mbcnt_hi((uint32_t)(me >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)me, 0))] = st;
+                base_eq += __popcll(me);
+            }
+        }
+        // rank every listed candidate among the cntT listed ones; the krem best go out
+        for (int i = lane; i < cntT; i += 64) {
+            const unsigned long long st = list[i], key = staged_to_key(st);
+            int rank = 0;
+            for (int q = 0; q < cntT; q++) rank += staged_to_key(list[q]) > key ? 1 : 0;
+            if (rank < krem) stage[n_gt + rank] = st;
+        }
+    }
+    for (int i = lane; i < m; i += 64) dst[i] = staged_to_key(stage[i]);
+}
+
+// ---------------------------------------------------------------------------
 // stage B: one workgroup per request
 // ---------------------------------------------------------------------------
 #define SELB_THREADS 1024
@@ -403,6 +623,22 @@ __global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned lo
 
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// 0: pick the kernel by shape; 1: always the workgroup-per-row kernel (GR4AD_SELECT_MODE, for comparisons)
+static int g_select_mode = getenv("GR4AD_SELECT_MODE") ? atoi(getenv("GR4AD_SELECT_MODE")) : 0;
+
+template <int VEC>
+static int launch_rows_wave(unsigned grid, size_t lds, hipStream_t st, const float *logits, const float *cum, int64_t rows, int n, int V,
+                            int m, unsigned long long *cand) {
+    auto kern = select_rows_wave<VEC>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (512 + GR4AD_MAX_BEAM) * 8) != hipSuccess) return GR4AD_EHIP;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, logits, cum, rows, n, V, m, cand);
+    return GR4AD_OK;
+}
+
 size_t select_workspace_bytes(int B, int n, int V, int k) {
     int m = k < V ? k : V;
     return align256((size_t)B * n * m * sizeof(unsigned long long));
@@ -419,15 +655,27 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
     {
         ProfScope ps(KC_SELECT_ROWS, st, 0.0, (double)rows * V * 4 + (double)rows * (k < V ? k : V) * 8);
         unsigned long long *cand = (unsigned long long *)ws;
-        const size_t stage_bytes = (size_t)m * sizeof(unsigned long long);  // <= 32 KB (GR4AD_MAX_BEAM)
-        if (V <= 1024)
-            hipLaunchKernelGGL(select_rows<4>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
-        else if (V <= 4096)
-            hipLaunchKernelGGL(select_rows<16>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
-        else if (V <= 8192)
-            hipLaunchKernelGGL(select_rows<32>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
-        else
-            hipLaunchKernelGGL(select_rows<64>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
+        if (V <= 8192 && V % 4 == 0 && ((uintptr_t)logits % 16) == 0 && g_select_mode != 1) {
+            // one wavefront per row, four rows per workgroup
+            const size_t lds = 4 * (size_t)(512 + m) * sizeof(unsigned long long);  // <= 4 * (4 KB + 32 KB)
+            const unsigned grid = (unsigned)ceil_div64(rows, 4);
+            int s = GR4AD_OK;
+            if (V <= 1024) s = launch_rows_wave<4>(grid, lds, st, logits, cum, rows, n, V, m, cand);
+            else if (V <= 2048) s = launch_rows_wave<8>(grid, lds, st, logits, cum, rows, n, V, m, cand);
+            else if (V <= 4096) s = launch_rows_wave<16>(grid, lds, st, logits, cum, rows, n, V, m, cand);
+            else s = launch_rows_wave<32>(grid, lds, st, logits, cum, rows, n, V, m, cand);
+            if (s) return s;
+        } else {
+            const size_t stage_bytes = (size_t)m * sizeof(unsigned long long);  // <= 32 KB (GR4AD_MAX_BEAM)
+            if (V <= 1024)
+                hipLaunchKernelGGL(select_rows<4>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
+            else if (V <= 4096)
+                hipLaunchKernelGGL(select_rows<16>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
+            else if (V <= 8192)
+                hipLaunchKernelGGL(select_rows<32>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
+            else
+                hipLaunchKernelGGL(select_rows<64>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
+        }
     }
     GR4AD_LAUNCH_CHECK();
     ProfScope ps(KC_SELECT_REQUEST, st, 0.0, (double)rows * m * 8 + (double)B * k * 12);
