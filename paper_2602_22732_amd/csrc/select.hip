@@ -384,7 +384,8 @@ __device__ __noinline__ void select_row_radix_wave(const float (&sc)[VEC * 4], i
     }
 }
 
-template <int VEC>
+// FULL: V == VEC*256, every register holds a token (the validity tests fold away)
+template <int VEC, bool FULL>
 __global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restrict__ logits, const float *__restrict__ cum, int64_t rows,
                                                           int n, int V, int m, unsigned long long *__restrict__ cand) {
     extern __shared__ unsigned long long wave_lds[];  // per wavefront: 512 slots of histogram / list, then m slots of staged output
@@ -403,14 +404,14 @@ __global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restri
     for (int j = 0; j < VEC; j++) {
         const int q = j * 64 + lane;
         floatx4 v = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-        if (q * 4 < V) v = z4[q];
+        if (FULL || q * 4 < V) v = z4[q];
 #pragma unroll
         for (int e = 0; e < 4; e++) x[j * 4 + e] = v[e];
     }
 #pragma unroll
     for (int i = 0; i < VEC * 4; i++) {
         mx = fmaxf(mx, x[i]);
-        mn = fminf(mn, ((i / 4) * 64 + lane) * 4 < V ? x[i] : INFINITY);
+        mn = fminf(mn, (FULL || ((i / 4) * 64 + lane) * 4 < V) ? x[i] : INFINITY);
     }
     mx = wave_max(mx);
     mn = -wave_max(-mn);
@@ -427,7 +428,7 @@ __global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restri
     if (m >= V) {  // nothing to cut: every token is a candidate
 #pragma unroll
         for (int j = 0; j < VEC; j++)
-            if ((j * 64 + lane) * 4 < V) {
+            if (FULL || (j * 64 + lane) * 4 < V) {
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
                     const int v = (j * 64 + lane) * 4 + e;
@@ -445,7 +446,7 @@ __global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restri
 #pragma unroll
     for (int i = 0; i < VEC * 4; i++) {
         const uint32_t bi = min((uint32_t)__builtin_fmaf(x[i], inv_w, k0), (uint32_t)(WROW_BINS - 1));  // negative and NaN convert to 0
-        if (((i / 4) * 64 + lane) * 4 < V) atomicAdd(&hist[bi], 1);
+        if (FULL || ((i / 4) * 64 + lane) * 4 < V) atomicAdd(&hist[bi], 1);
     }
     // 2. lane l owns bins 1023-16l .. 1008-16l; inclusive scan from the top bin down finds the bin T of the m-th best score
     int h[16];
@@ -488,7 +489,7 @@ __global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restri
 #pragma unroll
         for (int i = 0; i < VEC * 4; i++) {
             const int bi = (int)min((uint32_t)__builtin_fmaf(x[i], inv_w2, k02), (uint32_t)(WROW_BINS - 1));
-            const bool ok = ((i / 4) * 64 + lane) * 4 < V;
+            const bool ok = FULL || ((i / 4) * 64 + lane) * 4 < V;
             const bool gt = ok && bi > T, eq = ok && bi == T;
             const unsigned long long mg = __ballot(gt), me = __ballot(eq);
             const unsigned long long st = ((unsigned long long)__float_as_uint(x[i] + 0.0f) << 32) | (nflat - (uint32_t)((i / 4) * 256 + (i % 4)));
@@ -626,10 +627,10 @@ static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 // 0: pick the kernel by shape; 1: always the workgroup-per-row kernel (GR4AD_SELECT_MODE, for comparisons)
 static int g_select_mode = getenv("GR4AD_SELECT_MODE") ? atoi(getenv("GR4AD_SELECT_MODE")) : 0;
 
-template <int VEC>
-static int launch_rows_wave(unsigned grid, size_t lds, hipStream_t st, const float *logits, const float *cum, int64_t rows, int n, int V,
-                            int m, unsigned long long *cand) {
-    auto kern = select_rows_wave<VEC>;
+template <int VEC, bool FULL>
+static int launch_rows_wave_kind(unsigned grid, size_t lds, hipStream_t st, const float *logits, const float *cum, int64_t rows, int n,
+                                 int V, int m, unsigned long long *cand) {
+    auto kern = select_rows_wave<VEC, FULL>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (512 + GR4AD_MAX_BEAM) * 8) != hipSuccess) return GR4AD_EHIP;
@@ -637,6 +638,12 @@ static int launch_rows_wave(unsigned grid, size_t lds, hipStream_t st, const flo
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, logits, cum, rows, n, V, m, cand);
     return GR4AD_OK;
+}
+template <int VEC>
+static int launch_rows_wave(unsigned grid, size_t lds, hipStream_t st, const float *logits, const float *cum, int64_t rows, int n, int V,
+                            int m, unsigned long long *cand) {
+    if (V == VEC * 256) return launch_rows_wave_kind<VEC, true>(grid, lds, st, logits, cum, rows, n, V, m, cand);
+    return launch_rows_wave_kind<VEC, false>(grid, lds, st, logits, cum, rows, n, V, m, cand);
 }
 
 size_t select_workspace_bytes(int B, int n, int V, int k) {
