@@ -95,33 +95,37 @@ __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16 *__restrict
     }
 }
 
-// One workgroup: NW wavefronts x QT tiles of 32 beams of one (request, head).  Per 64-key
-// tile of the context the workgroup stages K [64 x DH] and V^T [DH x 64] in LDS once and
-// every beam of the block reuses them.  Both products are computed transposed,
+// One workgroup: NW wavefronts x QT tiles of 32 beams of one (request, head).  The context streams through LDS
+// in macro-tiles of SUBS x 64 keys (K [64 x DH] and V^T [DH x 64] per 64 keys), two macro-tiles double-buffered,
+// filled by direct global->LDS loads (no staging registers) one whole macro-tile ahead; every beam of the block
+// reuses them.  The workgroup meets at a barrier once per macro-tile only: in between, the two wavefronts that
+// share a SIMD drift apart, so one's softmax (vector instructions, the larger part) overlaps the other's MFMAs.
+// Both products are computed transposed,
 //   S^T = K Q^T  (keys x beams)   and   O^T = V^T P^T  (head dims x beams),
 // so that each lane owns one beam: its running max / sum are lane-local, P^T leaves the
 // accumulators of the first product already in the operand layout of the second, and the
 // only cross-lane step is one exchange between the two half-waves.  Key rows enter the
 // first product with index bits 2 and 3 swapped, which makes the 8 keys a lane holds for
 // one MFMA k-step consecutive (one 16-byte chunk of a V^T row).
-template <int DH, int QT, int NW>
+template <int DH, int QT, int NW, int SUBS>
 __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__restrict__ q, int64_t ldq, const bf16 *__restrict__ kv,
                                                                  const bf16 *__restrict__ vt, const int32_t *__restrict__ ctx_len,
                                                                  bf16 *__restrict__ out, int64_t ldo, int n, int S, int Spad, int d,
                                                                  int H, float scale_log2e) {
-    constexpr int NTH = NW * 64;
     constexpr int KCH = DH / 8;                   // 16-byte chunks per K row
     constexpr int K_CHUNKS = 64 * KCH, V_CHUNKS = DH * 8;
-    constexpr int STAGE = K_CHUNKS + V_CHUNKS;
-    constexpr int PER_THREAD = (STAGE + NTH - 1) / NTH;
+    constexpr int STAGE = K_CHUNKS + V_CHUNKS;    // one 64-key tile
+    constexpr int MACRO = SUBS * STAGE;
     constexpr int KSTEPS = DH / 16, MT = DH / 32;
-    __shared__ bf16x8 smem[2 * STAGE];
-    const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+    extern __shared__ bf16x8 smem[];              // 2 * MACRO chunks
+    const int tid = threadIdx.x, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
     const int b = blockIdx.z, h = blockIdx.y;
     const int frow = lane % 32, hf = lane / 32;
     int len = ctx_len ? ctx_len[b] : S;
     len = len < 1 ? 1 : (len > S ? S : len);
     const int ntiles = (len + 63) / 64;
+    const int nmacro = (ntiles + SUBS - 1) / SUBS;
     const int q0 = (blockIdx.x * NW + wave) * (QT * 32);
 
     // query fragments stay in registers for the whole kernel
@@ -135,35 +139,36 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
         for (int s = 0; s < KSTEPS; s++) qf[qt][s] = *(const bf16x8 *)(qr + 16 * s + 8 * hf);
     }
 
-    // staging of one key tile: chunk ids [0, K_CHUNKS) are K, the rest V^T
+    // loads of one macro-tile: per 64-key tile, K_CHUNKS/64 wave loads of K rows and V_CHUNKS/64 of V^T rows, dealt round-robin
+    // to the wavefronts.  A wave load fills 64 consecutive 16-byte slots; slot p of row r holds chunk p ^ swizzle(r), applied on
+    // the global side.  Keys past the context end re-read its last row (masked later); V^T is zero beyond the length.
     const bf16 *kbase = kv + (int64_t)b * S * 2 * d + h * DH;
     const bf16 *vbase = vt + ((int64_t)b * d + h * DH) * Spad;
-    bf16x8 stage_reg[PER_THREAD];
-    auto load_tile = [&](int tile) {
+    auto issue_macro = [&](int macro, int buf) {
+        constexpr int KI = K_CHUNKS / 64, VI = V_CHUNKS / 64, PER_TILE = KI + VI;
 #pragma unroll
-        for (int i = 0; i < PER_THREAD; i++) {
-            const int id = tid + i * NTH;
-            if (id < K_CHUNKS) {
-                int key = tile * 64 + id / KCH;
-                if (key > S - 1) key = S - 1;  // stays inside the buffer; masked below
-                stage_reg[i] = *(const bf16x8 *)(kbase + (int64_t)key * 2 * d + (id % KCH) * 8);
-            } else if (id < STAGE) {
-                const int v = id - K_CHUNKS;
-                stage_reg[i] = *(const bf16x8 *)(vbase + (int64_t)(v / 8) * Spad + tile * 64 + (v % 8) * 8);
-            }
-        }
-    };
-    auto store_tile = [&](int stage) {
-        bf16x8 *sk = smem + stage * STAGE, *sv = sk + K_CHUNKS;
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; i++) {
-            const int id = tid + i * NTH;
-            if (id < K_CHUNKS) {
-                const int r = id / KCH, c = id % KCH;
-                sk[r * KCH + (c ^ ((KCH == 8 ? (r >> 1) : (r >> 2)) & (KCH - 1)))] = stage_reg[i];
-            } else if (id < STAGE) {
-                const int v = id - K_CHUNKS, r = v / 8, c = v % 8;
-                sv[r * 8 + (c ^ ((r >> 1) & 7))] = stage_reg[i];
+        for (int i = 0; i < (SUBS * PER_TILE + NW - 1) / NW; i++) {
+            const int idx = i * NW + wave;  // wave-uniform
+            const int sub = idx / PER_TILE, w = idx % PER_TILE;
+            const int tile = macro * SUBS + sub;
+            if (idx < SUBS * PER_TILE && tile < ntiles) {
+                bf16x8 *dst = smem + buf * MACRO + sub * STAGE;
+                const bf16 *src;
+                if (w < KI) {
+                    const int id = w * 64 + lane, r = id / KCH, pslot = id % KCH;
+                    const int c = pslot ^ ((KCH == 8 ? (r >> 1) : (r >> 2)) & (KCH - 1));
+                    int key = tile * 64 + r;
+                    if (key > S - 1) key = S - 1;
+                    src = kbase + (int64_t)key * 2 * d + c * 8;
+                    dst += w * 64;
+                } else {
+                    const int id = (w - KI) * 64 + lane, r = id / 8, pslot = id % 8;
+                    const int c = pslot ^ ((r >> 1) & 7);
+                    src = vbase + (int64_t)r * Spad + tile * 64 + c * 8;
+                    dst += K_CHUNKS + (w - KI) * 64;
+                }
+                __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)src,
+                                                 (void __attribute__((address_space(3))) *)dst, 16, 0, 0);
             }
         }
     };
@@ -182,12 +187,21 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
     // key row read by this lane in the first product: bits 2 and 3 of the row index swapped
     const int krow = (frow & 0x13) | ((frow & 4) << 1) | ((frow & 8) >> 1);
 
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
+    issue_macro(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (nmacro > 1) issue_macro(1, 1);
     for (int tile = 0; tile < ntiles; tile++) {
-        if (tile + 1 < ntiles) load_tile(tile + 1);
-        const bf16x8 *sk = smem + (tile & 1) * STAGE, *sv = sk + K_CHUNKS;
+        const int macro = tile / SUBS, sub_tile = tile % SUBS;
+        if (sub_tile == 0 && macro > 0) {
+            // the previous macro-tile is read out and this wave's share of the current one has landed: meet, then refill the free buffer
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (macro + 1 < nmacro) issue_macro(macro + 1, (macro + 1) & 1);
+        }
+        const bf16x8 *sk = smem + (macro & 1) * MACRO + sub_tile * STAGE, *sv = sk + K_CHUNKS;
         floatx16 s[QT][2];
 #pragma unroll
         for (int sub = 0; sub < 2; sub++) {
@@ -259,8 +273,6 @@ __global__ __launch_bounds__(NW * 64) void cross_attn_flash_bf16(const bf16 *__r
 #pragma unroll
                 for (int qt = 0; qt < QT; qt++) o[qt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][ks], o[qt][mt], 0, 0, 0);
             }
-        if (tile + 1 < ntiles) store_tile((tile + 1) & 1);
-        __syncthreads();
     }
 #pragma unroll
     for (int qt = 0; qt < QT; qt++) {
@@ -301,16 +313,22 @@ int launch_cross_attention_prepare(gr4ad_dtype dtype, const void *kv, const int3
     return GR4AD_OK;
 }
 
-template <int DH, int QT, int NW>
+template <int DH, int QT, int NW, int SUBS>
 static int launch_flash(const bf16 *q, int64_t ldq, const bf16 *kv, const bf16 *vt, const int32_t *ctx_len, bf16 *out, int64_t ldo, int B,
                         int n, int S, int d, int H, hipStream_t st) {
+    auto kern = cross_attn_flash_bf16<DH, QT, NW, SUBS>;
+    constexpr int LDS_BYTES = 2 * SUBS * (64 * (DH / 8) + DH * 8) * 16;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) return GR4AD_EHIP;
+        attr_done = true;
+    }
     const int per_block = NW * QT * 32;
     dim3 grid((n + per_block - 1) / per_block, H, B);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
     // flops on the padded length S; bytes: queries and outputs once, keys and values once per request (beam-shared)
     ProfScope ps(KC_XATTN_FLASH, st, 4.0 * B * (double)n * S * d, (2.0 * B * n * d + 2.0 * B * (double)S * d) * sizeof(bf16));
-    hipLaunchKernelGGL((cross_attn_flash_bf16<DH, QT, NW>), grid, dim3(NW * 64), 0, st, q, ldq, kv, vt, ctx_len, out, ldo, n, S,
-                       (S + 63) / 64 * 64, d, H, scale_log2e);
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), LDS_BYTES, st, q, ldq, kv, vt, ctx_len, out, ldo, n, S, (S + 63) / 64 * 64, d, H, scale_log2e);
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }
@@ -325,13 +343,13 @@ int launch_cross_attention(gr4ad_dtype dtype, const void *q, int64_t ldq, const 
         const bf16 *qq = (const bf16 *)q, *kk = (const bf16 *)kv, *vv = (const bf16 *)vt;
         bf16 *oo = (bf16 *)out;
         if (dh == 64) {
-            if (n <= 128) return launch_flash<64, 1, 4>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
-            if (n <= 256) return launch_flash<64, 2, 4>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
-            return launch_flash<64, 2, 8>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+            if (n <= 128) return launch_flash<64, 1, 4, 2>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+            if (n <= 256) return launch_flash<64, 2, 4, 2>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+            return launch_flash<64, 2, 8, 4>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
         } else {
-            if (n <= 128) return launch_flash<32, 1, 4>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
-            if (n <= 256) return launch_flash<32, 2, 4>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
-            return launch_flash<32, 2, 8>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+            if (n <= 128) return launch_flash<32, 1, 4, 2>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+            if (n <= 256) return launch_flash<32, 2, 4, 2>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+            return launch_flash<32, 2, 8, 4>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
         }
     }
     const int64_t rows = (int64_t)B * n;
