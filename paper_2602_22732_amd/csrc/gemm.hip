@@ -289,13 +289,16 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
     const int64_t xcd_end = (xcd + 1) * per_xcd < total ? (xcd + 1) * per_xcd : total;
     int64_t L = xcd * per_xcd + wslot;
     if (L >= xcd_end) return;
-    const int64_t gsz = (int64_t)group_m * tiles_n;
-    auto tile_coords = [&](int64_t l, int64_t &m0, int &n0) {
-        const int64_t grp = l / gsz, in = l % gsz;
-        const int64_t first_m = grp * group_m;
-        const int64_t gm = tiles_m - first_m < group_m ? tiles_m - first_m : group_m;
-        m0 = (first_m + in % gm) * 256;
-        n0 = (int)(in / gm) * 256;
+    const uint32_t gsz = (uint32_t)group_m * (uint32_t)tiles_n;
+    auto tile_coords = [&](int64_t l64, int64_t &m0, int &n0) {  // fewer than 2^31 tiles: 32-bit division
+        const uint32_t l = (uint32_t)l64;
+        const uint32_t grp = l / gsz, in = l - grp * gsz;
+        const uint32_t first_m = grp * (uint32_t)group_m;
+        const uint32_t left = (uint32_t)tiles_m - first_m;
+        const uint32_t gm = left < (uint32_t)group_m ? left : (uint32_t)group_m;
+        const uint32_t nn = in / gm;
+        m0 = (int64_t)(first_m + (in - nn * gm)) * 256;
+        n0 = (int)nn * 256;
     };
 
     // ---- loads: load j of this wave fills rows (wave*4+j)*8 .. +7 of a half-tile, lane -> row lane/8, position lane%8.
@@ -459,7 +462,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                         const int64_t row = wrow0 + pass * 64 + r;
                         const int col = wcol0 + c * 8;
                         if (row < M && col < N) {
-                            if (col + 7 < N) *(bf16x8 *)((bf16 *)epi.C + row * epi.ldc + col) = x;
+                            if (col + 7 < N) __builtin_nontemporal_store(x, (bf16x8 *)((bf16 *)epi.C + row * epi.ldc + col));  // C streams out: not re-read before it leaves the caches
                             else for (int e = 0; e < 8 && col + e < N; e++) ((bf16 *)epi.C)[row * epi.ldc + col + e] = x[e];
                         }
                     }
@@ -493,7 +496,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                                 if (KIND == EPI_F32 && epi.bias) add = *(const floatx4 *)(epi.bias + col);
                                 if (KIND == EPI_F32_RESID) add = *(const floatx4 *)(epi.resid + row * epi.ldr + col);
                                 if (KIND == EPI_F32_TABLE) add = *(const floatx4 *)(epi.table + (epi.tok ? (int64_t)epi.tok[row] : 0) * N + col);
-                                *(floatx4 *)((float *)epi.C + row * epi.ldc + col) = x + add;
+                                __builtin_nontemporal_store(x + add, (floatx4 *)((float *)epi.C + row * epi.ldc + col));
                             } else {
                                 for (int e = 0; e < 4 && col + e < N; e++) {
                                     float y = x[e];
@@ -546,6 +549,7 @@ static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
     const int64_t tiles_m = ceil_div64(M, 256);
     const int tiles_n = (N + 255) / 256;
     const int64_t total = tiles_m * tiles_n;
+    if (total > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
     // one workgroup per compute unit (the ring takes the whole LDS), a multiple of the 8 XCDs
     int64_t grid = n_cu / 8 * 8;
     if (grid < 8) grid = 8;
