@@ -532,6 +532,87 @@ __device__ __forceinline__ void bitonic_sort_desc(unsigned long long *s, int n_p
         }
 }
 
+// every key of a request's candidate list, 16 bytes per lane and four loads in flight (the list is streamed several times)
+template <typename F>
+__device__ __forceinline__ void for_each_key(const unsigned long long *__restrict__ src, int64_t ncand, F f) {
+    const int tid = threadIdx.x;
+    if ((((uintptr_t)src) & 15) == 0) {
+        const ulonglong2 *src2 = (const ulonglong2 *)src;
+        const int64_t pairs = ncand / 2;
+        int64_t i = tid;
+        for (; i + 3 * SELB_THREADS < pairs; i += 4 * SELB_THREADS) {
+            const ulonglong2 a = src2[i], b = src2[i + SELB_THREADS], c = src2[i + 2 * SELB_THREADS], d = src2[i + 3 * SELB_THREADS];
+            f(a.x); f(a.y); f(b.x); f(b.y); f(c.x); f(c.y); f(d.x); f(d.y);
+        }
+        for (; i < pairs; i += SELB_THREADS) { const ulonglong2 a = src2[i]; f(a.x); f(a.y); }
+        if ((ncand & 1) && tid == 0) f(src[ncand - 1]);
+    } else {
+        for (int64_t i = tid; i < ncand; i += SELB_THREADS) f(src[i]);
+    }
+}
+
+// Usual path of stage B: two sweeps over the candidates.  A sample of one key per thread gives the span of the score bits;
+// the first sweep counts the keys in 2048 equal bins of that span (keys outside it fall into the end bins; the bin index is
+// monotone in the key, and the counts spread over the bins, unlike the leading radix digit, which most keys of a request
+// share), the second collects every key from the threshold bin up into LDS, where a sort finishes the job.  Returns false,
+// having selected nothing, when more than SELB_SORT_MAX keys lie from the threshold bin up (the exact radix selection then runs).
+__device__ __forceinline__ bool select_request_binned(const unsigned long long *__restrict__ src, int64_t ncand, int k,
+                                                      unsigned long long *skeys, int *hist, int *wave_tot, int *sel_digit, int *sel_krem,
+                                                      int *sel_cnt, int *out_cnt) {
+    const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
+    const uint32_t smp = (uint32_t)(src[(int64_t)tid * ncand / SELB_THREADS] >> 32);
+    uint32_t smax = smp, smin = smp;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { smax = max(smax, (uint32_t)__shfl_xor((int)smax, o, 64)); smin = min(smin, (uint32_t)__shfl_xor((int)smin, o, 64)); }
+    if (lane == 0) { wave_tot[wv] = (int)smax; hist[wv] = (int)smin; }
+    __syncthreads();
+    for (int q = 0; q < SELB_THREADS / 64; q++) { smax = max(smax, (uint32_t)wave_tot[q]); smin = min(smin, (uint32_t)hist[q]); }
+    __syncthreads();
+    int nsh = 0;
+    while (((smax - smin) >> nsh) >= 2040u) nsh++;
+    const long long base = (long long)smin;
+    auto digit = [&](unsigned long long key) {
+        const long long d = ((((long long)(key >> 32)) - base) >> nsh) + 4;  // floor, also below the sampled minimum
+        return (int)(d < 0 ? 0 : (d > 2047 ? 2047 : d));
+    };
+    for (int i = tid; i < 2048; i += SELB_THREADS) hist[i] = 0;
+    if (tid == 0) *out_cnt = 0;
+    __syncthreads();
+    for_each_key(src, ncand, [&](unsigned long long key) { atomicAdd(&hist[digit(key)], 1); });
+    __syncthreads();
+    // thread t owns digits 2047-2t (hi) and 2046-2t (lo); scan from the top digit down
+    const int hi = hist[2047 - 2 * tid], lo = hist[2046 - 2 * tid];
+    int v = hi + lo;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int t = __shfl_up(v, o, 64);
+        if (lane >= o) v += t;
+    }
+    if (lane == 63) wave_tot[wv] = v;
+    __syncthreads();
+    int add = 0;
+    for (int q = 0; q < wv; q++) add += wave_tot[q];
+    const int incl = v + add, excl = incl - hi - lo;
+    if (excl < k && incl >= k) {
+        if (excl + hi >= k) { *sel_digit = 2047 - 2 * tid; *sel_krem = k - excl; *sel_cnt = hi; }
+        else { *sel_digit = 2046 - 2 * tid; *sel_krem = k - excl - hi; *sel_cnt = lo; }
+    }
+    __syncthreads();
+    const int T = *sel_digit, total_ge = (k - *sel_krem) + *sel_cnt;
+    __syncthreads();
+    if (total_ge > SELB_SORT_MAX) return false;  // uniform: every thread read the same shared values
+    int np = 1;
+    while (np < total_ge) np <<= 1;
+    for (int i = tid; i < np; i += SELB_THREADS) skeys[i] = 0ull;
+    __syncthreads();
+    for_each_key(src, ncand, [&](unsigned long long key) {
+        if (digit(key) >= T) skeys[atomicAdd(out_cnt, 1)] = key;  // exactly total_ge keys qualify
+    });
+    __syncthreads();
+    bitonic_sort_desc(skeys, np);
+    return true;
+}
+
 __global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned long long *__restrict__ cand, int64_t ncand, int V, int k,
                                                                int32_t *__restrict__ parent, int32_t *__restrict__ tok,
                                                                float *__restrict__ score, const int32_t *__restrict__ sid_old,
@@ -552,6 +633,8 @@ __global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned lo
         for (int i = tid; i < np; i += SELB_THREADS) skeys[i] = i < ncand ? src[i] : 0ull;
         __syncthreads();
         bitonic_sort_desc(skeys, np);
+    } else if (select_request_binned(src, ncand, k, skeys, hist, wave_tot, &sel_digit, &sel_krem, &sel_cnt, &out_cnt)) {
+        // done: skeys holds the k best in order
     } else {
         // radix select on the unique 64-bit keys, 11-bit digits from the top; stops as
         // soon as the chosen bin holds exactly the number of keys still needed
@@ -563,10 +646,9 @@ __global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned lo
             const int nshift = shift - w;
             for (int i = tid; i < 2048; i += SELB_THREADS) hist[i] = 0;
             __syncthreads();
-            for (int64_t i = tid; i < ncand; i += SELB_THREADS) {
-                unsigned long long key = src[i];
+            for_each_key(src, ncand, [&](unsigned long long key) {
                 if (pass == 0 || (key >> shift) == prefix) atomicAdd(&hist[(int)((key >> nshift) & ((1u << w) - 1))], 1);
-            }
+            });
             __syncthreads();
             // thread t owns digits 2047-2t (hi) and 2046-2t (lo); scan from the top digit down
             const int hi = hist[2047 - 2 * tid], lo = hist[2046 - 2 * tid];
@@ -596,13 +678,12 @@ __global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned lo
         if (tid == 0) out_cnt = 0;
         for (int i = tid; i < kp; i += SELB_THREADS) skeys[i] = 0ull;
         __syncthreads();
-        for (int64_t i = tid; i < ncand; i += SELB_THREADS) {
-            unsigned long long key = src[i];
+        for_each_key(src, ncand, [&](unsigned long long key) {
             if ((key >> shift) >= prefix) {
                 int p = atomicAdd(&out_cnt, 1);
                 if (p < kp) skeys[p] = key;
             }
-        }
+        });
         __syncthreads();
         bitonic_sort_desc(skeys, kp);
     }
