@@ -44,10 +44,18 @@ struct GemmEpilogue {
     const int32_t *tok;  // [M] row selector of `table`
     const void *rowmul;  // unused by the GEMM (reserved)
     int act;             // ACT_*
+    const int32_t *ctx_len;  // launch_gemm_vt only: valid rows per request (NULL = all)
+    int vt_S;                // launch_gemm_vt only: rows per request
 };
 // A row stride lda, W row stride ldw (elements).  dtype: storage type of A, W (and C unless out_f32).
 int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K,
                 const GemmEpilogue &epi, hipStream_t st);
+
+// transposed-per-request product (context values for the attention kernel): see gemm.hip
+bool gemm_vt_supported(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K, int S,
+                       const void *out, int64_t ld_out);
+int launch_gemm_vt(const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K, int S, const int32_t *ctx_len, void *out,
+                   int64_t ld_out, hipStream_t st);
 
 // ---- element-wise / norm kernels -------------------------------------------
 // y[r,:] = g * x[r,:] / sqrt(mean(x[r,:]^2) + eps); x is the float32 residual stream, g and y have the storage dtype

@@ -364,10 +364,20 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     // ---- step 0: context keys/values of the autoregressive layers, once per request ----
     auto vt_ar = [&](int a) { return p.vt_bytes ? (void *)(ws + p.vt_ar + (size_t)a * p.vt_bytes) : (void *)nullptr; };
     void *vt_lazy = p.vt_bytes ? (void *)(ws + p.vt_lazy) : (void *)nullptr;
-    for (int a = 0; a < A; a++) {
-        OP_TRY(dec, gemm(ctx, (int64_t)B * S, dec->layers[K + a].wkv_x, 2 * d, d, plain_epilogue(kv_ar(a), 2 * d)), "context K/V projection");
-        OP_TRY(dec, launch_cross_attention_prepare(dt, kv_ar(a), ctx_len, vt_ar(a), B, S, d, H, st), "context value transpose");
-    }
+    // Where the attention kernel reads the values from its transposed copy, the value projection writes that copy
+    // directly (transposed per request, zero beyond the length) and only the key half of the K/V buffer is filled.
+    auto context_kv = [&](const LayerPacked &lw, void *kvbuf, void *vtbuf) -> int {
+        const void *wv = (const char *)lw.wkv_x + (size_t)d * d * e;
+        if (vtbuf && gemm_vt_supported(dt, ctx, d, wv, d, (int64_t)B * S, d, d, S, vtbuf, S)) {
+            int s = gemm(ctx, (int64_t)B * S, lw.wkv_x, d, d, plain_epilogue(kvbuf, 2 * d));
+            if (s) return s;
+            return launch_gemm_vt(ctx, d, wv, d, (int64_t)B * S, d, d, S, ctx_len, vtbuf, S, st);
+        }
+        int s = gemm(ctx, (int64_t)B * S, lw.wkv_x, 2 * d, d, plain_epilogue(kvbuf, 2 * d));
+        if (s) return s;
+        return launch_cross_attention_prepare(dt, kvbuf, ctx_len, vtbuf, B, S, d, H, st);
+    };
+    for (int a = 0; a < A; a++) OP_TRY(dec, context_kv(dec->layers[K + a], kv_ar(a), vt_ar(a)), "context K/V projection");
 
     // ---- step 1: lazy pass (eq. trunk): all T levels at once, no beam dimension ----
     OP_TRY(dec, launch_broadcast_rows(dt, dec->pos, trunk, B, T, d, st), "trunk input");
@@ -375,8 +385,7 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         const LayerPacked &lw = dec->layers[l];
         void *kvl = ws + p.kv_lazy;
         const int64_t rows = (int64_t)B * T;
-        OP_TRY(dec, gemm(ctx, (int64_t)B * S, lw.wkv_x, 2 * d, d, plain_epilogue(kvl, 2 * d)), "lazy context K/V projection");
-        OP_TRY(dec, launch_cross_attention_prepare(dt, kvl, ctx_len, vt_lazy, B, S, d, H, st), "lazy context value transpose");
+        OP_TRY(dec, context_kv(lw, kvl, vt_lazy), "lazy context K/V projection");
         OP_TRY(dec, cross_block(lw, trunk, rows, T, kvl, vt_lazy), "lazy cross-attention");
         OP_TRY(dec, launch_rmsnorm(dt, trunk, lw.ln_s, xn, rows, d, dec->eps, st), "lazy norm");
         OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, plain_epilogue(qkv, 3 * d)), "lazy qkv");

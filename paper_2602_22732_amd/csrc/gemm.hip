@@ -12,6 +12,8 @@
 //                        XOR swizzle of 16-byte chunks; XCD-aware tile order.
 //  * gemm_bf16_ring<..>  the kernel of the large shapes: persistent, 256x256 tiles,
 //                        operands stream global -> LDS without passing registers.
+#include <string.h>
+
 #include "common.h"
 
 // ---------------------------------------------------------------------------
@@ -85,7 +87,7 @@ __global__ __launch_bounds__(256) void gemm_simple(const T *__restrict__ A, int6
 // per cycle from 64 banks, and the 16 rows such a group of lanes reads (or the 2 rows it
 // writes) then fall on 16 different 16-byte slots.  The next K tile travels
 // global -> registers while the current one is multiplied, then registers -> LDS.
-enum { EPI_STORE = 0, EPI_SILU, EPI_F32, EPI_F32_RESID, EPI_F32_TABLE };
+enum { EPI_STORE = 0, EPI_SILU, EPI_F32, EPI_F32_RESID, EPI_F32_TABLE, EPI_VT };  // EPI_VT: persistent kernel only
 
 // bytes a bf16 GEMM must move once: both operands, the output, and the residual it adds
 static double gemm_bytes(int64_t M, int N, int K, bool out_f32, bool resid) {
@@ -378,7 +380,11 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
 #pragma unroll
         for (int i = 0; i < 4; i++)
 #pragma unroll
-            for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < 2; j++) {
+                // EPI_VT wants C transposed: with the operands in natural order a lane owns one column of C and four consecutive rows
+                if (KIND == EPI_VT) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
+                else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0);
+            }
     };
 
     // ---- prologue: A(0) W(0) A(1) W(1) A(2) into slots 0..4 (K >= 192, so all belong to the first tile) ----
@@ -429,11 +435,50 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
         // ---- epilogue: slots sa (waves 0..3) and sa+1 (waves 4..7) are free, 8 KB per wave ----
         const int sw = sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1;
         {
-            constexpr bool OUT_F32 = KIND >= EPI_F32;
+            constexpr bool OUT_F32 = KIND >= EPI_F32 && KIND != EPI_VT;
             char *stage = (char *)(smem + (wave < 4 ? sa : sw) * SLOT_CHUNKS) + (wave % 4) * 8192;
             const int64_t wrow0 = m0 + wm * 128;
             const int wcol0 = n0 + wn * 64;
-            if (!OUT_F32) {
+            if (KIND == EPI_VT) {
+                // C^T per request: out[(b*N + n) * ldc + s] = C[b*S + s][n] for s < len_b, 0 beyond (values of the context, transposed
+                // per head for the attention kernel's second product).  S is a multiple of 64, so the 64 rows of a pass share one request.
+                // Two passes of 64 rows: staged as 64 columns x 64 rows (128-byte lines of 8 chunks, chunk c of line r at c ^ (r & 7)).
+#pragma unroll
+                for (int pass = 0; pass < 2; pass++) {
+#pragma unroll
+                    for (int ii = 0; ii < 2; ii++)
+#pragma unroll
+                        for (int j = 0; j < 2; j++) {
+                            const int r = j * 32 + frow;
+#pragma unroll
+                            for (int g = 0; g < 4; g++) {
+                                bf16x4 pk;
+#pragma unroll
+                                for (int e = 0; e < 4; e++) pk[e] = (bf16)acc[pass * 2 + ii][j][4 * g + e];
+                                const int c = ii * 4 + g;
+                                *(bf16x4 *)(stage + r * 128 + ((c ^ (r & 7)) * 16) + hf * 8) = pk;
+                            }
+                        }
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    const int64_t t0 = wrow0 + pass * 64;  // first of the 64 rows (tokens) of this pass
+                    if (t0 < M) {
+                        const int64_t b = t0 / epi.vt_S;
+                        const int s0 = (int)(t0 - b * epi.vt_S);
+                        int len = epi.ctx_len ? epi.ctx_len[b] : epi.vt_S;
+                        len = len < 1 ? 1 : (len > epi.vt_S ? epi.vt_S : len);
+#pragma unroll 4
+                        for (int it = 0; it < 8; it++) {
+                            const int r = it * 8 + lane / 8, c = lane % 8;
+                            bf16x8 x = *(const bf16x8 *)(stage + r * 128 + ((c ^ (r & 7)) * 16));
+                            const int col = wcol0 + r, s = s0 + c * 8;
+#pragma unroll
+                            for (int e = 0; e < 8; e++) if (s + e >= len) x[e] = (bf16)0.0f;
+                            if (col < N) __builtin_nontemporal_store(x, (bf16x8 *)((bf16 *)epi.C + (b * N + col) * epi.ldc + s));
+                        }
+                    }
+                    if (pass == 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                }
+            } else if (!OUT_F32) {
                 // two passes of 64 rows x 64 columns: 128-byte rows of 8 chunks, chunk c of row r at position c ^ (r & 7)
 #pragma unroll
                 for (int pass = 0; pass < 2; pass++) {
@@ -555,7 +600,7 @@ static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
     if (grid < 8) grid = 8;
     if (total < grid) grid = ceil_div64(total, 8) * 8;
     {
-        ProfScope ps(KC_GEMM_RING, st, 2.0 * (double)M * N * K, gemm_bytes(M, N, K, KIND >= EPI_F32, KIND == EPI_F32_RESID));
+        ProfScope ps(KC_GEMM_RING, st, 2.0 * (double)M * N * K, gemm_bytes(M, N, K, KIND >= EPI_F32 && KIND != EPI_VT, KIND == EPI_F32_RESID));
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), RING_LDS_BYTES, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, 4, epi);
     }
     GR4AD_LAUNCH_CHECK();
@@ -581,6 +626,7 @@ static int launch_ring(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, i
         case EPI_SILU: return launch_ring_kind<EPI_SILU>(A, lda, W, ldw, M, N, K, epi, st);
         case EPI_F32: return launch_ring_kind<EPI_F32>(A, lda, W, ldw, M, N, K, epi, st);
         case EPI_F32_RESID: return launch_ring_kind<EPI_F32_RESID>(A, lda, W, ldw, M, N, K, epi, st);
+        case EPI_VT: return launch_ring_kind<EPI_VT>(A, lda, W, ldw, M, N, K, epi, st);
         default: return launch_ring_kind<EPI_F32_TABLE>(A, lda, W, ldw, M, N, K, epi, st);
     }
 }
@@ -630,6 +676,26 @@ static int launch_mfma(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, i
         case EPI_F32_RESID: return launch_mfma_kind<BM, BN, WM, WN, EPI_F32_RESID>(A, lda, W, ldw, M, N, K, epi, st);
         default: return launch_mfma_kind<BM, BN, WM, WN, EPI_F32_TABLE>(A, lda, W, ldw, M, N, K, epi, st);
     }
+}
+
+// Transposed-per-request product for the context values: out[(b*N + n) * ld_out + s] = sum_k A[b*S + s][k] * W[n][k] for
+// s < len_b, 0 for len_b <= s < S.  Only the persistent kernel does this; false = shape not covered (caller takes another route).
+bool gemm_vt_supported(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K, int S,
+                       const void *out, int64_t ld_out) {
+    return dtype == GR4AD_BF16 && K % 64 == 0 && K >= 192 && S % 64 == 0 && M % S == 0 && M >= 256 && N >= 256 && lda % 8 == 0 && ldw % 8 == 0 &&
+           lda < (1 << 22) && ldw < (1 << 22) && ((uintptr_t)A % 16) == 0 && ((uintptr_t)W % 16) == 0 && ((uintptr_t)out % 16) == 0 &&
+           ld_out % 8 == 0 && ld_out >= S;
+}
+int launch_gemm_vt(const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K, int S, const int32_t *ctx_len, void *out,
+                   int64_t ld_out, hipStream_t st) {
+    if (!gemm_vt_supported(GR4AD_BF16, A, lda, W, ldw, M, N, K, S, out, ld_out)) return GR4AD_EUNSUPPORTED;
+    GemmEpilogue e;
+    memset(&e, 0, sizeof(e));
+    e.C = out;
+    e.ldc = ld_out;
+    e.ctx_len = ctx_len;
+    e.vt_S = S;
+    return launch_ring((const bf16 *)A, lda, (const bf16 *)W, ldw, M, N, K, EPI_VT, e, st);
 }
 
 // 0 auto, 1 plain FMA kernel, 2 128x128 tiles, 3 256x256 tiles with 8 wavefronts, 4 256x256 tiles with 4 wavefronts,
