@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the batch size")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three device-to-device copies of 1 GiB before the warm-up (a kernel of known HBM traffic for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (requests shard data-parallel with no communication; "
@@ -112,6 +114,13 @@ def main():
     def step():
         dec.decode_batch(ctx, ctx_len, w.beam, workspace=ws, out_sid=out_sid, out_logprob=out_lp)
 
+    if args.calibrate_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        c = torch.empty_like(a)
+        for _ in range(3):
+            c.copy_(a)
+        torch.cuda.synchronize()
+        del a, c
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
