@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) void cross_attn_simple(const T *__restrict__ q
 // Values transposed per (request, head): vt[b][h][c][s] = V[b][s][h*dh+c] for s < len_b, 0 beyond
 // (s runs to Spad = S rounded up to 64), so a tile of V^T is row-major like a tile of K.
 __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16 *__restrict__ kv, const int32_t *__restrict__ ctx_len,
-                                                          bf16 *__restrict__ vt, int S, int Spad, int d) {
+                                                          bf16 *__restrict__ vt, int S, int Spad, int d, int src_pitch, int src_col0) {
     __shared__ bf16 tile[64][66];
     const int b = blockIdx.z, c0 = blockIdx.y * 64, s0 = blockIdx.x * 64;
     int len = ctx_len ? ctx_len[b] : S;
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16 *__restrict
     for (int i = tid; i < 64 * 8; i += 256) {  // 64 rows (s) x 8 chunks of 8 columns
         const int r = i / 8, ch = i % 8, s = s0 + r;
         uint4 raw = make_uint4(0, 0, 0, 0);
-        if (s < len) raw = *(const uint4 *)(kv + ((int64_t)b * S + s) * 2 * d + d + c0 + ch * 8);
+        if (s < len) raw = *(const uint4 *)(kv + ((int64_t)b * S + s) * src_pitch + src_col0 + c0 + ch * 8);
         const bf16 *e = (const bf16 *)&raw;
 #pragma unroll
         for (int k = 0; k < 8; k++) tile[r][ch * 8 + k] = e[k];
@@ -308,7 +308,79 @@ int launch_cross_attention_prepare(gr4ad_dtype dtype, const void *kv, const int3
     const int Spad = (S + 63) / 64 * 64;
     if (B > 65535 || d / 64 > 65535) return GR4AD_EUNSUPPORTED;
     ProfScope ps(KC_V_TRANSPOSE, st, 0.0, 2.0 * B * (double)S * d * sizeof(bf16));
-    hipLaunchKernelGGL(v_transpose_kernel, dim3(Spad / 64, d / 64, B), dim3(256), 0, st, (const bf16 *)kv, ctx_len, (bf16 *)vt, S, Spad, d);
+    hipLaunchKernelGGL(v_transpose_kernel, dim3(Spad / 64, d / 64, B), dim3(256), 0, st, (const bf16 *)kv, ctx_len, (bf16 *)vt, S, Spad, d, 2 * d,
+                       d);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+// xt[b][c][s] = x[b][s][c] for s < len_b, zero beyond (s up to the padded length): the operand layout of the
+// P*X product of the lazy layers' cross-attention in absorbed form.  x: [B, S, d] bf16, d % 64 == 0.
+int launch_context_transpose(const void *x, const int32_t *ctx_len, void *xt, int B, int S, int d, hipStream_t st) {
+    const int Spad = (S + 63) / 64 * 64;
+    if (B < 1 || S < 1 || d < 64 || d % 64 || B > 65535 || d / 64 > 65535) return GR4AD_EUNSUPPORTED;
+    if (!x || !xt || ((uintptr_t)x % 16) || ((uintptr_t)xt % 16)) return GR4AD_EINVAL;
+    ProfScope ps(KC_V_TRANSPOSE, st, 0.0, 2.0 * B * (double)S * d * sizeof(bf16));
+    hipLaunchKernelGGL(v_transpose_kernel, dim3(Spad / 64, d / 64, B), dim3(256), 0, st, (const bf16 *)x, ctx_len, (bf16 *)xt, S, Spad, d, d, 0);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+// Row softmax over the valid keys of a request: one wavefront per row of raw scores sc [rows, ld] (float32);
+// row r belongs to request r / rows_per_req.  p[r, s] = softmax_s(scale * sc[r, s]) over s < len, exactly zero
+// for len <= s < ld (the product with the values then runs over whole tiles without a mask).
+__global__ __launch_bounds__(256) void masked_softmax_rows(const float *__restrict__ sc, bf16 *__restrict__ p, const int32_t *__restrict__ ctx_len,
+                                                           int64_t rows, int rows_per_req, int S, int ld, float scale_log2e) {
+    const int lane = threadIdx.x % 64;
+    const int64_t r = (int64_t)blockIdx.x * 4 + threadIdx.x / 64;
+    if (r >= rows) return;
+    int len = ctx_len ? ctx_len[r / rows_per_req] : S;
+    len = len < 1 ? 1 : (len > S ? S : len);
+    const float *row = sc + r * ld;
+    bf16 *out = p + r * ld;
+    const int full = len & ~3;  // whole float4 groups below len
+    float mx = -INFINITY;
+    for (int s = lane * 4; s < full; s += 256) {
+        const float4 v = *(const float4 *)(row + s);
+        mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+    }
+    for (int s = full + lane; s < len; s += 64) mx = fmaxf(mx, row[s]);
+    mx = wave_max(mx) * scale_log2e;  // scale > 0: the max commutes with it
+    float sum = 0.f;
+    for (int s = lane * 4; s < full; s += 256) {
+        const float4 v = *(const float4 *)(row + s);
+        sum += exp2f(fmaf(v.x, scale_log2e, -mx)) + exp2f(fmaf(v.y, scale_log2e, -mx)) + exp2f(fmaf(v.z, scale_log2e, -mx)) +
+               exp2f(fmaf(v.w, scale_log2e, -mx));
+    }
+    for (int s = full + lane; s < len; s += 64) sum += exp2f(fmaf(row[s], scale_log2e, -mx));
+    const float inv = 1.f / wave_sum(sum);
+    for (int s = lane * 4; s < ld; s += 256) {  // ld % 4 == 0
+        float e[4] = {0.f, 0.f, 0.f, 0.f};
+        if (s + 3 < len) {
+            const float4 v = *(const float4 *)(row + s);
+            e[0] = v.x; e[1] = v.y; e[2] = v.z; e[3] = v.w;
+#pragma unroll
+            for (int k = 0; k < 4; k++) e[k] = exp2f(fmaf(e[k], scale_log2e, -mx)) * inv;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+                if (s + k < len) e[k] = exp2f(fmaf(row[s + k], scale_log2e, -mx)) * inv;
+        }
+        bf16x4 o;
+#pragma unroll
+        for (int k = 0; k < 4; k++) o[k] = (bf16)e[k];
+        *(bf16x4 *)(out + s) = o;
+    }
+}
+
+int launch_masked_softmax(const float *sc, void *p, const int32_t *ctx_len, int64_t rows, int rows_per_req, int S, int ld, float scale,
+                          hipStream_t st) {
+    if (rows < 1 || rows_per_req < 1 || S < 1 || ld < S || ld % 4 || !sc || !p || ((uintptr_t)sc % 16) || ((uintptr_t)p % 8)) return GR4AD_EINVAL;
+    const int64_t grid = ceil_div64(rows, 4);
+    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    ProfScope ps(KC_SOFTMAX, st, 0.0, (double)rows * S * (sizeof(float) + sizeof(bf16)));
+    hipLaunchKernelGGL(masked_softmax_rows, dim3((unsigned)grid), dim3(256), 0, st, sc, (bf16 *)p, ctx_len, rows, rows_per_req, S, ld,
+                       scale * 1.4426950408889634f);
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }

@@ -46,11 +46,17 @@ struct GemmEpilogue {
     int act;             // ACT_*
     const int32_t *ctx_len;  // launch_gemm_vt only: valid rows per request (NULL = all)
     int vt_S;                // launch_gemm_vt only: rows per request
+    const int32_t *batch_len;  // launch_gemm_batched only: valid length per batch (NULL = none)
+    int len_bounds;            // 1: the length bounds the columns of C that are needed, 2: it bounds K
 };
 // A row stride lda, W row stride ldw (elements).  dtype: storage type of A, W (and C unless out_f32).
 int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K,
                 const GemmEpilogue &epi, hipStream_t st);
 
+// batched small products (bf16 operands, 128x128 MFMA tiles): see gemm.hip
+int launch_gemm_batched(const void *A, int64_t lda, int64_t batch_a, const void *W, int64_t ldw, int64_t batch_w, void *C, int64_t ldc,
+                        int64_t batch_c, int out_f32, int64_t M, int N, int K, int batch, const int32_t *batch_len, int len_bounds,
+                        hipStream_t st);
 // transposed-per-request product (context values for the attention kernel): see gemm.hip
 bool gemm_vt_supported(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K, int S,
                        const void *out, int64_t ld_out);
@@ -69,6 +75,9 @@ int launch_broadcast_rows(gr4ad_dtype dtype, const void *pos, void *dst, int B, 
 int launch_gather_rows(gr4ad_dtype dtype, const void *src, const int32_t *parent, void *dst, int B, int n, int k, int64_t row_elems,
                        int64_t row_stride, hipStream_t st);
 
+// out[h][j][c] = w[h*dh + c][j] for a bf16 [d, d] weight (init-time)
+int launch_head_transpose(const void *w, void *out, int d, int H, hipStream_t st);
+
 // ---- attention ---------------------------------------------------------------
 // beam-shared cross-attention; q/out row stride ldq/ldo elements, rows (b*n+i)
 // vt: per-(request, head) transposed values built by launch_cross_attention_prepare (NULL: plain kernel on kv alone)
@@ -78,6 +87,11 @@ int launch_cross_attention(gr4ad_dtype dtype, const void *q, int64_t ldq, const 
 size_t cross_attention_workspace_bytes(gr4ad_dtype dtype, int B, int S, int d, int H);
 int launch_cross_attention_prepare(gr4ad_dtype dtype, const void *kv, const int32_t *ctx_len, void *vt, int B, int S, int d, int H,
                                    hipStream_t st);
+// lazy layers' cross-attention in absorbed form (see decoder.hip): transposed, length-masked context copy [B, d, Spad]
+int launch_context_transpose(const void *x, const int32_t *ctx_len, void *xt, int B, int S, int d, hipStream_t st);
+// p[r, :] = softmax(scale * sc[r, :len]) (bf16, zero from len to ld) for float32 score rows; request of row r = r / rows_per_req
+int launch_masked_softmax(const float *sc, void *p, const int32_t *ctx_len, int64_t rows, int rows_per_req, int S, int ld, float scale,
+                          hipStream_t st);
 // autoregressive self-attention of position `pos` for rows (b*n+i): qkv [rows,3d];
 // cache [B*n_stride... ] laid out [rows][T][2d] with per-request capacity cache_rows; writes k,v at `pos`
 int launch_self_attention_step(gr4ad_dtype dtype, const void *qkv, void *cache, void *out, int64_t rows, int pos, int T, int d, int H,
@@ -93,7 +107,7 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
 
 // ---- optional per-kernel event timing ----------------------------------------
 enum KernelClass { KC_GEMM_256 = 0, KC_GEMM_128, KC_GEMM_SIMPLE, KC_XATTN_FLASH, KC_XATTN_SIMPLE, KC_SELF_STEP, KC_TRUNK_SELF,
-                   KC_RMSNORM, KC_FUSE_GATE, KC_SELECT_ROWS, KC_SELECT_REQUEST, KC_GATHER, KC_BROADCAST, KC_V_TRANSPOSE, KC_GEMM_RING, KC_COUNT };
+                   KC_RMSNORM, KC_FUSE_GATE, KC_SELECT_ROWS, KC_SELECT_REQUEST, KC_GATHER, KC_BROADCAST, KC_V_TRANSPOSE, KC_GEMM_RING, KC_SOFTMAX, KC_COUNT };
 // Declared around a kernel launch: records an event before and (on scope exit) after it when timing is on.
 struct ProfScope {
     ProfScope(int cls, hipStream_t st, double flops = 0.0, double bytes = 0.0);  // algorithmic work of the launch

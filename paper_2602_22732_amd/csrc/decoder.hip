@@ -3,6 +3,7 @@
 // section 4.2).  All device work is enqueued on the caller's stream.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -16,6 +17,7 @@ struct LayerPacked {
     void *ln_x, *wq_x, *wkv_x, *wo_x;   // wkv_x [2d,d]: rows of W_k then W_v (context projection)
     void *ln_s, *wqkv_s, *wo_s;         // wqkv_s [3d,d]
     void *ln_f, *w1, *w2;
+    void *wkT_x;  // lazy layers in absorbed form only: [H][d][dh], the key projection transposed per head
 };
 
 thread_local char g_init_error[512] = "";
@@ -39,6 +41,7 @@ struct gr4ad_decoder {
     int32_t *tr_parent[GR4AD_MAX_LEVELS], *tr_tok[GR4AD_MAX_LEVELS];
     float *tr_score[GR4AD_MAX_LEVELS];
     bool trace;
+    bool absorbed;  // lazy layers' cross-attention runs in absorbed form (see decode_batch)
     char err[512];
 };
 
@@ -57,7 +60,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Everything decode_batch carves out of the caller's workspace.
 struct Plan {
-    size_t kv_ar, kv_lazy, vt_ar, vt_lazy, vt_bytes, trunk, h, xn, q, o, qkv, f, logits, selws, cache[2], cum[2], par, tok[2], sid[2], total;
+    size_t kv_ar, kv_lazy, vt_ar, vt_lazy, vt_bytes, xt, qp, zb, sc, pb, trunk, h, xn, q, o, qkv, f, logits, selws, cache[2], cum[2], par, tok[2], sid[2], total;
     int64_t rows_max, nmax, bmax;
     size_t cache_layer_elems;
 };
@@ -92,10 +95,19 @@ Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *be
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
     p.kv_ar = take((size_t)dec->A * B * S * 2 * d * e);
-    p.kv_lazy = take(dec->K > 0 ? (size_t)B * S * 2 * d * e : 0);
+    const bool lazy_kv = dec->K > 0 && !dec->absorbed;
+    p.kv_lazy = take(lazy_kv ? (size_t)B * S * 2 * d * e : 0);
     p.vt_bytes = cross_attention_workspace_bytes(dec->dtype, (int)B, (int)S, dec->d, dec->H);
     p.vt_ar = take((size_t)dec->A * p.vt_bytes);
-    p.vt_lazy = take(dec->K > 0 ? p.vt_bytes : 0);
+    p.vt_lazy = take(lazy_kv ? p.vt_bytes : 0);
+    if (dec->absorbed) {  // bf16 only
+        const int64_t Spad = (S + 63) / 64 * 64, RQ = T * dec->H;
+        p.xt = take((size_t)B * d * Spad * e);
+        p.qp = take((size_t)B * RQ * d * e);
+        p.zb = take((size_t)B * RQ * d * e);
+        p.sc = take((size_t)B * RQ * Spad * sizeof(float));
+        p.pb = take((size_t)B * RQ * Spad * e);
+    }
     p.trunk = take((size_t)B * T * d * sizeof(float));  // residual streams stay float32 whatever the storage dtype
     p.h = take((size_t)p.rows_max * d * sizeof(float));
     p.xn = take((size_t)p.rows_max * d * e);
@@ -233,6 +245,11 @@ int init_impl(gr4ad_decoder *dec, const gr4ad_model_desc *ds, const gr4ad_weight
         if ((s = dev_clone(dec, &p.ln_f, x->ln_f, d * e))) return s;
         if ((s = dev_clone(dec, &p.w1, x->w1, F * d * e))) return s;
         if ((s = dev_clone(dec, &p.w2, x->w2, d * F * e))) return s;
+        p.wkT_x = nullptr;
+        if (dec->absorbed && l < dec->K) {
+            if ((s = dev_alloc(dec, &p.wkT_x, d * d * e))) return s;
+            OP_TRY(dec, launch_head_transpose(p.wkv_x, p.wkT_x, (int)d, dec->H, 0), "per-head key weight transpose");
+        }
     }
     // Fuse (eq. fuse) is linear in the token embedding s: W_f [m*(W_g s); s] = W_f[:, :d] (m * (W_g s)) + W_f[:, d:] s.
     // Split W_f and tabulate W_g s and W_f[:, d:] s for BOS and for every token of every level.
@@ -284,6 +301,13 @@ int gr4ad_decode_init(const gr4ad_model_desc *ds, const gr4ad_weights *w, gr4ad_
     dec->T = ds->n_levels; dec->A = dec->L - dec->K; dec->max_batch = ds->max_batch; dec->max_ctx = ds->max_ctx;
     dec->dtype = ds->dtype; dec->esz = ds->dtype == GR4AD_BF16 ? 2 : 4; dec->eps = ds->rms_eps;
     dec->trace = false; dec->err[0] = 0;
+    {
+        // The lazy layers attend with only T queries per request, so projecting every context row to keys and values
+        // would dominate them.  Where the batched matrix-core kernel covers the shapes they use the absorbed form instead.
+        const char *env = getenv("GR4AD_LAZY_XATTN");  // "kv": always project keys and values (for comparison)
+        const int dh = dec->d / dec->H;
+        dec->absorbed = dec->K > 0 && dec->dtype == GR4AD_BF16 && dh % 64 == 0 && !(env && !strcmp(env, "kv"));
+    }
     for (int t = 0; t < dec->T; t++) { dec->V[t] = ds->codebook[t]; dec->max_beam[t] = ds->max_beam[t]; }
     s = init_impl(dec, ds, w);
     if (s) {
@@ -379,14 +403,46 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     };
     for (int a = 0; a < A; a++) OP_TRY(dec, context_kv(dec->layers[K + a], kv_ar(a), vt_ar(a)), "context K/V projection");
 
+    // Lazy layers, cross-attention in absorbed form.  With k_s = W_k x_s and v_s = W_v x_s (per head h: rows h*dh.. of W_k, W_v),
+    //   q_h . k_{s,h} = (W_{k,h}^T q_h) . x_s        and        sum_s p_s v_{s,h} = W_{v,h} (sum_s p_s x_s),
+    // so T*H queries per request attend over the raw context rows: no key/value projection of the S context rows
+    // (2*S*d*2d flops per request and layer) but two small products per (row, head) and two [T*H, d] x [d, S] products
+    // per request.  Same function of the inputs as eq. trunk's cross-attention; the intermediate roundings to bf16
+    // fall on q' = W_{k,h}^T q_h and z = sum_s p_s x_s instead of on k_s and v_s.
+    auto absorbed_cross_block = [&](const LayerPacked &lw, bool first) -> int {
+        const int64_t rows = (int64_t)B * T, RQ = (int64_t)T * H;
+        const int dh = d / H, Spad = (S + 63) / 64 * 64;
+        char *xt = ws + p.xt, *qp = ws + p.qp, *zb = ws + p.zb, *pb = ws + p.pb;
+        float *sc = (float *)(ws + p.sc);
+        const char *wv = (const char *)lw.wkv_x + (size_t)d * d * e;
+        int s;
+        if (first && (s = launch_context_transpose(ctx, ctx_len, xt, B, S, d, st))) return s;  // once per decode, shared by all lazy layers
+        if ((s = launch_rmsnorm(dt, trunk, lw.ln_x, xn, rows, d, dec->eps, st))) return s;
+        if ((s = gemm(xn, rows, lw.wq_x, d, d, plain_epilogue(q, d)))) return s;
+        // q'[row][h][:] = W_{k,h}^T q[row][h*dh : (h+1)*dh]      (batch = head)
+        if ((s = launch_gemm_batched(q, d, dh, lw.wkT_x, dh, (int64_t)d * dh, qp, (int64_t)H * d, d, 0, rows, d, dh, H, nullptr, 0, st))) return s;
+        // raw scores[b][(t,h)][s] = q'[b][(t,h)] . x[b][s]         (batch = request; columns beyond the length are not needed)
+        if ((s = launch_gemm_batched(qp, d, RQ * d, ctx, d, (int64_t)S * d, sc, Spad, RQ * Spad, 1, RQ, S, d, B, ctx_len, 1, st))) return s;
+        if ((s = launch_masked_softmax(sc, pb, ctx_len, (int64_t)B * RQ, (int)RQ, S, Spad, 1.0f / sqrtf((float)dh), st))) return s;
+        // z[b][(t,h)][:] = sum_s p[b][(t,h)][s] x[b][s][:]         (batch = request; p and x^T are zero beyond the length)
+        if ((s = launch_gemm_batched(pb, Spad, RQ * Spad, xt, Spad, (int64_t)d * Spad, zb, d, RQ * d, 0, RQ, d, Spad, B, ctx_len, 2, st))) return s;
+        // o[row][h*dh : (h+1)*dh] = W_{v,h} z[row][h][:]           (batch = head)
+        if ((s = launch_gemm_batched(zb, (int64_t)H * d, d, wv, d, (int64_t)dh * d, o, d, dh, 0, rows, dh, d, H, nullptr, 0, st))) return s;
+        return gemm(o, rows, lw.wo_x, d, d, resid_epi(trunk, d));
+    };
+
     // ---- step 1: lazy pass (eq. trunk): all T levels at once, no beam dimension ----
     OP_TRY(dec, launch_broadcast_rows(dt, dec->pos, trunk, B, T, d, st), "trunk input");
     for (int l = 0; l < K; l++) {
         const LayerPacked &lw = dec->layers[l];
         void *kvl = ws + p.kv_lazy;
         const int64_t rows = (int64_t)B * T;
-        OP_TRY(dec, context_kv(lw, kvl, vt_lazy), "lazy context K/V projection");
-        OP_TRY(dec, cross_block(lw, trunk, rows, T, kvl, vt_lazy), "lazy cross-attention");
+        if (dec->absorbed) {
+            OP_TRY(dec, absorbed_cross_block(lw, l == 0), "lazy cross-attention (absorbed form)");
+        } else {
+            OP_TRY(dec, context_kv(lw, kvl, vt_lazy), "lazy context K/V projection");
+            OP_TRY(dec, cross_block(lw, trunk, rows, T, kvl, vt_lazy), "lazy cross-attention");
+        }
         OP_TRY(dec, launch_rmsnorm(dt, trunk, lw.ln_s, xn, rows, d, dec->eps, st), "lazy norm");
         OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, plain_epilogue(qkv, 3 * d)), "lazy qkv");
         OP_TRY(dec, launch_trunk_self_attention(dt, qkv, o, B, T, d, H, st), "lazy self-attention");

@@ -179,3 +179,25 @@ int launch_gather_rows(gr4ad_dtype dtype, const void *src, const int32_t *parent
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }
+
+// ---------------------------------------------------------------------------
+// Per-head transposed copy of a [d, d] projection weight (rows = output features): out[h][j][c] = w[h*dh + c][j].
+// Built once at init for the key projection of the lazy layers, whose cross-attention runs in absorbed form.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void head_transpose_kernel(const bf16 *__restrict__ w, bf16 *__restrict__ out, int d, int dh) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // output element
+    if (idx >= (int64_t)d * d) return;
+    const int c = (int)(idx % dh);
+    const int j = (int)((idx / dh) % d);
+    const int h = (int)(idx / ((int64_t)dh * d));
+    out[idx] = w[((int64_t)h * dh + c) * d + j];
+}
+
+int launch_head_transpose(const void *w, void *out, int d, int H, hipStream_t st) {
+    if (!w || !out || d < 1 || H < 1 || d % H) return GR4AD_EINVAL;
+    const int64_t grid = ceil_div64((int64_t)d * d, 256);
+    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    hipLaunchKernelGGL(head_transpose_kernel, dim3((unsigned)grid), dim3(256), 0, st, (const bf16 *)w, (bf16 *)out, d, d / H);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}

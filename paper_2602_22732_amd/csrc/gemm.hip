@@ -98,7 +98,12 @@ template <int BM, int BN, int WM, int WN, int KIND>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(const bf16 *__restrict__ A, int64_t lda,
                                                                              const bf16 *__restrict__ W, int64_t ldw, int64_t M,
                                                                              int N, int K, int64_t tiles_m, int tiles_n,
-                                                                             GemmEpilogue epi) {
+                                                                             GemmEpilogue epi, int64_t batch_a, int64_t batch_w,
+                                                                             int64_t batch_c) {
+    // blockIdx.y: batch index; the operands and the output of batch i start batch_a/w/c elements further on
+    A += (int64_t)blockIdx.y * batch_a;
+    W += (int64_t)blockIdx.y * batch_w;
+    epi.C = (char *)epi.C + (int64_t)blockIdx.y * batch_c * (KIND >= EPI_F32 ? 4 : 2);
     constexpr int WAVES_N = BN / WN;
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -117,6 +122,14 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(con
     if (logical >= total) return;
     const int64_t m0 = (logical / tiles_n) * BM;
     const int n0 = (int)(logical % tiles_n) * BN;
+    // batched launches may carry a valid length per batch: as a bound on N (columns from it on are never read by the
+    // consumer, so tiles wholly beyond it are skipped) or on K (the operands are zero from it on)
+    if (epi.batch_len) {
+        int len = epi.batch_len[blockIdx.y];
+        len = len < 1 ? 1 : len;
+        if (epi.len_bounds == 1 && n0 >= len) return;
+        if (epi.len_bounds == 2 && len < K) K = (len + 63) / 64 * 64;
+    }
 
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -644,7 +657,7 @@ static int epilogue_kind(const GemmEpilogue &e) {
 
 template <int BM, int BN, int WM, int WN, int KIND>
 static int launch_mfma_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, int64_t M, int N, int K, const GemmEpilogue &epi,
-                            hipStream_t st) {
+                            hipStream_t st, int batch = 1, int64_t batch_a = 0, int64_t batch_w = 0, int64_t batch_c = 0) {
     constexpr int NT = (BM / WM) * (BN / WN) * 64;
     constexpr size_t smem = 2 * (size_t)(BM + BN) * 128;
     auto kern = gemm_bf16_mfma<BM, BN, WM, WN, KIND>;
@@ -659,8 +672,11 @@ static int launch_mfma_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
     int64_t grid = ceil_div64(total, 8) * 8;
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
     {
-        ProfScope ps(BM == 256 ? KC_GEMM_256 : KC_GEMM_128, st, 2.0 * (double)M * N * K, gemm_bytes(M, N, K, KIND >= EPI_F32, KIND == EPI_F32_RESID));
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), smem, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, epi);
+        if (batch < 1 || batch > 65535) return GR4AD_EUNSUPPORTED;
+        ProfScope ps(BM == 256 ? KC_GEMM_256 : KC_GEMM_128, st, 2.0 * (double)M * N * K * batch,
+                     batch * gemm_bytes(M, N, K, KIND >= EPI_F32, KIND == EPI_F32_RESID));
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid, (unsigned)batch), dim3(NT), smem, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, epi, batch_a,
+                           batch_w, batch_c);
     }
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
@@ -676,6 +692,31 @@ static int launch_mfma(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, i
         case EPI_F32_RESID: return launch_mfma_kind<BM, BN, WM, WN, EPI_F32_RESID>(A, lda, W, ldw, M, N, K, epi, st);
         default: return launch_mfma_kind<BM, BN, WM, WN, EPI_F32_TABLE>(A, lda, W, ldw, M, N, K, epi, st);
     }
+}
+
+// Batched product on the 128x128 MFMA kernel: for i < batch, C_i[M,N] = A_i[M,K] * W_i[N,K]^T with A_i = A + i*batch_a elements etc.
+// bf16 operands; C bf16 or (out_f32) float.  Used by the lazy layers' cross-attention in absorbed form (many small products).
+// batch_len (may be NULL), len_bounds: 1 = batch i only needs columns n < batch_len[i] of C_i (the rest may stay unwritten),
+// 2 = A_i and W_i are zero from column batch_len[i] (rounded up to 64) on, so the K loop stops there.
+int launch_gemm_batched(const void *A, int64_t lda, int64_t batch_a, const void *W, int64_t ldw, int64_t batch_w, void *C, int64_t ldc,
+                        int64_t batch_c, int out_f32, int64_t M, int N, int K, int batch, const int32_t *batch_len, int len_bounds,
+                        hipStream_t st) {
+    if (M <= 0 || N <= 0 || K <= 0 || K % 64 || lda % 8 || ldw % 8 || batch_a % 8 || batch_w % 8 || ((uintptr_t)A % 16) || ((uintptr_t)W % 16))
+        return GR4AD_EUNSUPPORTED;
+    GemmEpilogue e;
+    memset(&e, 0, sizeof(e));
+    e.C = C;
+    e.ldc = ldc;
+    e.out_f32 = out_f32;
+    e.batch_len = batch_len;
+    e.len_bounds = batch_len ? len_bounds : 0;
+    const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
+    if (M <= 64) {  // few rows per batch: 64-row tiles waste no matrix-core work
+        if (out_f32) return launch_mfma_kind<64, 128, 32, 64, EPI_F32>(a, lda, w, ldw, M, N, K, e, st, batch, batch_a, batch_w, batch_c);
+        return launch_mfma_kind<64, 128, 32, 64, EPI_STORE>(a, lda, w, ldw, M, N, K, e, st, batch, batch_a, batch_w, batch_c);
+    }
+    if (out_f32) return launch_mfma_kind<128, 128, 64, 64, EPI_F32>(a, lda, w, ldw, M, N, K, e, st, batch, batch_a, batch_w, batch_c);
+    return launch_mfma_kind<128, 128, 64, 64, EPI_STORE>(a, lda, w, ldw, M, N, K, e, st, batch, batch_a, batch_w, batch_c);
 }
 
 // Transposed-per-request product for the context values: out[(b*N + n) * ld_out + s] = sum_k A[b*S + s][k] * W[n][k] for

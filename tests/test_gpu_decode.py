@@ -48,6 +48,10 @@ def test_config1_tiny_fp32_full_batch_matches_oracle_exactly_where_margins_allow
     dict(T=4, V=[17, 300, 64, 9], d=128, H=8, F=192, L=4, K=2, S=70, B=3, beam=[5, 64, 31, 40], len_min=1),  # dh=16
     dict(T=2, V=[520, 130], d=256, H=2, F=64, L=2, K=0, S=9, B=2, beam=[300, 77]),                # K=0, dh=128, beam>V
     dict(T=1, V=[1000], d=64, H=1, F=64, L=1, K=0, S=3, B=4, beam=[10]),                          # single level
+    # head widths of 64 and 128 with lazy layers: in bf16 their cross-attention runs in absorbed form
+    dict(T=3, V=[40, 33, 50], d=128, H=2, F=96, L=3, K=2, S=37, B=5, beam=[7, 13, 9], len_min=1),    # one ragged key tile
+    dict(T=2, V=[64, 50], d=256, H=2, F=64, L=2, K=1, S=150, B=3, beam=[8, 12], len_min=1),       # dh=128, three key tiles
+    dict(T=7, V=[12, 12, 12, 12, 12, 12, 12], d=640, H=10, F=64, L=2, K=1, S=200, B=2, beam=[4, 6, 5, 6, 4, 6, 5], len_min=90),  # T*H > 64
 ])
 def test_small_shapes_match_oracle(dtype, shape):
     w, W, X = tiny(dtype=dtype, gain_jitter=0.3 if dtype == "f32" else 0.1, **shape)
