@@ -286,7 +286,8 @@ __device__ __forceinline__ float fast_silu(float x) { return x * __builtin_amdgc
 
 template <int KIND>
 __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ W, int64_t ldw,
-                                                      int64_t M, int N, int K, int64_t tiles_m, int tiles_n, int group_m, GemmEpilogue epi) {
+                                                      int64_t M, int N, int K, int64_t tiles_m, int tiles_n, int group_m, GemmEpilogue epi,
+                                                      int stagger_ticks) {
     extern __shared__ bf16x8 smem[];
     const int tid = threadIdx.x, lane = tid % 64;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -304,6 +305,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
     const int64_t xcd_end = (xcd + 1) * per_xcd < total ? (xcd + 1) * per_xcd : total;
     int64_t L = xcd * per_xcd + wslot;
     if (L >= xcd_end) return;
+    // All workgroups start together and every tile takes the same time, so without help they would all reach their
+    // epilogues together: HBM idles while everybody multiplies and the matrix cores idle while everybody stores.
+    // Workgroup slot i of an XCD therefore starts i/nslots of one tile time late (wall-clock ticks, a bounded wait).
+    if (stagger_ticks > 0) {
+        const uint64_t t0 = wall_clock64();
+        const uint64_t wait = (uint64_t)stagger_ticks * (uint32_t)wslot / (uint32_t)nslots;
+        while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);
+    }
     const uint32_t gsz = (uint32_t)group_m * (uint32_t)tiles_n;
     auto tile_coords = [&](int64_t l64, int64_t &m0, int &n0) {  // fewer than 2^31 tiles: 32-bit division
         const uint32_t l = (uint32_t)l64;
@@ -437,7 +446,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
             asm volatile("" ::: "memory");
             const int sa1 = sa + 2 >= RING_SLOTS ? sa + 2 - RING_SLOTS : sa + 2;
             const int sw1 = sa + 3 >= RING_SLOTS ? sa + 3 - RING_SLOTS : sa + 3;
-            SB; if (kt + 1 < KT || has_next) read_frags(fa0, fw0, sa1, sw1, 0); SB;
+            SB; if (kt + 1 < KT) read_frags(fa0, fw0, sa1, sw1, 0); SB;  // (a next tile's first fragments are read after the epilogue: it needs the registers)
             if (kt + 1 < KT) {  // the two slots just released take W(g+2) and A(g+3); after a tile's last k-tile they first stage C
                 issue_w(kt + 2, sa);
                 issue_a(kt + 3, sw);
@@ -527,7 +536,26 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                     if (pass == 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 }
             } else {
-                // four passes of 32 rows x 64 columns: 256-byte rows of 16 chunks, chunk c of row r at position c ^ (r & 15)
+                // four passes of 32 rows x 64 columns: 256-byte rows of 16 chunks, chunk c of row r at position c ^ (r & 15).
+                // What the epilogue adds (residual rows, table rows, bias) is requested one pass ahead, so its latency hides behind
+                // the staging and the stores of the pass before instead of stalling every pass.
+                constexpr bool HAS_ADD = KIND == EPI_F32_RESID || KIND == EPI_F32_TABLE;  // per-row addends; a bias is one vector per lane
+                const int erow = lane / 16, ecol = wcol0 + (lane % 16) * 4;
+                auto load_adds = [&](int pass, floatx4 (&a)[8]) {
+#pragma unroll
+                    for (int it = 0; it < 8; it++) {
+                        const int64_t row = wrow0 + pass * 32 + it * 4 + erow;
+                        a[it] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+                        if (row < M && ecol + 3 < N) {
+                            if (KIND == EPI_F32_RESID) a[it] = *(const floatx4 *)(epi.resid + row * epi.ldr + ecol);
+                            if (KIND == EPI_F32_TABLE) a[it] = *(const floatx4 *)(epi.table + (epi.tok ? (int64_t)epi.tok[row] : 0) * N + ecol);
+                        }
+                    }
+                };
+                floatx4 adds[2][8];
+                if (HAS_ADD) load_adds(0, adds[0]);
+                floatx4 bias4 = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (KIND == EPI_F32 && epi.bias && ecol + 3 < N) bias4 = *(const floatx4 *)(epi.bias + ecol);
 #pragma unroll
                 for (int pass = 0; pass < 4; pass++) {
                     const int r = frow;
@@ -541,20 +569,19 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                             const int c = j * 8 + g * 2 + hf;
                             *(floatx4 *)(stage + r * 256 + ((c ^ (r & 15)) * 16)) = pk;
                         }
+                    if (HAS_ADD && pass < 3) load_adds(pass + 1, adds[(pass + 1) & 1]);
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll 4
-                    for (int it = 0; it < 8; it++) {
-                        const int rr = it * 4 + lane / 16, c = lane % 16;
+#pragma unroll
+                    for (int it = 0; it < 8; it++) {  // (fully unrolled: the addend arrays must stay in registers)
+                        const int rr = it * 4 + erow, c = lane % 16;
                         floatx4 x = *(const floatx4 *)(stage + rr * 256 + ((c ^ (rr & 15)) * 16));
                         const int64_t row = wrow0 + pass * 32 + rr;
-                        const int col = wcol0 + c * 4;
+                        const int col = ecol;
                         if (row < M && col < N) {
                             if (col + 3 < N) {
-                                floatx4 add = {0.0f, 0.0f, 0.0f, 0.0f};
-                                if (KIND == EPI_F32 && epi.bias) add = *(const floatx4 *)(epi.bias + col);
-                                if (KIND == EPI_F32_RESID) add = *(const floatx4 *)(epi.resid + row * epi.ldr + col);
-                                if (KIND == EPI_F32_TABLE) add = *(const floatx4 *)(epi.table + (epi.tok ? (int64_t)epi.tok[row] : 0) * N + col);
-                                __builtin_nontemporal_store(x + add, (floatx4 *)((float *)epi.C + row * epi.ldc + col));
+                                if (HAS_ADD) x += adds[pass & 1][it];
+                                if (KIND == EPI_F32) x += bias4;
+                                __builtin_nontemporal_store(x, (floatx4 *)((float *)epi.C + row * epi.ldc + col));
                             } else {
                                 for (int e = 0; e < 4 && col + e < N; e++) {
                                     float y = x[e];
@@ -586,6 +613,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
         issue_w(1, sa);
         issue_a(2, sw);
         sa = sa + 2 >= RING_SLOTS ? sa + 2 - RING_SLOTS : sa + 2;
+        read_frags(fa0, fw0, sa, sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1, 0);  // A(0), W(0) of the new tile landed before its predecessor's last barrier
     }
 #undef SB
 }
@@ -604,6 +632,14 @@ static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
         n_cu = prop.multiProcessorCount;
         attr_done = true;
     }
+    static double ticks_per_us = -1.0, stagger_scale = 1.0;
+    if (ticks_per_us < 0) {
+        int khz = 0, dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return GR4AD_EHIP;
+        ticks_per_us = khz / 1000.0;
+        const char *env = getenv("GR4AD_GEMM_STAGGER");  // multiple of the estimated tile time the starts are spread over (0: off)
+        if (env) stagger_scale = atof(env);
+    }
     const int64_t tiles_m = ceil_div64(M, 256);
     const int tiles_n = (N + 255) / 256;
     const int64_t total = tiles_m * tiles_n;
@@ -614,7 +650,15 @@ static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
     if (total < grid) grid = ceil_div64(total, 8) * 8;
     {
         ProfScope ps(KC_GEMM_RING, st, 2.0 * (double)M * N * K, gemm_bytes(M, N, K, KIND >= EPI_F32 && KIND != EPI_VT, KIND == EPI_F32_RESID));
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), RING_LDS_BYTES, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, 4, epi);
+        // tile time: about 1.7 us per k-tile of 64 in the main loop plus the epilogue; spreading the starts costs up to
+        // one tile time once, so it is only done when a workgroup has many tiles
+        int stagger = 0;
+        if (total >= 8 * grid && stagger_scale > 0) {
+            double us = (K / 64) * 1.7 + 4.0;
+            if (us > 200.0) us = 200.0;
+            stagger = (int)(us * ticks_per_us * stagger_scale);
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), RING_LDS_BYTES, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, 4, epi, stagger);
     }
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
