@@ -9,7 +9,9 @@
 //  * cross_attn_simple<T>   one wavefront per (beam row, head), any shape; float32
 //                           path and fallback.
 //  * self_attn_step<T>      autoregressive self-attention of the new position over
-//                           the beam path's cached positions (at most T keys).
+//                           the beam path's earlier positions (at most T keys), read
+//                           in place from the buffers their levels wrote, through
+//                           the beams' ancestor table (no reorder copy).
 //  * trunk_self_attn<T>     causal self-attention over the T trunk positions.
 #include "common.h"
 
@@ -474,8 +476,8 @@ template <> struct Chunk8<float> {
 };
 
 template <typename T>
-__global__ __launch_bounds__(256) void self_attn_step(const T *__restrict__ qkv, T *__restrict__ cache, T *__restrict__ out,
-                                                      int64_t rows, int pos, int Tlev, int d, int H) {
+__global__ __launch_bounds__(256) void self_attn_step(const T *__restrict__ qkv, LevelBuffers prev, const int32_t *__restrict__ anc,
+                                                      T *__restrict__ out, int64_t rows, int pos, int Tlev, int d, int H) {
     const int cpr = d / 8;        // chunks per row
     const int lph = (d / H) / 8;  // lanes per head: 2, 4, 8 or 16
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -484,15 +486,14 @@ __global__ __launch_bounds__(256) void self_attn_step(const T *__restrict__ qkv,
     const int ch = live ? (int)(gid % cpr) : 0;
     const float scale = 1.0f / sqrtf((float)(d / H));
     const T *qr = qkv + row * 3 * d + ch * 8;
-    T *cr = cache + row * (int64_t)Tlev * 2 * d + ch * 8;
     float qv[8], kn[8], vn[8];
     Chunk8<T>::load(qr, qv);
     Chunk8<T>::load(qr + d, kn);
     Chunk8<T>::load(qr + 2 * d, vn);
-    if (live) {
-        Chunk8<T>::store(cr + (int64_t)pos * 2 * d, kn);
-        Chunk8<T>::store(cr + (int64_t)pos * 2 * d + d, vn);
-    }
+    const T *kvp[GR4AD_MAX_LEVELS];  // k of position p (v follows d elements later)
+#pragma unroll
+    for (int p = 0; p < GR4AD_MAX_LEVELS; p++)
+        if (p < pos) kvp[p] = (const T *)prev.p[p] + (int64_t)anc[row * Tlev + p] * 3 * d + d + ch * 8;
     float s[GR4AD_MAX_LEVELS];
     float mx = -INFINITY;
 #pragma unroll
@@ -503,7 +504,7 @@ __global__ __launch_bounds__(256) void self_attn_step(const T *__restrict__ qkv,
 #pragma unroll
                 for (int i = 0; i < 8; i++) kk[i] = kn[i];
             } else {
-                Chunk8<T>::load(cr + (int64_t)p * 2 * d, kk);
+                Chunk8<T>::load(kvp[p], kk);
             }
             float part = 0.0f;
 #pragma unroll
@@ -527,7 +528,7 @@ __global__ __launch_bounds__(256) void self_attn_step(const T *__restrict__ qkv,
 #pragma unroll
                 for (int i = 0; i < 8; i++) vv[i] = vn[i];
             } else {
-                Chunk8<T>::load(cr + (int64_t)p * 2 * d + d, vv);
+                Chunk8<T>::load(kvp[p] + d, vv);
             }
             const float w = s[p] * inv;
 #pragma unroll
@@ -537,20 +538,26 @@ __global__ __launch_bounds__(256) void self_attn_step(const T *__restrict__ qkv,
     if (live) Chunk8<T>::store(out + row * d + ch * 8, o8);
 }
 
-int launch_self_attention_step(gr4ad_dtype dtype, const void *qkv, void *cache, void *out, int64_t rows, int pos, int T, int d, int H,
-                               hipStream_t st) {
+int launch_self_attention_step(gr4ad_dtype dtype, const void *qkv, const LevelBuffers &prev, const int32_t *anc, void *out, int64_t rows,
+                               int pos, int T, int d, int H, hipStream_t st) {
     if (rows <= 0 || pos < 0 || pos >= T || T > GR4AD_MAX_LEVELS || d % H) return GR4AD_EINVAL;
+    if (pos > 0 && !anc) return GR4AD_EINVAL;
+    for (int p = 0; p < pos; p++)
+        if (!prev.p[p] || ((uintptr_t)prev.p[p] % 32) || prev.rows[p] < 1) return GR4AD_EINVAL;
     const int dh = d / H;
     if (dh != 16 && dh != 32 && dh != 64 && dh != 128) return GR4AD_EUNSUPPORTED;
-    if (((uintptr_t)qkv % 32) || ((uintptr_t)cache % 32) || ((uintptr_t)out % 32)) return GR4AD_EUNSUPPORTED;
+    if (((uintptr_t)qkv % 32) || ((uintptr_t)out % 32)) return GR4AD_EUNSUPPORTED;
     const int64_t grid = ceil_div64(rows * (d / 8), 256);
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
-    // reads q,k,v and the pos cached (k,v) pairs, writes the new pair and the output
-    ProfScope ps(KC_SELF_STEP, st, 4.0 * rows * (double)(pos + 1) * d, (double)rows * d * (3 + 2 + 2 * pos + 1) * (dtype == GR4AD_BF16 ? 2 : 4));
+    // reads q,k,v of the new position and the pos earlier (k,v) pairs of the beam's path, writes the output
+    // (beams that share an ancestor share its row: an earlier level contributes at most its own size)
+    double units = 4.0 * rows;
+    for (int p = 0; p < pos; p++) units += 2.0 * (double)(prev.rows[p] > 0 && prev.rows[p] < rows ? prev.rows[p] : rows);
+    ProfScope ps(KC_SELF_STEP, st, 4.0 * rows * (double)(pos + 1) * d, units * d * (dtype == GR4AD_BF16 ? 2 : 4));
     if (dtype == GR4AD_BF16)
-        hipLaunchKernelGGL(self_attn_step<bf16>, dim3((unsigned)grid), dim3(256), 0, st, (const bf16 *)qkv, (bf16 *)cache, (bf16 *)out, rows, pos, T, d, H);
+        hipLaunchKernelGGL(self_attn_step<bf16>, dim3((unsigned)grid), dim3(256), 0, st, (const bf16 *)qkv, prev, anc, (bf16 *)out, rows, pos, T, d, H);
     else
-        hipLaunchKernelGGL(self_attn_step<float>, dim3((unsigned)grid), dim3(256), 0, st, (const float *)qkv, (float *)cache, (float *)out, rows, pos, T, d, H);
+        hipLaunchKernelGGL(self_attn_step<float>, dim3((unsigned)grid), dim3(256), 0, st, (const float *)qkv, prev, anc, (float *)out, rows, pos, T, d, H);
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }

@@ -92,18 +92,22 @@ int launch_context_transpose(const void *x, const int32_t *ctx_len, void *xt, in
 // p[r, :] = softmax(scale * sc[r, :len]) (bf16, zero from len to ld) for float32 score rows; request of row r = r / rows_per_req
 int launch_masked_softmax(const float *sc, void *p, const int32_t *ctx_len, int64_t rows, int rows_per_req, int S, int ld, float scale,
                           hipStream_t st);
-// autoregressive self-attention of position `pos` for rows (b*n+i): qkv [rows,3d];
-// cache [B*n_stride... ] laid out [rows][T][2d] with per-request capacity cache_rows; writes k,v at `pos`
-int launch_self_attention_step(gr4ad_dtype dtype, const void *qkv, void *cache, void *out, int64_t rows, int pos, int T, int d, int H,
-                               hipStream_t st);
+// autoregressive self-attention of position `pos` for rows (b*n+i).  qkv [rows,3d] holds q, k, v of the new position;
+// the keys and values of position p < pos are columns d..3d of row anc[row*T + p] of prev.p[p] (the [*,3d] q/k/v buffer
+// that level wrote): the beam reorder is the ancestor table, no rows are moved.
+struct LevelBuffers { const void *p[GR4AD_MAX_LEVELS]; int64_t rows[GR4AD_MAX_LEVELS]; };  // rows: rows of that level's buffer
+int launch_self_attention_step(gr4ad_dtype dtype, const void *qkv, const LevelBuffers &prev, const int32_t *anc, void *out, int64_t rows,
+                               int pos, int T, int d, int H, hipStream_t st);
 // causal self-attention over the T trunk positions of each request: qkv [B*T,3d] -> out [B*T,d]
 int launch_trunk_self_attention(gr4ad_dtype dtype, const void *qkv, void *out, int B, int T, int d, int H, hipStream_t st);
 
 // ---- selection ---------------------------------------------------------------
 size_t select_workspace_bytes(int B, int n, int V, int k);
-// sid_old [B,n,T] / sid_new [B,k,T] may be NULL (no path bookkeeping); level = 0-based t
+// sid_old [B,n,T] / sid_new [B,k,T] may be NULL (no path bookkeeping); anc_old / anc_new likewise: batch-wide row index of
+// each survivor's ancestor at levels 0..level (anc_new[.., level] = b*n + parent); level = 0-based t
 int launch_select(const float *logits, const float *cum, int B, int n, int V, int k, void *ws, size_t ws_bytes, int32_t *parent,
-                  int32_t *tok, float *score, const int32_t *sid_old, int32_t *sid_new, int T, int level, hipStream_t st);
+                  int32_t *tok, float *score, const int32_t *sid_old, int32_t *sid_new, const int32_t *anc_old, int32_t *anc_new, int T,
+                  int level, hipStream_t st);
 
 // ---- optional per-kernel event timing ----------------------------------------
 enum KernelClass { KC_GEMM_256 = 0, KC_GEMM_128, KC_GEMM_SIMPLE, KC_XATTN_FLASH, KC_XATTN_SIMPLE, KC_SELF_STEP, KC_TRUNK_SELF,

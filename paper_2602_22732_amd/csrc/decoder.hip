@@ -60,9 +60,9 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Everything decode_batch carves out of the caller's workspace.
 struct Plan {
-    size_t kv_ar, kv_lazy, vt_ar, vt_lazy, vt_bytes, xt, qp, zb, sc, pb, trunk, h, xn, q, o, qkv, f, logits, selws, cache[2], cum[2], par, tok[2], sid[2], total;
+    size_t kv_ar, kv_lazy, vt_ar, vt_lazy, vt_bytes, xt, qp, zb, sc, pb, trunk, h, xn, q, o, qkv, f, logits, selws, qkv_lvl[GR4AD_MAX_LEVELS], cum[2], par, tok[2], sid[2], anc[2], total;
     int64_t rows_max, nmax, bmax;
-    size_t cache_layer_elems;
+    size_t qkv_lvl_layer_bytes[GR4AD_MAX_LEVELS];  // one layer's [B*n_t, 3d] buffer of level t
 };
 
 bool beams_ok(const gr4ad_decoder *dec, const int32_t *beam) {
@@ -113,16 +113,23 @@ Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *be
     p.xn = take((size_t)p.rows_max * d * e);
     p.q = take((size_t)p.rows_max * d * e);
     p.o = take((size_t)p.rows_max * d * e);
-    p.qkv = take((size_t)p.rows_max * 3 * d * e);
+    p.qkv = take((size_t)B * T * 3 * d * e);  // lazy layers; the autoregressive layers keep one buffer per (level, layer), below
     p.f = take((size_t)p.rows_max * dec->F * e);
     p.logits = take((size_t)B * logit_max * sizeof(float));
     p.selws = take(selmax);
-    p.cache_layer_elems = (size_t)B * nmax * T * 2 * d;
-    for (int i = 0; i < 2; i++) p.cache[i] = take((size_t)dec->A * p.cache_layer_elems * e);
+    // q/k/v of every level stay resident: they are the self-attention cache of the later levels, read through the
+    // beams' ancestor table (the last level's are only read by that level itself)
+    n = 1;
+    for (int t = 0; t < T; t++) {
+        p.qkv_lvl_layer_bytes[t] = align256((size_t)B * n * 3 * d * e);
+        p.qkv_lvl[t] = take((size_t)dec->A * p.qkv_lvl_layer_bytes[t]);
+        n = beam[t];
+    }
     for (int i = 0; i < 2; i++) p.cum[i] = take((size_t)B * bmax * sizeof(float));
     p.par = take((size_t)B * bmax * sizeof(int32_t));
     for (int i = 0; i < 2; i++) p.tok[i] = take((size_t)B * bmax * sizeof(int32_t));
     for (int i = 0; i < 2; i++) p.sid[i] = take((size_t)B * bmax * T * sizeof(int32_t));
+    for (int i = 0; i < 2; i++) p.anc[i] = take((size_t)B * bmax * T * sizeof(int32_t));
     p.total = off;
     return p;
 }
@@ -362,7 +369,7 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     void *h = ws + p.h, *xn = ws + p.xn, *q = ws + p.q, *o = ws + p.o, *qkv = ws + p.qkv, *f = ws + p.f, *trunk = ws + p.trunk;
     float *logits = (float *)(ws + p.logits);
     auto kv_ar = [&](int a) { return (void *)(ws + p.kv_ar + (size_t)a * B * S * 2 * d * e); };
-    auto cache = [&](int i, int a) { return (void *)(ws + p.cache[i] + (size_t)a * p.cache_layer_elems * e); };
+    auto qkv_lvl = [&](int t, int a) { return (void *)(ws + p.qkv_lvl[t] + (size_t)a * p.qkv_lvl_layer_bytes[t]); };
 
     auto gemm = [&](const void *Ain, int64_t M, const void *W, int N, int Kdim, const GemmEpilogue &epi) {
         return launch_gemm(dt, Ain, Kdim, W, Kdim, M, N, Kdim, epi, st);
@@ -468,8 +475,14 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
             const LayerPacked &lw = dec->layers[K + a];
             OP_TRY(dec, cross_block(lw, h, rows, n, kv_ar(a), vt_ar(a)), "cross-attention");
             OP_TRY(dec, launch_rmsnorm(dt, h, lw.ln_s, xn, rows, d, dec->eps, st), "self-attention norm");
-            OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, plain_epilogue(qkv, 3 * d)), "self-attention qkv");
-            OP_TRY(dec, launch_self_attention_step(dt, qkv, cache(cur, a), o, rows, t, T, d, H, st), "self-attention");
+            LevelBuffers prev;
+            for (int u = 0; u < GR4AD_MAX_LEVELS; u++) {
+                prev.p[u] = u < t ? qkv_lvl(u, a) : nullptr;
+                prev.rows[u] = u < t ? (int64_t)B * (u == 0 ? 1 : beam[u - 1]) : 0;
+            }
+            OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, plain_epilogue(qkv_lvl(t, a), 3 * d)), "self-attention qkv");
+            OP_TRY(dec, launch_self_attention_step(dt, qkv_lvl(t, a), prev, (const int32_t *)(ws + p.anc[cur]), o, rows, t, T, d, H, st),
+                   "self-attention");
             OP_TRY(dec, gemm(o, rows, lw.wo_s, d, d, resid_epi(h, d)), "self-attention output");
             OP_TRY(dec, ffn_block(lw, h, rows), "FFN");
         }
@@ -486,7 +499,7 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         int32_t *sid_new = last ? out_sid : (int32_t *)(ws + p.sid[cur ^ 1]);
         OP_TRY(dec, launch_select(logits, t == 0 ? nullptr : (const float *)(ws + p.cum[cur]), B, n, dec->V[t], bt, ws + p.selws,
                                   select_workspace_bytes(B, n, dec->V[t], bt), par, tok_new, score_new, (const int32_t *)(ws + p.sid[cur]),
-                                  sid_new, T, t, st),
+                                  sid_new, (const int32_t *)(ws + p.anc[cur]), last ? nullptr : (int32_t *)(ws + p.anc[cur ^ 1]), T, t, st),
                "selection");
         if (dec->trace) {
             const size_t nb = (size_t)B * bt * 4;
@@ -494,10 +507,8 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
             if (dec->tr_tok[t]) HIP_TRY(dec, hipMemcpyAsync(dec->tr_tok[t], tok_new, nb, hipMemcpyDeviceToDevice, st));
             if (dec->tr_score[t]) HIP_TRY(dec, hipMemcpyAsync(dec->tr_score[t], score_new, nb, hipMemcpyDeviceToDevice, st));
         }
-        if (!last)
-            for (int a = 0; a < A; a++)
-                OP_TRY(dec, launch_gather_rows(dt, cache(cur, a), par, cache(cur ^ 1, a), B, n, bt, (int64_t)(t + 1) * 2 * d, (int64_t)T * 2 * d, st),
-                       "beam reorder");
+        // beam reorder: the survivors' ancestor rows (written by the selection) are all that moves; keys and values stay where
+        // their level wrote them
         cur ^= 1;
         n = bt;
     }
@@ -522,7 +533,8 @@ size_t gr4ad_op_select_workspace_bytes(int32_t B, int32_t n, int32_t V, int32_t 
 int gr4ad_op_select(const float *logits, const float *cum, int32_t B, int32_t n, int32_t V, int32_t k, void *ws, size_t ws_bytes,
                     int32_t *parent, int32_t *tok, float *score, void *hip_stream) {
     if (!logits || !ws || !parent || !tok || !score) return GR4AD_EINVAL;
-    return launch_select(logits, cum, B, n, V, k, ws, ws_bytes, parent, tok, score, nullptr, nullptr, 0, 0, (hipStream_t)hip_stream);
+    return launch_select(logits, cum, B, n, V, k, ws, ws_bytes, parent, tok, score, nullptr, nullptr, nullptr, nullptr, 0, 0,
+                         (hipStream_t)hip_stream);
 }
 
 size_t gr4ad_op_cross_attention_workspace_bytes(gr4ad_dtype dtype, int32_t B, int32_t S, int32_t d, int32_t H) {

@@ -616,7 +616,8 @@ __device__ __forceinline__ bool select_request_binned(const unsigned long long *
 __global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned long long *__restrict__ cand, int64_t ncand, int V, int k,
                                                                int32_t *__restrict__ parent, int32_t *__restrict__ tok,
                                                                float *__restrict__ score, const int32_t *__restrict__ sid_old,
-                                                               int32_t *__restrict__ sid_new, int n, int T, int level) {
+                                                               int32_t *__restrict__ sid_new, const int32_t *__restrict__ anc_old,
+                                                               int32_t *__restrict__ anc_new, int n, int T, int level) {
     __shared__ unsigned long long skeys[SELB_SORT_MAX];
     __shared__ int hist[2048];
     __shared__ int wave_tot[16];
@@ -700,6 +701,10 @@ __global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned lo
             sid_new[(b * k + j) * T + level] = tk;
             for (int t = level + 1; t < T; t++) sid_new[(b * k + j) * T + t] = 0;
         }
+        if (anc_new) {  // row (over the whole batch) of the survivor's ancestor at every level so far: the reorder is this index table
+            for (int t = 0; t < level; t++) anc_new[(b * k + j) * T + t] = anc_old[(b * n + par) * T + t];
+            anc_new[(b * k + j) * T + level] = (int32_t)(b * n + par);
+        }
     }
 }
 
@@ -733,7 +738,8 @@ size_t select_workspace_bytes(int B, int n, int V, int k) {
 }
 
 int launch_select(const float *logits, const float *cum, int B, int n, int V, int k, void *ws, size_t ws_bytes, int32_t *parent,
-                  int32_t *tok, float *score, const int32_t *sid_old, int32_t *sid_new, int T, int level, hipStream_t st) {
+                  int32_t *tok, float *score, const int32_t *sid_old, int32_t *sid_new, const int32_t *anc_old, int32_t *anc_new, int T, int level,
+                  hipStream_t st) {
     if (B <= 0 || n <= 0 || V <= 0 || k <= 0 || (int64_t)k > (int64_t)n * V) return GR4AD_EINVAL;
     if (k > GR4AD_MAX_BEAM || V > GR4AD_MAX_CODEBOOK || (int64_t)n * V >= 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
     if (ws_bytes < select_workspace_bytes(B, n, V, k) || ((uintptr_t)ws % 8)) return GR4AD_EWORKSPACE;
@@ -768,7 +774,7 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
     GR4AD_LAUNCH_CHECK();
     ProfScope ps(KC_SELECT_REQUEST, st, 0.0, (double)rows * m * 8 + (double)B * k * 12);
     hipLaunchKernelGGL(select_request, dim3((unsigned)B), dim3(SELB_THREADS), 0, st, (const unsigned long long *)ws, (int64_t)n * m, V, k,
-                       parent, tok, score, sid_old, sid_new, n, T, level);
+                       parent, tok, score, sid_old, sid_new, anc_old, anc_new, n, T, level);
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }
