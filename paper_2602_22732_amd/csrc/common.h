@@ -46,12 +46,25 @@ struct GemmEpilogue {
     int act;             // ACT_*
     const int32_t *ctx_len;  // launch_gemm_vt only: valid rows per request (NULL = all)
     int vt_S;                // launch_gemm_vt only: rows per request
+    // RMSNorm folded into the projections around it (persistent kernel only; launch_gemm fails if it cannot honour them):
+    // writer side (out_f32 with resid or table, N % 256 == 0): besides C, write norm_out[row, col] = C[row, col] * norm_gain[col]
+    // in the storage dtype (row stride norm_ld) and norm_ss[row * (N / 64) + col / 64] = sum of C^2 over those 64 columns
+    // (launch_row_inv turns them into 1/rms per row); reader side: scale row r of the product by row_inv[r] before anything
+    // else the epilogue does (activation, bias).
+    const void *norm_gain;
+    void *norm_out;
+    int64_t norm_ld;
+    float *norm_ss;
+    const float *row_inv;
     const int32_t *batch_len;  // launch_gemm_batched only: valid length per batch (NULL = none)
     int len_bounds;            // 1: the length bounds the columns of C that are needed, 2: it bounds K
 };
 // A row stride lda, W row stride ldw (elements).  dtype: storage type of A, W (and C unless out_f32).
 int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K,
                 const GemmEpilogue &epi, hipStream_t st);
+// true if launch_gemm would run this product on the persistent kernel (the one that supports the folded RMSNorm)
+bool gemm_on_persistent_kernel(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K,
+                               const GemmEpilogue &epi);
 
 // batched small products (bf16 operands, 128x128 MFMA tiles): see gemm.hip
 int launch_gemm_batched(const void *A, int64_t lda, int64_t batch_a, const void *W, int64_t ldw, int64_t batch_w, void *C, int64_t ldc,
@@ -66,6 +79,8 @@ int launch_gemm_vt(const void *A, int64_t lda, const void *W, int64_t ldw, int64
 // ---- element-wise / norm kernels -------------------------------------------
 // y[r,:] = g * x[r,:] / sqrt(mean(x[r,:]^2) + eps); x is the float32 residual stream, g and y have the storage dtype
 int launch_rmsnorm(gr4ad_dtype dtype, const void *x, const void *g, void *y, int64_t rows, int d, float eps, hipStream_t st);
+// inv[r] = 1 / sqrt(sum(ss[r*parts .. r*parts+parts-1]) / dim + eps): per-row factor of the folded RMSNorm from the partial sums
+int launch_row_inv(const float *ss, float *inv, int64_t rows, int parts, int dim, float eps, hipStream_t st);
 // a[(b*n+i), :] = m[b*m_stride + :] * G[tok(b,i), :]   (tok == NULL: row 0 of G); m float32, G and a storage dtype
 int launch_fuse_gate(gr4ad_dtype dtype, const void *m, int64_t m_req_stride, const void *G, const int32_t *tok, void *a, int B, int n,
                      int d, hipStream_t st);

@@ -60,7 +60,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Everything decode_batch carves out of the caller's workspace.
 struct Plan {
-    size_t kv_ar, kv_lazy, vt_ar, vt_lazy, vt_bytes, xt, qp, zb, sc, pb, trunk, h, xn, q, o, qkv, f, logits, selws, qkv_lvl[GR4AD_MAX_LEVELS], cum[2], par, tok[2], sid[2], anc[2], total;
+    size_t kv_ar, kv_lazy, vt_ar, vt_lazy, vt_bytes, xt, qp, zb, sc, pb, ss, trunk, h, xn, q, o, qkv, f, logits, selws, qkv_lvl[GR4AD_MAX_LEVELS], cum[2], par, tok[2], sid[2], anc[2], total;
     int64_t rows_max, nmax, bmax;
     size_t qkv_lvl_layer_bytes[GR4AD_MAX_LEVELS];  // one layer's [B*n_t, 3d] buffer of level t
 };
@@ -108,6 +108,7 @@ Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *be
         p.sc = take((size_t)B * RQ * Spad * sizeof(float));
         p.pb = take((size_t)B * RQ * Spad * e);
     }
+    p.ss = take((size_t)p.rows_max * (d / 64 + 1) * sizeof(float));  // partial sums of squares of the folded RMSNorm
     p.trunk = take((size_t)B * T * d * sizeof(float));  // residual streams stay float32 whatever the storage dtype
     p.h = take((size_t)p.rows_max * d * sizeof(float));
     p.xn = take((size_t)p.rows_max * d * e);
@@ -377,19 +378,61 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     auto resid_epi = [&](void *x, int64_t ld) { GemmEpilogue g = plain_epilogue(x, ld); g.resid = (const float *)x; g.ldr = ld; g.out_f32 = 1; return g; };
     auto silu_epi = [&](void *x, int64_t ld) { GemmEpilogue g = plain_epilogue(x, ld); g.act = ACT_SILU; return g; };
 
-    // cross-attention + its residual; x is the residual stream [rows,d]
+    // RMSNorm folded into the projections around it.  Every norm sits between a projection that writes the residual
+    // stream x (residual update or Fuse) and one that reads norm(x).  On launches that run on the persistent kernel the
+    // writer also stores gain * x (storage dtype, into xn) and per-row partial sums of x^2, and the reader scales its
+    // product rows by 1/rms(x) - (gain * x / rms) W^T = (1/rms) (gain * x) W^T - so the norm kernel and its pass over
+    // the stream disappear.  Elsewhere (small launches, float32, widths the kernel does not cover) the norm kernel runs.
+    const int nparts = d / 64;
+    float *ss = (float *)(ws + p.ss), *rinv = ss + (size_t)p.rows_max * nparts;  // partial sums of x^2; 1/rms per row
+    bool fold = false;             // set per phase: this row count and these widths run on the persistent kernel
+    bool scaled = false;           // xn holds gain * x without the 1/rms factor; its reader must apply row_ss
+    const void *emitted = nullptr; // gain the last writer of x folded in (xn and ss are current for exactly that norm)
+    auto fold_ok = [&](int64_t rows, int n_cls) -> bool {
+        if (dt != GR4AD_BF16 || d % 256 || F % 64 || F < 256 || F % 8 || (n_cls && (n_cls < 256 || n_cls % 4))) return false;
+        const char *env = getenv("GR4AD_FOLD_NORM");
+        if (env && !strcmp(env, "0")) return false;
+        GemmEpilogue g = plain_epilogue(trunk, d);  // representative writer: a d x d residual update
+        g.resid = (const float *)trunk; g.ldr = d; g.out_f32 = 1;
+        g.norm_gain = dec->ln_out; g.norm_out = xn; g.norm_ld = d; g.norm_ss = ss;
+        GemmEpilogue r = plain_epilogue(q, d);      // representative reader
+        r.row_inv = rinv;
+        return gemm_on_persistent_kernel(dt, o, d, dec->layers[0].wo_x, d, rows, d, d, g) &&
+               gemm_on_persistent_kernel(dt, xn, d, dec->layers[0].wq_x, d, rows, d, d, r);
+    };
+    auto emit_norm = [&](GemmEpilogue g, const void *next_gain) {  // writer side: x is followed by RMSNorm with next_gain
+        emitted = nullptr;
+        if (fold && next_gain) { g.norm_gain = next_gain; g.norm_out = xn; g.norm_ld = d; g.norm_ss = ss; emitted = next_gain; }
+        return g;
+    };
+    auto norm = [&](void *x, const void *gain, int64_t rows) -> int {
+        if (emitted && emitted == gain) {
+            emitted = nullptr;
+            scaled = true;
+            return launch_row_inv(ss, rinv, rows, nparts, d, dec->eps, st);
+        }
+        emitted = nullptr;
+        scaled = false;
+        return launch_rmsnorm(dt, x, gain, xn, rows, d, dec->eps, st);
+    };
+    auto reads_norm = [&](GemmEpilogue g) {  // reader side: the A operand is xn
+        if (scaled) g.row_inv = rinv;
+        return g;
+    };
+
+    // cross-attention + its residual; x is the residual stream [rows,d]; next_gain: gain of the norm that follows
     auto cross_block = [&](const LayerPacked &lw, void *x, int64_t rows, int n, const void *kvbuf, const void *vtbuf) -> int {
         int s;
-        if ((s = launch_rmsnorm(dt, x, lw.ln_x, xn, rows, d, dec->eps, st))) return s;
-        if ((s = gemm(xn, rows, lw.wq_x, d, d, plain_epilogue(q, d)))) return s;
+        if ((s = norm(x, lw.ln_x, rows))) return s;
+        if ((s = gemm(xn, rows, lw.wq_x, d, d, reads_norm(plain_epilogue(q, d))))) return s;
         if ((s = launch_cross_attention(dt, q, d, kvbuf, vtbuf, ctx_len, o, d, B, n, S, d, H, st))) return s;
-        return gemm(o, rows, lw.wo_x, d, d, resid_epi(x, d));
+        return gemm(o, rows, lw.wo_x, d, d, emit_norm(resid_epi(x, d), lw.ln_s));
     };
-    auto ffn_block = [&](const LayerPacked &lw, void *x, int64_t rows) -> int {
+    auto ffn_block = [&](const LayerPacked &lw, void *x, int64_t rows, const void *next_gain) -> int {
         int s;
-        if ((s = launch_rmsnorm(dt, x, lw.ln_f, xn, rows, d, dec->eps, st))) return s;
-        if ((s = gemm(xn, rows, lw.w1, F, d, silu_epi(f, F)))) return s;
-        return gemm(f, rows, lw.w2, d, F, resid_epi(x, d));
+        if ((s = norm(x, lw.ln_f, rows))) return s;
+        if ((s = gemm(xn, rows, lw.w1, F, d, reads_norm(silu_epi(f, F))))) return s;
+        return gemm(f, rows, lw.w2, d, F, emit_norm(resid_epi(x, d), next_gain));
     };
 
     // ---- step 0: context keys/values of the autoregressive layers, once per request ----
@@ -424,8 +467,8 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         const char *wv = (const char *)lw.wkv_x + (size_t)d * d * e;
         int s;
         if (first && (s = launch_context_transpose(ctx, ctx_len, xt, B, S, d, st))) return s;  // once per decode, shared by all lazy layers
-        if ((s = launch_rmsnorm(dt, trunk, lw.ln_x, xn, rows, d, dec->eps, st))) return s;
-        if ((s = gemm(xn, rows, lw.wq_x, d, d, plain_epilogue(q, d)))) return s;
+        if ((s = norm(trunk, lw.ln_x, rows))) return s;
+        if ((s = gemm(xn, rows, lw.wq_x, d, d, reads_norm(plain_epilogue(q, d))))) return s;
         // q'[row][h][:] = W_{k,h}^T q[row][h*dh : (h+1)*dh]      (batch = head)
         if ((s = launch_gemm_batched(q, d, dh, lw.wkT_x, dh, (int64_t)d * dh, qp, (int64_t)H * d, d, 0, rows, d, dh, H, nullptr, 0, st))) return s;
         // raw scores[b][(t,h)][s] = q'[b][(t,h)] . x[b][s]         (batch = request; columns beyond the length are not needed)
@@ -435,11 +478,12 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         if ((s = launch_gemm_batched(pb, Spad, RQ * Spad, xt, Spad, (int64_t)d * Spad, zb, d, RQ * d, 0, RQ, d, Spad, B, ctx_len, 2, st))) return s;
         // o[row][h*dh : (h+1)*dh] = W_{v,h} z[row][h][:]           (batch = head)
         if ((s = launch_gemm_batched(zb, (int64_t)H * d, d, wv, d, (int64_t)dh * d, o, d, dh, 0, rows, dh, d, H, nullptr, 0, st))) return s;
-        return gemm(o, rows, lw.wo_x, d, d, resid_epi(trunk, d));
+        return gemm(o, rows, lw.wo_x, d, d, emit_norm(resid_epi(trunk, d), lw.ln_s));
     };
 
     // ---- step 1: lazy pass (eq. trunk): all T levels at once, no beam dimension ----
     OP_TRY(dec, launch_broadcast_rows(dt, dec->pos, trunk, B, T, d, st), "trunk input");
+    fold = K > 0 && fold_ok((int64_t)B * T, 0);
     for (int l = 0; l < K; l++) {
         const LayerPacked &lw = dec->layers[l];
         void *kvl = ws + p.kv_lazy;
@@ -450,11 +494,11 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
             OP_TRY(dec, context_kv(lw, kvl, vt_lazy), "lazy context K/V projection");
             OP_TRY(dec, cross_block(lw, trunk, rows, T, kvl, vt_lazy), "lazy cross-attention");
         }
-        OP_TRY(dec, launch_rmsnorm(dt, trunk, lw.ln_s, xn, rows, d, dec->eps, st), "lazy norm");
-        OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, plain_epilogue(qkv, 3 * d)), "lazy qkv");
+        OP_TRY(dec, norm(trunk, lw.ln_s, rows), "lazy norm");
+        OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, reads_norm(plain_epilogue(qkv, 3 * d))), "lazy qkv");
         OP_TRY(dec, launch_trunk_self_attention(dt, qkv, o, B, T, d, H, st), "lazy self-attention");
-        OP_TRY(dec, gemm(o, rows, lw.wo_s, d, d, resid_epi(trunk, d)), "lazy self-attention output");
-        OP_TRY(dec, ffn_block(lw, trunk, rows), "lazy FFN");
+        OP_TRY(dec, gemm(o, rows, lw.wo_s, d, d, emit_norm(resid_epi(trunk, d), lw.ln_f)), "lazy self-attention output");
+        OP_TRY(dec, ffn_block(lw, trunk, rows, l + 1 < K ? dec->layers[l + 1].ln_x : nullptr), "lazy FFN");
     }
 
     // ---- level loop (eq. fuse, eq. head, classifier, selection, reorder) ----
@@ -463,35 +507,40 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         const int64_t rows = (int64_t)B * n;
         const int bt = beam[t];
         const int32_t *tok_prev = t == 0 ? nullptr : (const int32_t *)(ws + p.tok[cur]);
-        OP_TRY(dec, launch_fuse_gate(dt, (const float *)trunk + (size_t)t * d, (int64_t)T * d, dec->G[t], tok_prev, xn, B, n, d, st), "Fuse gate");
+        fold = fold_ok(rows, dec->V[t]);
+        scaled = false;
+        emitted = nullptr;
         {
+            // the gated embedding goes through q when the Fuse projection also writes the first norm's input into xn
+            void *gated = fold ? q : xn;
+            OP_TRY(dec, launch_fuse_gate(dt, (const float *)trunk + (size_t)t * d, (int64_t)T * d, dec->G[t], tok_prev, gated, B, n, d, st), "Fuse gate");
             GemmEpilogue g = plain_epilogue(h, d);
             g.out_f32 = 1;
             g.table = (const float *)dec->P[t];
             g.tok = tok_prev;
-            OP_TRY(dec, gemm(xn, rows, dec->wf1, d, d, g), "Fuse projection");
+            OP_TRY(dec, gemm(gated, rows, dec->wf1, d, d, emit_norm(g, dec->layers[K].ln_x)), "Fuse projection");
         }
         for (int a = 0; a < A; a++) {
             const LayerPacked &lw = dec->layers[K + a];
             OP_TRY(dec, cross_block(lw, h, rows, n, kv_ar(a), vt_ar(a)), "cross-attention");
-            OP_TRY(dec, launch_rmsnorm(dt, h, lw.ln_s, xn, rows, d, dec->eps, st), "self-attention norm");
+            OP_TRY(dec, norm(h, lw.ln_s, rows), "self-attention norm");
             LevelBuffers prev;
             for (int u = 0; u < GR4AD_MAX_LEVELS; u++) {
                 prev.p[u] = u < t ? qkv_lvl(u, a) : nullptr;
                 prev.rows[u] = u < t ? (int64_t)B * (u == 0 ? 1 : beam[u - 1]) : 0;
             }
-            OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, plain_epilogue(qkv_lvl(t, a), 3 * d)), "self-attention qkv");
+            OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, reads_norm(plain_epilogue(qkv_lvl(t, a), 3 * d))), "self-attention qkv");
             OP_TRY(dec, launch_self_attention_step(dt, qkv_lvl(t, a), prev, (const int32_t *)(ws + p.anc[cur]), o, rows, t, T, d, H, st),
                    "self-attention");
-            OP_TRY(dec, gemm(o, rows, lw.wo_s, d, d, resid_epi(h, d)), "self-attention output");
-            OP_TRY(dec, ffn_block(lw, h, rows), "FFN");
+            OP_TRY(dec, gemm(o, rows, lw.wo_s, d, d, emit_norm(resid_epi(h, d), lw.ln_f)), "self-attention output");
+            OP_TRY(dec, ffn_block(lw, h, rows, a + 1 < A ? dec->layers[K + a + 1].ln_x : dec->ln_out), "FFN");
         }
-        OP_TRY(dec, launch_rmsnorm(dt, h, dec->ln_out, xn, rows, d, dec->eps, st), "final norm");
+        OP_TRY(dec, norm(h, dec->ln_out, rows), "final norm");
         {
             GemmEpilogue g = plain_epilogue(logits, dec->V[t]);
             g.out_f32 = 1;
             g.bias = dec->cls_bias[t];
-            OP_TRY(dec, gemm(xn, rows, dec->cls[t], dec->V[t], d, g), "classifier");
+            OP_TRY(dec, gemm(xn, rows, dec->cls[t], dec->V[t], d, reads_norm(g)), "classifier");
         }
         const bool last = t == T - 1;
         int32_t *par = (int32_t *)(ws + p.par), *tok_new = (int32_t *)(ws + p.tok[cur ^ 1]);

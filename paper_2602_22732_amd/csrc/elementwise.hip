@@ -201,3 +201,32 @@ int launch_head_transpose(const void *w, void *out, int d, int H, hipStream_t st
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }
+
+// ---------------------------------------------------------------------------
+// Folded RMSNorm: per-row factor from the partial sums of squares a projection's epilogue left
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void row_inv_kernel(const float *__restrict__ ss, float *__restrict__ inv, int64_t rows, int parts, int dim,
+                                                      float eps) {
+    // 16 lanes per row: consecutive lanes read consecutive 16-byte pieces of the row's partial sums
+    const int64_t r = ((int64_t)blockIdx.x * 256 + threadIdx.x) / 16;
+    const int sub = threadIdx.x % 16;
+    float s = 0.0f;
+    if (r < rows)
+        for (int u = sub * 4; u < parts; u += 64) {  // parts % 4 == 0
+            const floatx4 v = *(const floatx4 *)(ss + r * parts + u);
+            s += (v[0] + v[1]) + (v[2] + v[3]);
+        }
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o, 64);
+    if (r < rows && sub == 0) inv[r] = 1.0f / sqrtf(s / (float)dim + eps);
+}
+
+int launch_row_inv(const float *ss, float *inv, int64_t rows, int parts, int dim, float eps, hipStream_t st) {
+    if (!ss || !inv || rows < 1 || parts < 4 || parts % 4 || dim < 1 || ((uintptr_t)ss % 16)) return GR4AD_EINVAL;
+    const int64_t grid = ceil_div64(rows * 16, 256);
+    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    ProfScope ps(KC_RMSNORM, st, 0.0, (double)rows * (parts + 1) * sizeof(float));
+    hipLaunchKernelGGL(row_inv_kernel, dim3((unsigned)grid), dim3(256), 0, st, ss, inv, rows, parts, dim, eps);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}

@@ -430,6 +430,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
             for (int j = 0; j < 2; j++)
 #pragma unroll
                 for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
+        float rinv[4] = {1.0f, 1.0f, 1.0f, 1.0f};
+        if (KIND != EPI_VT && epi.row_inv) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const int64_t row = m0 + wm * 128 + i * 32 + frow;
+                rinv[i] = epi.row_inv[row < M ? row : M - 1];
+            }
+        }
         for (int kt = 0; kt < KT; kt++) {
             const int sw = sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1;
             SB; read_frags(fa1, fw1, sa, sw, 1); wait_frags(fa0, fw0, false); SB;
@@ -461,6 +469,16 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
             char *stage = (char *)(smem + (wave < 4 ? sa : sw) * SLOT_CHUNKS) + (wave % 4) * 8192;
             const int64_t wrow0 = m0 + wm * 128;
             const int wcol0 = n0 + wn * 64;
+            if (KIND != EPI_VT && epi.row_inv) {
+                // folded RMSNorm, reader side: the A operand was gain * x, not yet divided by rms(x); a lane owns row frow of
+                // each 32-row block (factors requested at the start of the tile)
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+#pragma unroll
+                    for (int j = 0; j < 2; j++)
+#pragma unroll
+                        for (int v = 0; v < 16; v++) acc[i][j][v] *= rinv[i];
+            }
             if (KIND == EPI_VT) {
                 // C^T per request: out[(b*N + n) * ldc + s] = C[b*S + s][n] for s < len_b, 0 beyond (values of the context, transposed
                 // per head for the attention kernel's second product).  S is a multiple of 64, so the 64 rows of a pass share one request.
@@ -537,27 +555,34 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                 }
             } else {
                 // four passes of 32 rows x 64 columns: 256-byte rows of 16 chunks, chunk c of row r at position c ^ (r & 15).
-                // What the epilogue adds (residual rows, table rows, bias) is requested one pass ahead, so its latency hides behind
-                // the staging and the stores of the pass before instead of stalling every pass.
+                // What a pass adds (residual rows, table rows) is requested before its accumulators are staged, all eight
+                // 16-byte pieces at once, so that latency overlaps the trip through LDS.
                 constexpr bool HAS_ADD = KIND == EPI_F32_RESID || KIND == EPI_F32_TABLE;  // per-row addends; a bias is one vector per lane
                 const int erow = lane / 16, ecol = wcol0 + (lane % 16) * 4;
-                auto load_adds = [&](int pass, floatx4 (&a)[8]) {
+                // folded RMSNorm, writer side (N % 256 == 0: every column exists)
+                const bool emit = HAS_ADD && epi.norm_out != nullptr;
+                floatx4 gain4 = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (emit) {
+                    const bf16x4 g4 = *(const bf16x4 *)((const bf16 *)epi.norm_gain + ecol);
 #pragma unroll
-                    for (int it = 0; it < 8; it++) {
-                        const int64_t row = wrow0 + pass * 32 + it * 4 + erow;
-                        a[it] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
-                        if (row < M && ecol + 3 < N) {
-                            if (KIND == EPI_F32_RESID) a[it] = *(const floatx4 *)(epi.resid + row * epi.ldr + ecol);
-                            if (KIND == EPI_F32_TABLE) a[it] = *(const floatx4 *)(epi.table + (epi.tok ? (int64_t)epi.tok[row] : 0) * N + ecol);
-                        }
-                    }
-                };
-                floatx4 adds[2][8];
-                if (HAS_ADD) load_adds(0, adds[0]);
+                    for (int e = 0; e < 4; e++) gain4[e] = (float)g4[e];
+                }
                 floatx4 bias4 = {0.0f, 0.0f, 0.0f, 0.0f};
                 if (KIND == EPI_F32 && epi.bias && ecol + 3 < N) bias4 = *(const floatx4 *)(epi.bias + ecol);
 #pragma unroll
                 for (int pass = 0; pass < 4; pass++) {
+                    floatx4 adds[8];
+                    if (HAS_ADD) {
+#pragma unroll
+                        for (int it = 0; it < 8; it++) {
+                            const int64_t row = wrow0 + pass * 32 + it * 4 + erow;
+                            adds[it] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+                            if (row < M && ecol + 3 < N) {
+                                if (KIND == EPI_F32_RESID) adds[it] = *(const floatx4 *)(epi.resid + row * epi.ldr + ecol);
+                                if (KIND == EPI_F32_TABLE) adds[it] = *(const floatx4 *)(epi.table + (epi.tok ? (int64_t)epi.tok[row] : 0) * N + ecol);
+                            }
+                        }
+                    }
                     const int r = frow;
 #pragma unroll
                     for (int j = 0; j < 2; j++)
@@ -569,19 +594,34 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                             const int c = j * 8 + g * 2 + hf;
                             *(floatx4 *)(stage + r * 256 + ((c ^ (r & 15)) * 16)) = pk;
                         }
-                    if (HAS_ADD && pass < 3) load_adds(pass + 1, adds[(pass + 1) & 1]);
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-                    for (int it = 0; it < 8; it++) {  // (fully unrolled: the addend arrays must stay in registers)
+                    for (int it = 0; it < 8; it++) {  // (fully unrolled: the addends must stay in registers)
                         const int rr = it * 4 + erow, c = lane % 16;
                         floatx4 x = *(const floatx4 *)(stage + rr * 256 + ((c ^ (rr & 15)) * 16));
                         const int64_t row = wrow0 + pass * 32 + rr;
                         const int col = ecol;
+                        if (HAS_ADD) x += adds[it];  // (zero where the lane stores nothing or takes the slow path below)
+                        if (emit) {  // sum of squares over the row's 64 columns in this wave: the 16 lanes of a DPP row
+                            float sq = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
+                            sq += __shfl_xor(sq, 1, 64);
+                            sq += __shfl_xor(sq, 2, 64);  // every lane: its quad's sum
+                            // row_shr:4 then row_shr:8 (lane i takes lane i-4 / i-8 of its row, 0 if there is none): lane 15 of the
+                            // row ends with all four quads
+                            sq += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sq), 0x114, 0xf, 0xf, true));
+                            sq += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sq), 0x118, 0xf, 0xf, true));
+                            if (lane % 16 == 15 && row < M) epi.norm_ss[row * (N / 64) + (wcol0 >> 6)] = sq;
+                        }
                         if (row < M && col < N) {
                             if (col + 3 < N) {
-                                if (HAS_ADD) x += adds[pass & 1][it];
                                 if (KIND == EPI_F32) x += bias4;
                                 __builtin_nontemporal_store(x, (floatx4 *)((float *)epi.C + row * epi.ldc + col));
+                                if (emit) {
+                                    bf16x4 nb;
+#pragma unroll
+                                    for (int e = 0; e < 4; e++) nb[e] = (bf16)(x[e] * gain4[e]);
+                                    *(bf16x4 *)((bf16 *)epi.norm_out + row * epi.norm_ld + col) = nb;
+                                }
                             } else {
                                 for (int e = 0; e < 4 && col + e < N; e++) {
                                     float y = x[e];
@@ -673,6 +713,11 @@ static bool ring_ok(int kind, int N, int K, int64_t lda, int64_t ldw, const Gemm
     if (kind == EPI_F32 && e.bias && ((uintptr_t)e.bias % 16)) return false;
     if (kind == EPI_F32_RESID && (e.ldr % 4 || ((uintptr_t)e.resid % 16))) return false;
     if (kind == EPI_F32_TABLE && (N % 4 || ((uintptr_t)e.table % 16))) return false;
+    if (e.norm_out) {  // folded RMSNorm, producer side
+        if ((kind != EPI_F32_RESID && kind != EPI_F32_TABLE) || N % 256 || !e.norm_gain || !e.norm_ss) return false;
+        if (e.norm_ld % 4 || ((uintptr_t)e.norm_out % 8) || ((uintptr_t)e.norm_gain % 8)) return false;
+    }
+    if (e.row_inv && kind == EPI_VT) return false;  // reader side
     return true;
 }
 
@@ -794,11 +839,25 @@ static int gemm_mode() {
     return g_gemm_mode;
 }
 
+bool gemm_on_persistent_kernel(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K,
+                               const GemmEpilogue &epi) {
+    const int mode = gemm_mode();
+    const int kind = epilogue_kind(epi);
+    if (M <= 0 || N <= 0 || K <= 0) return false;
+    if (!(dtype == GR4AD_BF16 && mode != 1 && kind >= 0 && K % 64 == 0 && lda % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)A % 16) == 0 &&
+          ((uintptr_t)W % 16) == 0))
+        return false;
+    const bool big = (M >= 8192 && N >= 256);
+    return (mode == 5 || (mode == 0 && big)) && ring_ok(kind, N, K, lda, ldw, epi);
+}
+
 int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K,
                 const GemmEpilogue &epi, hipStream_t st) {
     if (M <= 0 || N <= 0 || K <= 0) return GR4AD_EINVAL;
     const int mode = gemm_mode();
     const int kind = epilogue_kind(epi);
+    // only the persistent kernel folds the RMSNorm: never drop such a request silently
+    if ((epi.norm_out || epi.row_inv) && !gemm_on_persistent_kernel(dtype, A, lda, W, ldw, M, N, K, epi)) return GR4AD_EUNSUPPORTED;
     if (dtype == GR4AD_BF16 && mode != 1 && kind >= 0 && K % 64 == 0 && lda % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)A % 16) == 0 &&
         ((uintptr_t)W % 16) == 0) {
         const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
