@@ -431,6 +431,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
 #pragma unroll
                 for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
         float rinv[4] = {1.0f, 1.0f, 1.0f, 1.0f};
+        floatx4 bias4 = {0.0f, 0.0f, 0.0f, 0.0f};  // EPI_F32: bias of this lane's four columns in the epilogue's read-back layout
         if (KIND != EPI_VT && epi.row_inv) {
 #pragma unroll
             for (int i = 0; i < 4; i++) {
@@ -455,6 +456,15 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
             const int sa1 = sa + 2 >= RING_SLOTS ? sa + 2 - RING_SLOTS : sa + 2;
             const int sw1 = sa + 3 >= RING_SLOTS ? sa + 3 - RING_SLOTS : sa + 3;
             SB; if (kt + 1 < KT) read_frags(fa0, fw0, sa1, sw1, 0); SB;  // (a next tile's first fragments are read after the epilogue: it needs the registers)
+            if (KIND == EPI_F32 && kt + 2 == KT && epi.bias) {
+                // The bias of this lane's four columns (read-back layout of the epilogue) is requested here, just before the
+                // tile's last operand loads, by a load the compiler does not track: the wait that ends the last k-tile (all but
+                // the four newest loads have landed) covers it.  A tracked load in the epilogue would make the compiler guard
+                // the reuse of its registers with a full drain of outstanding loads inside the k-loop.
+                const int c0 = n0 + wn * 64 + (lane % 16) * 4;
+                const float *src = epi.bias + (c0 + 3 < N ? c0 : 0);
+                asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(bias4) : "v"(src) : "memory");
+            }
             if (kt + 1 < KT) {  // the two slots just released take W(g+2) and A(g+3); after a tile's last k-tile they first stage C
                 issue_w(kt + 2, sa);
                 issue_a(kt + 3, sw);
@@ -556,7 +566,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
             } else {
                 // four passes of 32 rows x 64 columns: 256-byte rows of 16 chunks, chunk c of row r at position c ^ (r & 15).
                 // What a pass adds (residual rows, table rows) is requested before its accumulators are staged, all eight
-                // 16-byte pieces at once, so that latency overlaps the trip through LDS.
+                // 16-byte pieces at once.  (Requesting them a pass ahead changes nothing: at N = K = 1024 these launches move
+                // 12-14 bytes per output element and run at the memory system's mixed read/write rate.)
                 constexpr bool HAS_ADD = KIND == EPI_F32_RESID || KIND == EPI_F32_TABLE;  // per-row addends; a bias is one vector per lane
                 const int erow = lane / 16, ecol = wcol0 + (lane % 16) * 4;
                 // folded RMSNorm, writer side (N % 256 == 0: every column exists)
@@ -567,8 +578,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
 #pragma unroll
                     for (int e = 0; e < 4; e++) gain4[e] = (float)g4[e];
                 }
-                floatx4 bias4 = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (KIND == EPI_F32 && epi.bias && ecol + 3 < N) bias4 = *(const floatx4 *)(epi.bias + ecol);
 #pragma unroll
                 for (int pass = 0; pass < 4; pass++) {
                     floatx4 adds[8];
