@@ -181,9 +181,12 @@ int gr4ad_op_cross_attention(gr4ad_dtype dtype, const void *q_dev, const void *k
                              void *out_dev, int32_t B, int32_t n, int32_t S, int32_t d, int32_t H, void *workspace_dev,
                              size_t workspace_bytes, void *hip_stream);
 
-/* Beam reorder: dst[b, j, 0:row_elems] = src[b, parent[b,j], 0:row_elems] for
- * j < k; rows are `row_stride` elements apart in both buffers, src holds n rows
- * per request and dst k.  Element size follows dtype. */
+/* Beam reorder as a row gather: dst[b, j, 0:row_elems] = src[b, parent[b,j],
+ * 0:row_elems] for j < k; rows are `row_stride` elements apart in both buffers,
+ * src holds n rows per request and dst k.  Element size follows dtype.
+ * (gr4ad_decode_batch itself reorders nothing: it addresses a beam's earlier
+ * keys and values through an ancestor-row table.  This entry point is for
+ * callers that keep a per-beam cache of their own.) */
 int gr4ad_op_gather_rows(gr4ad_dtype dtype, const void *src_dev, const int32_t *parent_dev, void *dst_dev, int32_t B, int32_t n,
                          int32_t k, int64_t row_elems, int64_t row_stride, void *hip_stream);
 
