@@ -392,7 +392,7 @@ __global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restri
     const int lane = threadIdx.x % 64, wv = threadIdx.x / 64;
     const int64_t row = (int64_t)blockIdx.x * 4 + wv;
     if (row >= rows) return;  // whole wavefronts leave; nothing below synchronises across wavefronts
-    unsigned long long *list = wave_lds + (size_t)wv * (512 + m);
+    unsigned long long *list = wave_lds + (size_t)wv * ((512 + m + 1) & ~1);  // even number of 8-byte slots: 16-byte accesses stay aligned
     int *hist = (int *)list;
     unsigned long long *stage = list + 512;
     const floatx4 *z4 = (const floatx4 *)(logits + row * (int64_t)V);
@@ -719,7 +719,7 @@ static int launch_rows_wave_kind(unsigned grid, size_t lds, hipStream_t st, cons
     auto kern = select_rows_wave<VEC, FULL>;
     static bool attr_done = false;
     if (!attr_done) {
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (512 + GR4AD_MAX_BEAM) * 8) != hipSuccess) return GR4AD_EHIP;
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (512 + GR4AD_MAX_BEAM + 2) * 8) != hipSuccess) return GR4AD_EHIP;
         attr_done = true;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, logits, cum, rows, n, V, m, cand);
@@ -751,7 +751,7 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
         unsigned long long *cand = (unsigned long long *)ws;
         if (V <= 8192 && V % 4 == 0 && ((uintptr_t)logits % 16) == 0 && g_select_mode != 1) {
             // one wavefront per row, four rows per workgroup
-            const size_t lds = 4 * (size_t)(512 + m) * sizeof(unsigned long long);  // <= 4 * (4 KB + 32 KB)
+            const size_t lds = 4 * (size_t)((512 + m + 1) & ~1) * sizeof(unsigned long long);  // <= 4 * (4 KB + 32 KB)
             const unsigned grid = (unsigned)ceil_div64(rows, 4);
             int s = GR4AD_OK;
             if (V <= 1024) s = launch_rows_wave<4>(grid, lds, st, logits, cum, rows, n, V, m, cand);
