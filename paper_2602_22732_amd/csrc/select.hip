@@ -5,7 +5,12 @@
 // section 4.2 Dynamic Beam Width).  The selection is two-stage, as TopK Pre-Cut
 // (appendix A.2) describes: every beam row first keeps its own min(b_t, V_t)
 // best tokens, then the request keeps the b_t best of those.  Both stages are
-// exact radix selections, so the result equals a full sort of all candidates.
+// exact selections, so the result equals a full sort of all candidates.
+// The per-row cut is tightened by a bound per request: the request's first row
+// holds its best beam, and that row's own cut already has b_t candidates, so no
+// candidate below the worst of them can survive.  The other rows write only what
+// reaches that bound (at most their own cut), compacted per request; with beams
+// of unequal scores that is a fraction of b_t per row.
 //
 // Candidates travel between the stages as unique 64-bit keys
 //     (order-preserving bits of the fp32 score) << 32 | (0xFFFFFFFF - flat index)
@@ -387,11 +392,16 @@ __device__ __noinline__ void select_row_radix_wave(const float (&sc)[VEC * 4], i
 // FULL: V == VEC*256, every register holds a token (the validity tests fold away)
 template <int VEC, bool FULL>
 __global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restrict__ logits, const float *__restrict__ cum, int64_t rows,
-                                                          int n, int V, int m, unsigned long long *__restrict__ cand) {
+                                                          int n, int V, int m, unsigned long long *__restrict__ cand, int64_t row_step,
+                                                          const unsigned long long *__restrict__ bound, int *__restrict__ req_count) {
+    // row_step: the launch visits rows 0, row_step, 2 row_step, ... of the logits (row_step = n: the first beam of every request).
+    // bound / req_count (both or neither): per request, a key no survivor can lie below; the launch then writes only
+    // the candidates that reach it (at most the row's m best), compacted per request behind a running count.
     extern __shared__ unsigned long long wave_lds[];  // per wavefront: 512 slots of histogram / list, then m slots of staged output
     const int lane = threadIdx.x % 64, wv = threadIdx.x / 64;
-    const int64_t row = (int64_t)blockIdx.x * 4 + wv;
-    if (row >= rows) return;  // whole wavefronts leave; nothing below synchronises across wavefronts
+    const int64_t vrow = (int64_t)blockIdx.x * 4 + wv;  // row of this launch
+    if (vrow >= rows) return;  // whole wavefronts leave; nothing below synchronises across wavefronts
+    const int64_t row = vrow * row_step;  // row of the logits
     unsigned long long *list = wave_lds + (size_t)wv * ((512 + m + 1) & ~1);  // even number of 8-byte slots: 16-byte accesses stay aligned
     int *hist = (int *)list;
     unsigned long long *stage = list + 512;
@@ -423,8 +433,37 @@ __global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restri
 #pragma unroll
     for (int i = 0; i < VEC * 4; i++) x[i] = c + (x[i] - lse);  // scores from here on (padding stays -inf)
 
-    unsigned long long *dst = cand + row * (int64_t)m;
+    unsigned long long *dst = cand + vrow * (int64_t)m;
     const uint32_t flat0 = (uint32_t)((row % n) * (int64_t)V);
+    if (bound) {
+        // Request-level bound: the request's first row alone has m candidates at or above `bound`, so nothing below it can
+        // survive the request's selection.  Rows that have at most m candidates there write exactly those - usually far
+        // fewer than m - and skip the histogram; the others fall through to the row's own top-m cut.
+        const int64_t req = row / n;
+        const float sstar = key_score((uint32_t)(bound[req] >> 32));
+        // one sweep: the candidates at or above the bound are compacted into the staging slots (as the cut below does, so that
+        // the keys leave in full wavefront stores); more than m of them means the row needs its own cut after all
+        int cnt = 0;
+        const uint32_t nflat = 0xFFFFFFFFu - flat0 - (uint32_t)lane * 4u;
+#pragma unroll
+        for (int i = 0; i < VEC * 4; i++) {
+            const bool hit = x[i] >= sstar;  // padding is -inf
+            const unsigned long long mk = __ballot(hit);
+            const unsigned long long st = ((unsigned long long)__float_as_uint(x[i] + 0.0f) << 32) | (nflat - (uint32_t)((i / 4) * 256 + (i % 4)));
+            const int at = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(mk >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mk, 0));
+            if (hit && at < m) stage[at] = st;
+            cnt += __popcll(mk);
+        }
+        const int take = cnt <= m ? cnt : m;
+        int base = 0;
+        if (lane == 0) base = atomicAdd(&req_count[req], take);
+        base = __shfl(base, 0, 64);
+        dst = cand + req * ((int64_t)n * m) + base;
+        if (cnt <= m) {
+            for (int i = lane; i < cnt; i += 64) dst[i] = staged_to_key(stage[i]);
+            return;
+        }
+    }
     if (m >= V) {  // nothing to cut: every token is a candidate
 #pragma unroll
         for (int j = 0; j < VEC; j++)
@@ -613,7 +652,8 @@ __device__ __forceinline__ bool select_request_binned(const unsigned long long *
     return true;
 }
 
-__global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned long long *__restrict__ cand, int64_t ncand, int V, int k,
+__global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned long long *__restrict__ cand, int64_t req_stride,
+                                                               const int *__restrict__ req_count, int V, int k,
                                                                int32_t *__restrict__ parent, int32_t *__restrict__ tok,
                                                                float *__restrict__ score, const int32_t *__restrict__ sid_old,
                                                                int32_t *__restrict__ sid_new, const int32_t *__restrict__ anc_old,
@@ -624,7 +664,8 @@ __global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned lo
     __shared__ int sel_digit, sel_krem, sel_cnt, out_cnt;
     const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
     const int64_t b = blockIdx.x;
-    const unsigned long long *src = cand + b * ncand;
+    const unsigned long long *src = cand + b * req_stride;  // the request's candidates: the first req_count[b] keys of its segment
+    const int64_t ncand = req_count[b];
     int kp = 1;
     while (kp < k) kp <<= 1;
 
@@ -715,26 +756,55 @@ static int g_select_mode = getenv("GR4AD_SELECT_MODE") ? atoi(getenv("GR4AD_SELE
 
 template <int VEC, bool FULL>
 static int launch_rows_wave_kind(unsigned grid, size_t lds, hipStream_t st, const float *logits, const float *cum, int64_t rows, int n,
-                                 int V, int m, unsigned long long *cand) {
+                                 int V, int m, unsigned long long *cand, int64_t row_step, const unsigned long long *bound, int *req_count) {
     auto kern = select_rows_wave<VEC, FULL>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (512 + GR4AD_MAX_BEAM + 2) * 8) != hipSuccess) return GR4AD_EHIP;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, logits, cum, rows, n, V, m, cand);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
     return GR4AD_OK;
 }
 template <int VEC>
 static int launch_rows_wave(unsigned grid, size_t lds, hipStream_t st, const float *logits, const float *cum, int64_t rows, int n, int V,
-                            int m, unsigned long long *cand) {
-    if (V == VEC * 256) return launch_rows_wave_kind<VEC, true>(grid, lds, st, logits, cum, rows, n, V, m, cand);
-    return launch_rows_wave_kind<VEC, false>(grid, lds, st, logits, cum, rows, n, V, m, cand);
+                            int m, unsigned long long *cand, int64_t row_step, const unsigned long long *bound, int *req_count) {
+    if (V == VEC * 256) return launch_rows_wave_kind<VEC, true>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
+    return launch_rows_wave_kind<VEC, false>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
+}
+static int launch_rows_wave_any(hipStream_t st, const float *logits, const float *cum, int64_t rows, int n, int V, int m,
+                                unsigned long long *cand, int64_t row_step, const unsigned long long *bound, int *req_count) {
+    const size_t lds = 4 * (size_t)((512 + m + 1) & ~1) * sizeof(unsigned long long);  // <= 4 * (4 KB + 32 KB)
+    const unsigned grid = (unsigned)ceil_div64(rows, 4);
+    if (V <= 1024) return launch_rows_wave<4>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
+    if (V <= 2048) return launch_rows_wave<8>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
+    if (V <= 4096) return launch_rows_wave<16>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
+    return launch_rows_wave<32>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
 }
 
+// bound[b] = smallest of the m keys the first row of request b kept (wavefront per request); count[b] = 0
+__global__ __launch_bounds__(256) void request_bound_kernel(const unsigned long long *__restrict__ cand0, int m, int B,
+                                                            unsigned long long *__restrict__ bound, int *__restrict__ req_count) {
+    const int lane = threadIdx.x % 64;
+    const int b = blockIdx.x * 4 + threadIdx.x / 64;
+    if (b >= B) return;
+    unsigned long long mn = ~0ull;
+    for (int i = lane; i < m; i += 64) { const unsigned long long k = cand0[(int64_t)b * m + i]; mn = k < mn ? k : mn; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { const unsigned long long t = __shfl_xor(mn, o, 64); mn = t < mn ? t : mn; }
+    if (lane == 0) { bound[b] = mn; req_count[b] = 0; }
+}
+__global__ __launch_bounds__(256) void fill_count_kernel(int *__restrict__ req_count, int B, int v) {
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b < B) req_count[b] = v;
+}
+
+// workspace: candidates [B][n*m] keys, then the first rows' cuts [B][m], the request bounds [B] and the request counts [B]
+static inline size_t sel_ws_cand(int B, int n, int m) { return align256((size_t)B * n * m * sizeof(unsigned long long)); }
+static inline size_t sel_ws_cand0(int B, int m) { return align256((size_t)B * m * sizeof(unsigned long long)); }
 size_t select_workspace_bytes(int B, int n, int V, int k) {
     int m = k < V ? k : V;
-    return align256((size_t)B * n * m * sizeof(unsigned long long));
+    return sel_ws_cand(B, n, m) + sel_ws_cand0(B, m) + align256((size_t)B * sizeof(unsigned long long)) + align256((size_t)B * sizeof(int));
 }
 
 int launch_select(const float *logits, const float *cum, int B, int n, int V, int k, void *ws, size_t ws_bytes, int32_t *parent,
@@ -746,19 +816,30 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
     const int m = k < V ? k : V;
     const int64_t rows = (int64_t)B * n;
     if (rows > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    unsigned long long *cand = (unsigned long long *)ws;
+    unsigned long long *cand0 = (unsigned long long *)((char *)ws + sel_ws_cand(B, n, m));
+    unsigned long long *bound = (unsigned long long *)((char *)cand0 + sel_ws_cand0(B, m));
+    int *req_count = (int *)((char *)bound + align256((size_t)B * sizeof(unsigned long long)));
+    const bool wave_path = V <= 8192 && V % 4 == 0 && ((uintptr_t)logits % 16) == 0 && g_select_mode != 1;
+    // Request-level bound (several rows per request, cut smaller than the row): the first row of a request holds its best
+    // beam; the m-th best candidate of that row is a score no survivor of the request can lie below.
+    const bool bounded = wave_path && n > 1 && k <= V && g_select_mode != 2;
     {
-        ProfScope ps(KC_SELECT_ROWS, st, 0.0, (double)rows * V * 4 + (double)rows * (k < V ? k : V) * 8);
-        unsigned long long *cand = (unsigned long long *)ws;
-        if (V <= 8192 && V % 4 == 0 && ((uintptr_t)logits % 16) == 0 && g_select_mode != 1) {
+        // algorithmic bytes: every logit once; the candidates written depend on the data (between k per request and m per row):
+        // the lower bound is counted when the request-level bound is in use
+        ProfScope ps(KC_SELECT_ROWS, st, 0.0, (double)rows * V * 4 + (bounded ? (double)B * k : (double)rows * m) * 8);
+        if (wave_path) {
             // one wavefront per row, four rows per workgroup
-            const size_t lds = 4 * (size_t)((512 + m + 1) & ~1) * sizeof(unsigned long long);  // <= 4 * (4 KB + 32 KB)
-            const unsigned grid = (unsigned)ceil_div64(rows, 4);
-            int s = GR4AD_OK;
-            if (V <= 1024) s = launch_rows_wave<4>(grid, lds, st, logits, cum, rows, n, V, m, cand);
-            else if (V <= 2048) s = launch_rows_wave<8>(grid, lds, st, logits, cum, rows, n, V, m, cand);
-            else if (V <= 4096) s = launch_rows_wave<16>(grid, lds, st, logits, cum, rows, n, V, m, cand);
-            else s = launch_rows_wave<32>(grid, lds, st, logits, cum, rows, n, V, m, cand);
-            if (s) return s;
+            int s;
+            if (bounded) {
+                if ((s = launch_rows_wave_any(st, logits, cum, B, n, V, m, cand0, n, nullptr, nullptr))) return s;
+                GR4AD_LAUNCH_CHECK();
+                hipLaunchKernelGGL(request_bound_kernel, dim3((unsigned)((B + 3) / 4)), dim3(256), 0, st, cand0, m, B, bound, req_count);
+                GR4AD_LAUNCH_CHECK();
+                if ((s = launch_rows_wave_any(st, logits, cum, rows, n, V, m, cand, 1, bound, req_count))) return s;
+            } else {
+                if ((s = launch_rows_wave_any(st, logits, cum, rows, n, V, m, cand, 1, nullptr, nullptr))) return s;
+            }
         } else {
             const size_t stage_bytes = (size_t)m * sizeof(unsigned long long);  // <= 32 KB (GR4AD_MAX_BEAM)
             if (V <= 1024)
@@ -770,10 +851,14 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
             else
                 hipLaunchKernelGGL(select_rows<64>, dim3((unsigned)rows), dim3(256), stage_bytes, st, logits, cum, n, V, m, cand);
         }
+        GR4AD_LAUNCH_CHECK();
+        if (!bounded) {  // every row wrote its m: the request's candidates are the n*m keys of its rows
+            hipLaunchKernelGGL(fill_count_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, st, req_count, B, n * m);
+            GR4AD_LAUNCH_CHECK();
+        }
     }
-    GR4AD_LAUNCH_CHECK();
-    ProfScope ps(KC_SELECT_REQUEST, st, 0.0, (double)rows * m * 8 + (double)B * k * 12);
-    hipLaunchKernelGGL(select_request, dim3((unsigned)B), dim3(SELB_THREADS), 0, st, (const unsigned long long *)ws, (int64_t)n * m, V, k,
+    ProfScope ps(KC_SELECT_REQUEST, st, 0.0, (bounded ? (double)B * k : (double)rows * m) * 8 + (double)B * k * 12);  // (same convention)
+    hipLaunchKernelGGL(select_request, dim3((unsigned)B), dim3(SELB_THREADS), 0, st, (const unsigned long long *)ws, (int64_t)n * m, req_count, V, k,
                        parent, tok, score, sid_old, sid_new, anc_old, anc_new, n, T, level);
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;

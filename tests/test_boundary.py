@@ -84,8 +84,13 @@ def test_init_rejects_null_pointers():
 
 def test_select_workspace_formula():
     L = binding.lib()
-    assert L.gr4ad_op_select_workspace_bytes(3, 5, 100, 7) == ((3 * 5 * 7 * 8 + 255) // 256) * 256
-    assert L.gr4ad_op_select_workspace_bytes(3, 5, 4, 7) == ((3 * 5 * 4 * 8 + 255) // 256) * 256
+    def expect(B, n, V, k):
+        # candidates [B][n*m] 64-bit keys, the first rows' cuts [B][m], request bounds [B] (64-bit), request counts [B] (32-bit)
+        m = min(k, V)
+        r = lambda x: (x + 255) // 256 * 256
+        return r(B * n * m * 8) + r(B * m * 8) + r(B * 8) + r(B * 4)
+    assert L.gr4ad_op_select_workspace_bytes(3, 5, 100, 7) == expect(3, 5, 100, 7)
+    assert L.gr4ad_op_select_workspace_bytes(3, 5, 4, 7) == expect(3, 5, 4, 7)
     assert L.gr4ad_op_select_workspace_bytes(0, 5, 4, 7) == 0
 
 
