@@ -1,4 +1,6 @@
 """GPU parity tests of the single-operation entry points against the CPU oracle's primitives."""
+import zlib
+
 import numpy as np
 import pytest
 import torch
@@ -58,6 +60,33 @@ def test_select_matches_oracle(B, n, V, k):
         wide = np.abs(np.diff(osc)).min() > 1e-5 if k > 1 else True
         if wide and (k == n * V or allsc.ravel()[np.argsort(-allsc.ravel())[k]] < osc[-1] - 1e-5):
             assert np.array_equal(flat, oflat)
+
+
+@pytest.mark.parametrize("profile", ["steep", "flat", "first_row_worst", "first_row_minus_inf"])
+@pytest.mark.parametrize("B,n,V,k", [(2, 24, 8192, 1024), (1, 9, 5000, 600), (2, 6, 4096, 4096), (1, 300, 512, 200)])
+def test_select_request_bound_regimes(profile, B, n, V, k):
+    # The per-row cut is tightened by a bound taken from each request's first row: rows far below it contribute
+    # nothing, rows level with it contribute about k each, and any row may be the first one.
+    rng = np.random.default_rng(zlib.crc32(repr((profile, B, n, V, k)).encode()))
+    logits = (rng.standard_normal((B, n, V)) * 1.2).astype(np.float32)
+    if profile == "steep":
+        cum = np.tile(-4.0 * np.arange(n, dtype=np.float32), (B, 1))
+    elif profile == "flat":
+        cum = np.full((B, n), -7.5, dtype=np.float32)
+    elif profile == "first_row_worst":
+        cum = np.tile(-3.0 * np.arange(n, dtype=np.float32)[::-1].copy(), (B, 1))
+    else:
+        cum = (-rng.random((B, n)) * 2).astype(np.float32)
+        cum[:, 0] = -np.inf
+    parent, tok, score = binding.op_select(torch.from_numpy(logits).cuda(), torch.from_numpy(cum).cuda(), k)
+    torch.cuda.synchronize()
+    parent, tok, score = parent.cpu().numpy(), tok.cpu().numpy(), score.cpu().numpy()
+    for b in range(B):
+        lp = np.stack([oracle.prim_log_softmax(logits[b, i]) for i in range(n)])
+        allsc = cum[b].astype(np.float64)[:, None] + lp
+        flat = parent[b].astype(np.int64) * V + tok[b]
+        assert len(set(flat.tolist())) == k
+        judge_selection(allsc, flat, score[b], k, tol=2e-5, margin=1e-5, what="%s b=%d" % (profile, b))
 
 
 def test_select_exact_ties_and_quantised_scores():
