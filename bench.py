@@ -8,7 +8,9 @@ and beam reorder.  Prints ONE JSON line (requests/s, plus candidates/s,
 beam-rows/s, the roofline of the dominant kernel and the CPU oracle timed on
 the host cores).
 
-    python bench.py [--config 4] [--steps 5] [--warmup 2] [--scale 1.0] [--no-cpu]
+    python bench.py [--config 5] [--scale 1.0] [--steps 5] [--warmup 2] [--no-cpu]
+
+Default: configuration 5 at beam scale 1.0, the largest-batch configuration (2048 requests).
 """
 import argparse
 import json
@@ -44,8 +46,8 @@ def algorithmic_flops(w, lens):
 
 
 def measured_traffic(cfg_id):
-    """HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by a copy
-    kernel of known size), read from the committed summary of that run: {kernel: bytes} or {}."""
+    """HBM bytes per decode_batch call and kernel class, measured with rocprofv3 counters (FETCH_SIZE + WRITE_SIZE,
+    scaled by a copy kernel of known size), read from the committed summary of that run: {kernel: bytes} or {}."""
     import re
     path = os.path.join(ROOT, "profiles", "decode_batch_config%d_hbm_traffic.md" % cfg_id)
     out = {}
@@ -77,7 +79,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5")
+    ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest-batch one)")
     ap.add_argument("--scale", type=float, default=1.0, help="beam scale of configuration 5")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -159,7 +161,8 @@ def main():
         elif rec["bytes"] > 0:
             k.update(bound="hbm", achieved=rec["bytes"] / sec / 1e9, peak=PEAK_HBM / 1e9, unit="GB/s", frac=rec["bytes"] / sec / PEAK_HBM,
                      bytes_per_launch=rec["bytes"] / rec["launches"])
-        k["traffic"] = traffic.get(name)
+        # the summary holds bytes per decode_batch call; per launch of this class as counted here
+        k["traffic"] = traffic[name] / k["launches_per_step"] if name in traffic and k["launches_per_step"] > 0 else None
         kernels[name] = k
     roofline = None
     if prof:

@@ -46,14 +46,15 @@ def test_config3_medium_bf16_sampled_requests():
 
 
 def test_config4_large_bf16_full_batch_sampled_requests():
-    # the workload bench.py times: B=1024, ragged context lengths, beams 256/512/512/1024
+    # B=1024, ragged context lengths, beams 256/512/512/1024 (bench.py --config 4)
     run_config(4, sample=[3, 1023])
 
 
 @pytest.mark.parametrize("scale,batch,sample", [
-    (0.25, 2048, [2047]),   # full batch at the narrowest schedule
-    (0.5, 96, [5]),         # the wider schedules on a slice of the batch (same model, same per-request work)
-    (1.0, 96, [95]),
+    (0.25, 2048, [2047]),   # the full batch of 2048 at every schedule of the sweep; one sampled request each
+    (0.5, 2048, [5]),
+    (1.0, 2048, [1095]),    # the workload bench.py times by default
+    (1.0, 96, [95]),        # and a slice of the batch: same model, same per-request work, another batch composition
 ])
 def test_config5_load_adaptive_sweep_with_zipf_bias(scale, batch, sample):
     run_config(5, sample=sample, batch=batch, scale=scale)
