@@ -81,6 +81,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest-batch one)")
     ap.add_argument("--scale", type=float, default=1.0, help="beam scale of configuration 5")
+    ap.add_argument("--lazy", type=int, default=None, help="number of lazy layers K of the same model (default: the configuration's; 0 = plain autoregressive decoding)")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
@@ -98,7 +99,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    w = synth.workload(args.config, scale=args.scale, batch=args.batch)
+    w = synth.workload(args.config, scale=args.scale, batch=args.batch, lazy=args.lazy)
     W = synth.make_weights(w)
     lens = synth.make_lengths(w)
     dev = torch.device("cuda:0")

@@ -53,8 +53,9 @@ def scale_beams(beam, factor):
     return [max(1, int(round(b * factor))) for b in beam]
 
 
-def workload(cfg, scale=1.0, batch=None):
-    """The five benchmark configurations (1-based)."""
+def workload(cfg, scale=1.0, batch=None, lazy=None):
+    """The five benchmark configurations (1-based).  lazy: another number of lazy layers K for the same
+    model (0 = every layer autoregressive, section 3.2's comparison of LazyAR with plain decoding)."""
     if cfg == 1:
         w = Workload("tiny-f32", "f32", 4, 64, 128, 2, 1, 4, 512, 3, [256] * 3, [16] * 3)
     elif cfg == 2:
@@ -72,6 +73,11 @@ def workload(cfg, scale=1.0, batch=None):
     w.cfg_id = cfg
     if batch is not None:
         w.B = batch
+    if lazy is not None:
+        if not 0 <= lazy < w.L:
+            raise ValueError("lazy must be in [0, L)")
+        w.K = lazy
+        w.name += "-K%d" % lazy
     return w
 
 

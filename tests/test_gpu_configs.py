@@ -19,8 +19,8 @@ def weights_of(w):
     return _weights[w.cfg_id]
 
 
-def run_config(cfg, sample, batch=None, scale=1.0):
-    w = synth.workload(cfg, scale=scale, batch=batch)
+def run_config(cfg, sample, batch=None, scale=1.0, lazy=None):
+    w = synth.workload(cfg, scale=scale, batch=batch, lazy=lazy)
     W = weights_of(w)
     lens = synth.make_lengths(w)
     X = synth.make_context(w, lens)
@@ -33,7 +33,7 @@ def run_config(cfg, sample, batch=None, scale=1.0):
     for r in range(0, w.B, max(1, w.B // 64)):
         assert len({tuple(p) for p in sid[r]}) == w.beam[-1], "returned SIDs of request %d are not distinct" % r
     stats = judge_decode(w, W, X, lens, sid, lp, tr, sample)
-    print("config %d (%s): %s" % (cfg, w.name, stats))
+    print("config %d (%s, K=%d): %s" % (cfg, w.name, w.K, stats))
     return stats
 
 
@@ -58,3 +58,10 @@ def test_config4_large_bf16_full_batch_sampled_requests():
 ])
 def test_config5_load_adaptive_sweep_with_zipf_bias(scale, batch, sample):
     run_config(5, sample=sample, batch=batch, scale=scale)
+
+
+@pytest.mark.parametrize("lazy", [0, 5])
+def test_config3_other_lazy_depths(lazy):
+    # section 3.2: the same model decoded with no lazy layer (plain autoregressive decoding, every layer per beam and
+    # level) and with all but one layer lazy; bench.py --lazy times these against the configuration's own depth
+    run_config(3, sample=[7], lazy=lazy)
