@@ -42,6 +42,14 @@ def algorithmic_flops(w, lens):
         "self_attn": sum(n * A * 4.0 * (t + 1) * d for t, n in enumerate(w.rows)),
         "classifier": sum(n * 2.0 * d * V for n, V in zip(w.rows, w.V)),
     }
+    if w.Ve > 0:  # eCPM-token step: one more position of the lazy pass and one more level for the b_T returned beams
+        n = float(w.beam[-1])
+        per_req["lazy"] *= (T + 1.0) / T
+        per_req["fuse"] += n * 2.0 * d * d
+        per_req["ar_gemm"] += n * A * (12.0 * d * d + 4.0 * d * F)
+        per_req["cross_attn"] += n * A * 4.0 * lens.mean() * d
+        per_req["self_attn"] += n * A * 4.0 * (T + 1) * d
+        per_req["classifier"] += n * 2.0 * d * w.Ve
     return {k: v * w.B for k, v in per_req.items()}
 
 
@@ -82,6 +90,7 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest-batch one)")
     ap.add_argument("--scale", type=float, default=1.0, help="beam scale of configuration 5")
     ap.add_argument("--lazy", type=int, default=None, help="number of lazy layers K of the same model (default: the configuration's; 0 = plain autoregressive decoding)")
+    ap.add_argument("--value", type=int, default=0, help="append an eCPM-token step with this many value buckets to the model and run it in every call (default: none)")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
@@ -99,7 +108,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    w = synth.workload(args.config, scale=args.scale, batch=args.batch, lazy=args.lazy)
+    w = synth.workload(args.config, scale=args.scale, batch=args.batch, lazy=args.lazy, value=args.value)
     W = synth.make_weights(w)
     lens = synth.make_lengths(w)
     dev = torch.device("cuda:0")
@@ -113,9 +122,10 @@ def main():
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     out_sid = torch.empty(w.B, w.beam[-1], w.T, dtype=torch.int32, device=dev)
     out_lp = torch.empty(w.B, w.beam[-1], dtype=torch.float32, device=dev)
+    out_val = torch.empty(w.B, w.beam[-1], w.Ve, dtype=torch.float32, device=dev) if w.Ve > 0 else None
 
     def step():
-        dec.decode_batch(ctx, ctx_len, w.beam, workspace=ws, out_sid=out_sid, out_logprob=out_lp)
+        dec.decode_batch(ctx, ctx_len, w.beam, workspace=ws, out_sid=out_sid, out_logprob=out_lp, value=w.Ve > 0, out_value=out_val)
 
     if args.calibrate_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
@@ -187,7 +197,7 @@ def main():
         "workspace_gib": ws_bytes / 2**30,
         "roofline": roofline, "kernels": kernels,
     }
-    if not args.no_cpu:
+    if not args.no_cpu and w.Ve == 0:  # the oracle's batch decode ends at the last SID level
         budget = {1: 4, 2: 64, 3: 16, 4: 2, 5: 2}[w.cfg_id]
         out["cpu_baseline"] = cpu_baseline(w, W, lens, budget)
     print(json.dumps(out))

@@ -59,6 +59,8 @@ typedef struct {
     int32_t max_ctx;         /* upper bound of S */
     gr4ad_dtype dtype;
     float rms_eps;           /* epsilon inside every RMSNorm */
+    int32_t n_value_buckets; /* V_e: size of the eCPM-token vocabulary of the value step (section 3.3), 0 = no value step;
+                              * with a value step T <= GR4AD_MAX_LEVELS - 1 */
 } gr4ad_model_desc;
 
 /* One decoder layer (section 3.2: cross-attention over X, self-attention over
@@ -81,6 +83,11 @@ typedef struct {
     const void *ln_out_dev;             /* [d]    gain of the final RMSNorm */
     const void *const *cls_dev;         /* host [T] -> [V_t,d]: classifier W_t */
     const float *const *cls_bias_dev;   /* NULL, or host [T] -> (NULL | [V_t] float32 logit bias) */
+    /* value step (only read when n_value_buckets > 0): the eCPM token is one more prediction step after s_T */
+    const void *value_pos_dev;          /* [d]      position embedding p_{T+1} */
+    const void *value_emb_dev;          /* [V_T,d]  embedding of s_T */
+    const void *value_cls_dev;          /* [V_e,d]  classifier over the eCPM buckets */
+    const float *value_bias_dev;        /* NULL or [V_e] float32 logit bias */
 } gr4ad_weights;
 
 typedef struct gr4ad_decoder gr4ad_decoder;
@@ -137,6 +144,19 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx_dev, const int32_t *c
  * by every later decode_batch call.  Pass three NULLs to switch it off.
  */
 int gr4ad_decode_set_trace(gr4ad_decoder *dec, int32_t *const *parent_dev, int32_t *const *tok_dev, float *const *score_dev);
+
+/*
+ * gr4ad_decode_set_value_output -- eCPM-token step (section 3.3, "ECPM-Aware
+ * Token Prediction": one more prediction step after the SID, used to re-rank
+ * the generated SIDs).  With a buffer set, every later decode_batch call runs
+ * that step for the b_T surviving beams of each request - Fuse with s_T, the
+ * autoregressive layers at position T+1, final norm, value classifier - with no
+ * beam expansion and writes log p(v | y, X):
+ *   out_value_logprob_dev  [B, b_T, V_e] float32, rows in the order of out_sid_dev.
+ * NULL switches the step off again (its workspace stays part of
+ * workspace_bytes).  EINVAL if the model has no value step.
+ */
+int gr4ad_decode_set_value_output(gr4ad_decoder *dec, float *out_value_logprob_dev);
 
 /* gr4ad_decode_free -- release everything init allocated.  NULL is a no-op. */
 void gr4ad_decode_free(gr4ad_decoder *dec);

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libgr4ad.so")
 F32, BF16 = 0, 1
 LAYER_FIELDS = ["ln_x", "wq_x", "wk_x", "wv_x", "wo_x", "ln_s", "wq_s", "wk_s", "wv_s", "wo_s", "ln_f", "w1", "w2"]
 EXPORTS = ["gr4ad_decode_init", "gr4ad_decode_workspace_bytes", "gr4ad_decode_batch", "gr4ad_decode_set_trace",
+           "gr4ad_decode_set_value_output",
            "gr4ad_decode_free", "gr4ad_strerror", "gr4ad_last_error", "gr4ad_op_linear", "gr4ad_op_select_workspace_bytes",
            "gr4ad_op_select", "gr4ad_op_cross_attention_workspace_bytes", "gr4ad_op_cross_attention", "gr4ad_op_gather_rows",
            "gr4ad_profile_enable",
@@ -28,7 +29,8 @@ _VP = C.c_void_p
 class ModelDesc(C.Structure):
     _fields_ = [("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ffn", C.c_int32), ("n_layers", C.c_int32),
                 ("n_lazy", C.c_int32), ("n_levels", C.c_int32), ("codebook", _IP), ("max_beam", _IP),
-                ("max_batch", C.c_int32), ("max_ctx", C.c_int32), ("dtype", C.c_int), ("rms_eps", C.c_float)]
+                ("max_batch", C.c_int32), ("max_ctx", C.c_int32), ("dtype", C.c_int), ("rms_eps", C.c_float),
+                ("n_value_buckets", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -38,7 +40,8 @@ class LayerWeights(C.Structure):
 class Weights(C.Structure):
     _fields_ = [("pos_dev", _VP), ("bos_dev", _VP), ("emb_dev", C.POINTER(_VP)), ("w_g_dev", _VP), ("w_f_dev", _VP),
                 ("layers", C.POINTER(LayerWeights)), ("ln_out_dev", _VP), ("cls_dev", C.POINTER(_VP)),
-                ("cls_bias_dev", C.POINTER(_VP))]
+                ("cls_bias_dev", C.POINTER(_VP)),
+                ("value_pos_dev", _VP), ("value_emb_dev", _VP), ("value_cls_dev", _VP), ("value_bias_dev", _VP)]
 
 
 class Gr4adError(RuntimeError):
@@ -65,6 +68,8 @@ def lib():
         L.gr4ad_decode_batch.argtypes = [_VP, _VP, _VP, C.c_int32, C.c_int32, _IP, _VP, C.c_size_t, _VP, _VP, _VP]
         L.gr4ad_decode_set_trace.restype = C.c_int
         L.gr4ad_decode_set_trace.argtypes = [_VP, C.POINTER(_VP), C.POINTER(_VP), C.POINTER(_VP)]
+        L.gr4ad_decode_set_value_output.restype = C.c_int
+        L.gr4ad_decode_set_value_output.argtypes = [_VP, _VP]
         L.gr4ad_decode_free.restype = None
         L.gr4ad_decode_free.argtypes = [_VP]
         L.gr4ad_strerror.restype = C.c_char_p
@@ -147,19 +152,24 @@ def weights_to_device(weights, dtype, device="cuda"):
     out["layers"] = [{n: dev(lw[n]) for n in LAYER_FIELDS} for lw in weights["layers"]]
     cb = weights.get("cls_bias")
     out["cls_bias"] = None if cb is None else [None if b is None else dev(b, torch.float32) for b in cb]
+    if weights.get("value_cls") is not None:  # eCPM-token step
+        for k in ("value_pos", "value_emb", "value_cls"):
+            out[k] = dev(weights[k])
+        vb = weights.get("value_bias")
+        out["value_bias"] = None if vb is None else dev(vb, torch.float32)
     return out
 
 
 class Decoder:
     """gr4ad_decode_init / gr4ad_decode_batch / gr4ad_decode_free."""
 
-    def __init__(self, d, H, F, L, K, T, V, dev_weights, dtype, max_beam, max_batch, max_ctx, eps=1e-6):
+    def __init__(self, d, H, F, L, K, T, V, dev_weights, dtype, max_beam, max_batch, max_ctx, eps=1e-6, Ve=0):
         self.L_ = lib()
         self.handle = None
-        self.T, self.V, self.d, self.dtype = T, list(V), d, dtype_code(dtype)
+        self.T, self.V, self.d, self.dtype, self.Ve = T, list(V), d, dtype_code(dtype), int(Ve)
         V_arr, V_ptr = _i32arr(self.V)
         mb_arr, mb_ptr = _i32arr(max_beam)
-        desc = ModelDesc(d, H, F, L, K, T, V_ptr, mb_ptr, max_batch, max_ctx, self.dtype, eps)
+        desc = ModelDesc(d, H, F, L, K, T, V_ptr, mb_ptr, max_batch, max_ctx, self.dtype, eps, self.Ve)
         w = dev_weights
         ptr = lambda t: C.c_void_p(t.data_ptr())
         emb = (_VP * max(T - 1, 1))(*[t.data_ptr() for t in w["emb"]])
@@ -169,7 +179,8 @@ class Decoder:
             bias = (_VP * T)(*[(b.data_ptr() if b is not None else None) for b in w["cls_bias"]])
         layers = (LayerWeights * L)(*[LayerWeights(*[lw[n].data_ptr() for n in LAYER_FIELDS]) for lw in w["layers"]])
         ws = Weights(ptr(w["pos"]), ptr(w["bos"]), emb, ptr(w["w_g"]), ptr(w["w_f"]), layers, ptr(w["ln_out"]), cls,
-                     bias if bias is not None else C.POINTER(_VP)())
+                     bias if bias is not None else C.POINTER(_VP)(),
+                     *[(w[k].data_ptr() if w.get(k) is not None else None) for k in ("value_pos", "value_emb", "value_cls", "value_bias")])
         h = _VP()
         _check(self.L_.gr4ad_decode_init(C.byref(desc), C.byref(ws), C.byref(h)))
         self.handle = h
@@ -201,9 +212,11 @@ class Decoder:
         _check(self.L_.gr4ad_decode_set_trace(self.handle, None, None, None), self.handle)
         self._trace = None
 
-    def decode_batch(self, ctx, ctx_len, beam, workspace=None, out_sid=None, out_logprob=None, stream=None):
+    def decode_batch(self, ctx, ctx_len, beam, workspace=None, out_sid=None, out_logprob=None, stream=None, value=False, out_value=None):
         """ctx [B,S,d] device tensor of the storage dtype; ctx_len [B] int32 device tensor or None.
-        Returns (sid [B,b_T,T] int32, logprob [B,b_T] float32) device tensors; asynchronous on the stream."""
+        Returns (sid [B,b_T,T] int32, logprob [B,b_T] float32) device tensors; asynchronous on the stream.
+        value=True (model with an eCPM-token step): also runs that step and returns, third, the
+        log-probabilities of the value buckets [B,b_T,V_e] float32 (gr4ad_decode_set_value_output)."""
         B, S, d = ctx.shape
         assert d == self.d and ctx.is_contiguous() and ctx.dtype == torch_dtype(self.dtype)
         beam_arr, beam_ptr = _i32arr(beam)
@@ -217,11 +230,19 @@ class Decoder:
             out_sid = torch.empty(B, bT, self.T, dtype=torch.int32, device=ctx.device)
         if out_logprob is None:
             out_logprob = torch.empty(B, bT, dtype=torch.float32, device=ctx.device)
+        if value or self.Ve > 0:
+            if value and out_value is None:
+                out_value = torch.empty(B, bT, self.Ve, dtype=torch.float32, device=ctx.device)
+            if value:
+                assert out_value.is_contiguous() and out_value.dtype == torch.float32 and out_value.numel() == B * bT * self.Ve
+            _check(self.L_.gr4ad_decode_set_value_output(self.handle, C.c_void_p(out_value.data_ptr()) if value else None), self.handle)
         cl = None if ctx_len is None else C.c_void_p(ctx_len.data_ptr())
         st = self.L_.gr4ad_decode_batch(self.handle, C.c_void_p(ctx.data_ptr()), cl, B, S, beam_ptr, C.c_void_p(workspace.data_ptr()),
                                         workspace.numel(), C.c_void_p(out_sid.data_ptr()), C.c_void_p(out_logprob.data_ptr()),
                                         _stream_ptr(stream))
         _check(st, self.handle)
+        if value:
+            return out_sid, out_logprob, out_value
         return out_sid, out_logprob
 
 
@@ -229,7 +250,7 @@ def decoder_for(workload, weights, max_beam=None, device="cuda"):
     """Decoder for a synth.Workload and its numpy weight dict."""
     w = workload
     dev_w = weights_to_device(weights, w.dtype, device)
-    dec = Decoder(w.d, w.H, w.F, w.L, w.K, w.T, w.V, dev_w, w.dtype, max_beam or list(w.beam), w.B, w.S, eps=w.eps)
+    dec = Decoder(w.d, w.H, w.F, w.L, w.K, w.T, w.V, dev_w, w.dtype, max_beam or list(w.beam), w.B, w.S, eps=w.eps, Ve=w.Ve)
     dec._keep = dev_w  # init copies the weights; kept only so callers may inspect them
     return dec
 

@@ -546,7 +546,8 @@ __global__ __launch_bounds__(256) void self_attn_step(const T *__restrict__ qkv,
 
 int launch_self_attention_step(gr4ad_dtype dtype, const void *qkv, const LevelBuffers &prev, const int32_t *anc, void *out, int64_t rows,
                                int pos, int T, int d, int H, hipStream_t st) {
-    if (rows <= 0 || pos < 0 || pos >= T || T > GR4AD_MAX_LEVELS || d % H) return GR4AD_EINVAL;
+    // T is the row stride of anc: positions 0..pos-1 are read from it, so pos == T (a step after the last level) is allowed
+    if (rows <= 0 || pos < 0 || pos > T || pos >= GR4AD_MAX_LEVELS || T > GR4AD_MAX_LEVELS || d % H) return GR4AD_EINVAL;
     if (pos > 0 && !anc) return GR4AD_EINVAL;
     for (int p = 0; p < pos; p++)
         if (!prev.p[p] || ((uintptr_t)prev.p[p] % 32) || prev.rows[p] < 1) return GR4AD_EINVAL;

@@ -90,6 +90,9 @@ int launch_broadcast_rows(gr4ad_dtype dtype, const void *pos, void *dst, int B, 
 int launch_gather_rows(gr4ad_dtype dtype, const void *src, const int32_t *parent, void *dst, int B, int n, int k, int64_t row_elems,
                        int64_t row_stride, hipStream_t st);
 
+// out[r, :] = logits[r, :] - log(sum(exp(logits[r, :])))   (float32 rows of V values)
+int launch_log_softmax_rows(const float *logits, float *out, int64_t rows, int V, hipStream_t st);
+
 // out[h][j][c] = w[h*dh + c][j] for a bf16 [d, d] weight (init-time)
 int launch_head_transpose(const void *w, void *out, int d, int H, hipStream_t st);
 

@@ -26,6 +26,8 @@ thread_local char g_init_error[512] = "";
 
 struct gr4ad_decoder {
     int d, H, F, L, K, T, A;
+    int Ve, Tp;  // value step: eCPM buckets (0 = none); Tp = T + (Ve > 0): positions the trunk computes, levels with tables
+    float *value_out;  // [B, b_T, Ve] log-probabilities of the value step, NULL = step off
     int V[GR4AD_MAX_LEVELS], max_beam[GR4AD_MAX_LEVELS];
     int max_batch, max_ctx;
     gr4ad_dtype dtype;
@@ -78,7 +80,7 @@ Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *be
     Plan p;
     memset(&p, 0, sizeof(p));
     const size_t e = dec->esz;
-    const int64_t d = dec->d, T = dec->T;
+    const int64_t d = dec->d, T = dec->T, Tp = dec->Tp;
     int64_t n = 1, nmax = 1, bmax = 1, logit_max = 0;
     size_t selmax = 0;
     for (int t = 0; t < T; t++) {
@@ -89,9 +91,13 @@ Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *be
         if (s > selmax) selmax = s;
         n = beam[t];
     }
+    if (dec->Ve > 0) {  // the value step: one more level of n = b_T rows, no selection
+        if (n > nmax) nmax = n;
+        if (n * dec->Ve > logit_max) logit_max = n * dec->Ve;
+    }
     p.nmax = nmax;
     p.bmax = bmax;
-    p.rows_max = B * (nmax > T ? nmax : T);
+    p.rows_max = B * (nmax > Tp ? nmax : Tp);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
     p.kv_ar = take((size_t)dec->A * B * S * 2 * d * e);
@@ -101,7 +107,7 @@ Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *be
     p.vt_ar = take((size_t)dec->A * p.vt_bytes);
     p.vt_lazy = take(lazy_kv ? p.vt_bytes : 0);
     if (dec->absorbed) {  // bf16 only
-        const int64_t Spad = (S + 63) / 64 * 64, RQ = T * dec->H;
+        const int64_t Spad = (S + 63) / 64 * 64, RQ = Tp * dec->H;
         p.xt = take((size_t)B * d * Spad * e);
         p.qp = take((size_t)B * RQ * d * e);
         p.zb = take((size_t)B * RQ * d * e);
@@ -109,22 +115,22 @@ Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *be
         p.pb = take((size_t)B * RQ * Spad * e);
     }
     p.ss = take((size_t)p.rows_max * (d / 64 + 1) * sizeof(float));  // partial sums of squares of the folded RMSNorm
-    p.trunk = take((size_t)B * T * d * sizeof(float));  // residual streams stay float32 whatever the storage dtype
+    p.trunk = take((size_t)B * Tp * d * sizeof(float));  // residual streams stay float32 whatever the storage dtype
     p.h = take((size_t)p.rows_max * d * sizeof(float));
     p.xn = take((size_t)p.rows_max * d * e);
     p.q = take((size_t)p.rows_max * d * e);
     p.o = take((size_t)p.rows_max * d * e);
-    p.qkv = take((size_t)B * T * 3 * d * e);  // lazy layers; the autoregressive layers keep one buffer per (level, layer), below
+    p.qkv = take((size_t)B * Tp * 3 * d * e);  // lazy layers; the autoregressive layers keep one buffer per (level, layer), below
     p.f = take((size_t)p.rows_max * dec->F * e);
     p.logits = take((size_t)B * logit_max * sizeof(float));
     p.selws = take(selmax);
     // q/k/v of every level stay resident: they are the self-attention cache of the later levels, read through the
-    // beams' ancestor table (the last level's are only read by that level itself)
+    // beams' ancestor table.  No level follows the last one, so its layers share one buffer.
     n = 1;
-    for (int t = 0; t < T; t++) {
+    for (int t = 0; t < Tp; t++) {
         p.qkv_lvl_layer_bytes[t] = align256((size_t)B * n * 3 * d * e);
-        p.qkv_lvl[t] = take((size_t)dec->A * p.qkv_lvl_layer_bytes[t]);
-        n = beam[t];
+        p.qkv_lvl[t] = take((size_t)(t == Tp - 1 ? 1 : dec->A) * p.qkv_lvl_layer_bytes[t]);
+        if (t < T) n = beam[t];
     }
     for (int i = 0; i < 2; i++) p.cum[i] = take((size_t)B * bmax * sizeof(float));
     p.par = take((size_t)B * bmax * sizeof(int32_t));
@@ -196,6 +202,10 @@ int validate_desc(const gr4ad_model_desc *ds) {
     if (ds->n_levels < 1 || ds->n_levels > GR4AD_MAX_LEVELS) return fail(nullptr, GR4AD_EINVAL, "n_levels %d outside [1,%d]", ds->n_levels, GR4AD_MAX_LEVELS);
     if (ds->dtype != GR4AD_F32 && ds->dtype != GR4AD_BF16) return fail(nullptr, GR4AD_EINVAL, "unknown dtype %d", (int)ds->dtype);
     if (!(ds->rms_eps >= 0.0f)) return fail(nullptr, GR4AD_EINVAL, "rms_eps must be >= 0");
+    if (ds->n_value_buckets < 0 || ds->n_value_buckets > GR4AD_MAX_CODEBOOK)
+        return fail(nullptr, GR4AD_EINVAL, "n_value_buckets %d outside [0,%d]", ds->n_value_buckets, GR4AD_MAX_CODEBOOK);
+    if (ds->n_value_buckets > 0 && ds->n_levels + 1 > GR4AD_MAX_LEVELS)
+        return fail(nullptr, GR4AD_EUNSUPPORTED, "a value step needs n_levels <= %d", GR4AD_MAX_LEVELS - 1);
     for (int t = 0; t < ds->n_levels; t++) {
         if (ds->codebook[t] < 1 || ds->max_beam[t] < 1) return fail(nullptr, GR4AD_EINVAL, "codebook/max_beam of level %d must be >= 1", t + 1);
         if (ds->codebook[t] > GR4AD_MAX_CODEBOOK) return fail(nullptr, GR4AD_EUNSUPPORTED, "codebook %d of level %d exceeds %d", ds->codebook[t], t + 1, GR4AD_MAX_CODEBOOK);
@@ -216,6 +226,8 @@ int validate_weights(const gr4ad_model_desc *ds, const gr4ad_weights *w) {
         if (!w->emb_dev[t]) return fail(nullptr, GR4AD_EINVAL, "emb_dev[%d] is NULL", t);
     for (int t = 0; t < ds->n_levels; t++)
         if (!w->cls_dev[t]) return fail(nullptr, GR4AD_EINVAL, "cls_dev[%d] is NULL", t);
+    if (ds->n_value_buckets > 0 && (!w->value_pos_dev || !w->value_emb_dev || !w->value_cls_dev))
+        return fail(nullptr, GR4AD_EINVAL, "a value-step weight pointer is NULL");
     for (int l = 0; l < ds->n_layers; l++) {
         const gr4ad_layer_weights *x = &w->layers[l];
         const void *all[] = {x->ln_x, x->wq_x, x->wk_x, x->wv_x, x->wo_x, x->ln_s, x->wq_s, x->wk_s, x->wv_s, x->wo_s, x->ln_f, x->w1, x->w2};
@@ -229,13 +241,22 @@ int init_impl(gr4ad_decoder *dec, const gr4ad_model_desc *ds, const gr4ad_weight
     const size_t e = dec->esz, d = dec->d, F = dec->F;
     HIP_TRY(dec, hipGetDevice(&dec->device));
     int s;
-    if ((s = dev_clone(dec, &dec->pos, w->pos_dev, dec->T * d * e))) return s;
+    if ((s = dev_alloc(dec, &dec->pos, dec->Tp * d * e))) return s;  // p_1..p_T, then p_{T+1} of the value step
+    HIP_TRY(dec, hipMemcpy(dec->pos, w->pos_dev, dec->T * d * e, hipMemcpyDeviceToDevice));
+    if (dec->Ve > 0) HIP_TRY(dec, hipMemcpy((char *)dec->pos + dec->T * d * e, w->value_pos_dev, d * e, hipMemcpyDeviceToDevice));
     if ((s = dev_clone(dec, &dec->ln_out, w->ln_out_dev, d * e))) return s;
     for (int t = 0; t < dec->T; t++) {
         if ((s = dev_clone(dec, &dec->cls[t], w->cls_dev[t], (size_t)dec->V[t] * d * e))) return s;
         dec->cls_bias[t] = nullptr;
         if (w->cls_bias_dev && w->cls_bias_dev[t])
             if ((s = dev_clone(dec, (void **)&dec->cls_bias[t], w->cls_bias_dev[t], (size_t)dec->V[t] * sizeof(float)))) return s;
+    }
+    if (dec->Ve > 0) {  // the value step is level T+1 with its own classifier
+        const int T = dec->T;
+        if ((s = dev_clone(dec, &dec->cls[T], w->value_cls_dev, (size_t)dec->Ve * d * e))) return s;
+        dec->cls_bias[T] = nullptr;
+        if (w->value_bias_dev)
+            if ((s = dev_clone(dec, (void **)&dec->cls_bias[T], w->value_bias_dev, (size_t)dec->Ve * sizeof(float)))) return s;
     }
     dec->layers.resize(dec->L);
     for (int l = 0; l < dec->L; l++) {
@@ -267,8 +288,8 @@ int init_impl(gr4ad_decoder *dec, const gr4ad_model_desc *ds, const gr4ad_weight
     if ((s = dev_clone(dec, &wg, w->w_g_dev, d * d * e))) return s;
     HIP_TRY(dec, hipMemcpy2D(dec->wf1, d * e, w->w_f_dev, 2 * d * e, d * e, d, hipMemcpyDeviceToDevice));
     HIP_TRY(dec, hipMemcpy2D(wf2, d * e, (const char *)w->w_f_dev + d * e, 2 * d * e, d * e, d, hipMemcpyDeviceToDevice));
-    for (int t = 0; t < dec->T; t++) {
-        const void *emb = t == 0 ? w->bos_dev : w->emb_dev[t - 1];
+    for (int t = 0; t < dec->Tp; t++) {
+        const void *emb = t == 0 ? w->bos_dev : t == dec->T ? w->value_emb_dev : w->emb_dev[t - 1];
         const int64_t rows = t == 0 ? 1 : dec->V[t - 1];
         if ((s = dev_alloc(dec, &dec->G[t], rows * d * sizeof(float)))) return s;
         if ((s = dev_alloc(dec, &dec->P[t], rows * d * sizeof(float)))) return s;
@@ -309,6 +330,7 @@ int gr4ad_decode_init(const gr4ad_model_desc *ds, const gr4ad_weights *w, gr4ad_
     dec->T = ds->n_levels; dec->A = dec->L - dec->K; dec->max_batch = ds->max_batch; dec->max_ctx = ds->max_ctx;
     dec->dtype = ds->dtype; dec->esz = ds->dtype == GR4AD_BF16 ? 2 : 4; dec->eps = ds->rms_eps;
     dec->trace = false; dec->err[0] = 0;
+    dec->Ve = ds->n_value_buckets; dec->Tp = dec->T + (dec->Ve > 0 ? 1 : 0); dec->value_out = nullptr;
     {
         // The lazy layers attend with only T queries per request, so projecting every context row to keys and values
         // would dominate them.  Where the batched matrix-core kernel covers the shapes they use the absorbed form instead.
@@ -317,6 +339,7 @@ int gr4ad_decode_init(const gr4ad_model_desc *ds, const gr4ad_weights *w, gr4ad_
         dec->absorbed = dec->K > 0 && dec->dtype == GR4AD_BF16 && dh % 64 == 0 && !(env && !strcmp(env, "kv"));
     }
     for (int t = 0; t < dec->T; t++) { dec->V[t] = ds->codebook[t]; dec->max_beam[t] = ds->max_beam[t]; }
+    if (dec->Ve > 0) dec->V[dec->T] = dec->Ve;
     s = init_impl(dec, ds, w);
     if (s) {
         snprintf(g_init_error, sizeof(g_init_error), "%s", dec->err);
@@ -349,6 +372,13 @@ int gr4ad_decode_set_trace(gr4ad_decoder *dec, int32_t *const *parent_dev, int32
     return GR4AD_OK;
 }
 
+int gr4ad_decode_set_value_output(gr4ad_decoder *dec, float *out_value_logprob_dev) {
+    if (!dec) return GR4AD_EINVAL;
+    if (dec->Ve <= 0) return fail(dec, GR4AD_EINVAL, "the model has no value step (n_value_buckets = 0)");
+    dec->value_out = out_value_logprob_dev;
+    return GR4AD_OK;
+}
+
 int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_len, int32_t B, int32_t S, const int32_t *beam,
                        void *workspace, size_t workspace_bytes, int32_t *out_sid, float *out_logprob, void *hip_stream) {
     if (!dec) return GR4AD_EINVAL;
@@ -366,11 +396,15 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     const gr4ad_dtype dt = dec->dtype;
     const size_t e = dec->esz;
     const int d = dec->d, F = dec->F, T = dec->T, H = dec->H, A = dec->A, K = dec->K;
+    // positions of the lazy pass and steps of the level loop: the value step (section 3.3) is one more level after s_T that
+    // ends in a log-softmax instead of a selection.  The lazy pass is causal, so the first T positions do not depend on it.
+    const bool value_step = dec->Ve > 0 && dec->value_out;
+    const int Tq = value_step ? T + 1 : T;
     char *ws = (char *)workspace;
     void *h = ws + p.h, *xn = ws + p.xn, *q = ws + p.q, *o = ws + p.o, *qkv = ws + p.qkv, *f = ws + p.f, *trunk = ws + p.trunk;
     float *logits = (float *)(ws + p.logits);
     auto kv_ar = [&](int a) { return (void *)(ws + p.kv_ar + (size_t)a * B * S * 2 * d * e); };
-    auto qkv_lvl = [&](int t, int a) { return (void *)(ws + p.qkv_lvl[t] + (size_t)a * p.qkv_lvl_layer_bytes[t]); };
+    auto qkv_lvl = [&](int t, int a) { return (void *)(ws + p.qkv_lvl[t] + (size_t)(t == dec->Tp - 1 ? 0 : a) * p.qkv_lvl_layer_bytes[t]); };
 
     auto gemm = [&](const void *Ain, int64_t M, const void *W, int N, int Kdim, const GemmEpilogue &epi) {
         return launch_gemm(dt, Ain, Kdim, W, Kdim, M, N, Kdim, epi, st);
@@ -460,7 +494,7 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     // per request.  Same function of the inputs as eq. trunk's cross-attention; the intermediate roundings to bf16
     // fall on q' = W_{k,h}^T q_h and z = sum_s p_s x_s instead of on k_s and v_s.
     auto absorbed_cross_block = [&](const LayerPacked &lw, bool first) -> int {
-        const int64_t rows = (int64_t)B * T, RQ = (int64_t)T * H;
+        const int64_t rows = (int64_t)B * Tq, RQ = (int64_t)Tq * H;
         const int dh = d / H, Spad = (S + 63) / 64 * 64;
         char *xt = ws + p.xt, *qp = ws + p.qp, *zb = ws + p.zb, *pb = ws + p.pb;
         float *sc = (float *)(ws + p.sc);
@@ -482,30 +516,30 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     };
 
     // ---- step 1: lazy pass (eq. trunk): all T levels at once, no beam dimension ----
-    OP_TRY(dec, launch_broadcast_rows(dt, dec->pos, trunk, B, T, d, st), "trunk input");
-    fold = K > 0 && fold_ok((int64_t)B * T, 0);
+    OP_TRY(dec, launch_broadcast_rows(dt, dec->pos, trunk, B, Tq, d, st), "trunk input");
+    fold = K > 0 && fold_ok((int64_t)B * Tq, 0);
     for (int l = 0; l < K; l++) {
         const LayerPacked &lw = dec->layers[l];
         void *kvl = ws + p.kv_lazy;
-        const int64_t rows = (int64_t)B * T;
+        const int64_t rows = (int64_t)B * Tq;
         if (dec->absorbed) {
             OP_TRY(dec, absorbed_cross_block(lw, l == 0), "lazy cross-attention (absorbed form)");
         } else {
             OP_TRY(dec, context_kv(lw, kvl, vt_lazy), "lazy context K/V projection");
-            OP_TRY(dec, cross_block(lw, trunk, rows, T, kvl, vt_lazy), "lazy cross-attention");
+            OP_TRY(dec, cross_block(lw, trunk, rows, Tq, kvl, vt_lazy), "lazy cross-attention");
         }
         OP_TRY(dec, norm(trunk, lw.ln_s, rows), "lazy norm");
         OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, reads_norm(plain_epilogue(qkv, 3 * d))), "lazy qkv");
-        OP_TRY(dec, launch_trunk_self_attention(dt, qkv, o, B, T, d, H, st), "lazy self-attention");
+        OP_TRY(dec, launch_trunk_self_attention(dt, qkv, o, B, Tq, d, H, st), "lazy self-attention");
         OP_TRY(dec, gemm(o, rows, lw.wo_s, d, d, emit_norm(resid_epi(trunk, d), lw.ln_f)), "lazy self-attention output");
         OP_TRY(dec, ffn_block(lw, trunk, rows, l + 1 < K ? dec->layers[l + 1].ln_x : nullptr), "lazy FFN");
     }
 
     // ---- level loop (eq. fuse, eq. head, classifier, selection, reorder) ----
     int n = 1, cur = 0;
-    for (int t = 0; t < T; t++) {
+    for (int t = 0; t < Tq; t++) {
         const int64_t rows = (int64_t)B * n;
-        const int bt = beam[t];
+        const int bt = t < T ? beam[t] : n;  // the value step keeps every beam
         const int32_t *tok_prev = t == 0 ? nullptr : (const int32_t *)(ws + p.tok[cur]);
         fold = fold_ok(rows, dec->V[t]);
         scaled = false;
@@ -513,7 +547,7 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         {
             // the gated embedding goes through q when the Fuse projection also writes the first norm's input into xn
             void *gated = fold ? q : xn;
-            OP_TRY(dec, launch_fuse_gate(dt, (const float *)trunk + (size_t)t * d, (int64_t)T * d, dec->G[t], tok_prev, gated, B, n, d, st), "Fuse gate");
+            OP_TRY(dec, launch_fuse_gate(dt, (const float *)trunk + (size_t)t * d, (int64_t)Tq * d, dec->G[t], tok_prev, gated, B, n, d, st), "Fuse gate");
             GemmEpilogue g = plain_epilogue(h, d);
             g.out_f32 = 1;
             g.table = (const float *)dec->P[t];
@@ -542,13 +576,17 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
             g.bias = dec->cls_bias[t];
             OP_TRY(dec, gemm(xn, rows, dec->cls[t], dec->V[t], d, reads_norm(g)), "classifier");
         }
+        if (t == T) {  // value step: log p(v | y, X) for every surviving beam, in the order of out_sid
+            OP_TRY(dec, launch_log_softmax_rows(logits, dec->value_out, rows, dec->Ve, st), "value log-softmax");
+            break;
+        }
         const bool last = t == T - 1;
         int32_t *par = (int32_t *)(ws + p.par), *tok_new = (int32_t *)(ws + p.tok[cur ^ 1]);
         float *score_new = last ? out_logprob : (float *)(ws + p.cum[cur ^ 1]);
         int32_t *sid_new = last ? out_sid : (int32_t *)(ws + p.sid[cur ^ 1]);
         OP_TRY(dec, launch_select(logits, t == 0 ? nullptr : (const float *)(ws + p.cum[cur]), B, n, dec->V[t], bt, ws + p.selws,
                                   select_workspace_bytes(B, n, dec->V[t], bt), par, tok_new, score_new, (const int32_t *)(ws + p.sid[cur]),
-                                  sid_new, (const int32_t *)(ws + p.anc[cur]), last ? nullptr : (int32_t *)(ws + p.anc[cur ^ 1]), T, t, st),
+                                  sid_new, (const int32_t *)(ws + p.anc[cur]), last && !value_step ? nullptr : (int32_t *)(ws + p.anc[cur ^ 1]), T, t, st),
                "selection");
         if (dec->trace) {
             const size_t nb = (size_t)B * bt * 4;

@@ -230,3 +230,33 @@ int launch_row_inv(const float *ss, float *inv, int64_t rows, int parts, int dim
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }
+
+// ---------------------------------------------------------------------------
+// row-wise log-softmax of float32 logits (value step: no selection follows, the whole distribution is the output)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void log_softmax_rows_kernel(const float *__restrict__ logits, float *__restrict__ out, int64_t rows, int V) {
+    // one wave per row; the row is read three times (maximum, sum, write), the second and third time from cache
+    const int lane = threadIdx.x % 64;
+    const int64_t r = (int64_t)blockIdx.x * 4 + threadIdx.x / 64;
+    if (r >= rows) return;
+    const float *x = logits + r * V;
+    float mx = -INFINITY;
+    for (int c = lane; c < V; c += 64) mx = fmaxf(mx, x[c]);
+    mx = wave_max(mx);
+    float s = 0.0f;
+    for (int c = lane; c < V; c += 64) s += __expf(x[c] - mx);
+    s = wave_sum(s);
+    const float lse = mx + __logf(s);
+    float *y = out + r * V;
+    for (int c = lane; c < V; c += 64) y[c] = x[c] - lse;
+}
+
+int launch_log_softmax_rows(const float *logits, float *out, int64_t rows, int V, hipStream_t st) {
+    if (!logits || !out || rows < 1 || V < 1) return GR4AD_EINVAL;
+    const int64_t grid = ceil_div64(rows, 4);
+    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    ProfScope ps(KC_SOFTMAX, st, 0.0, (double)rows * V * 2 * sizeof(float));
+    hipLaunchKernelGGL(log_softmax_rows_kernel, dim3((unsigned)grid), dim3(256), 0, st, logits, out, rows, V);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}

@@ -34,6 +34,7 @@ class Workload:
     zipf_bias: bool = False
     eps: float = 1e-6
     cfg_id: int = 0
+    Ve: int = 0  # eCPM-token step (section 3.3): number of value buckets, 0 = the model has no such step
     extra: dict = field(default_factory=dict)
 
     @property
@@ -53,9 +54,10 @@ def scale_beams(beam, factor):
     return [max(1, int(round(b * factor))) for b in beam]
 
 
-def workload(cfg, scale=1.0, batch=None, lazy=None):
+def workload(cfg, scale=1.0, batch=None, lazy=None, value=None):
     """The five benchmark configurations (1-based).  lazy: another number of lazy layers K for the same
-    model (0 = every layer autoregressive, section 3.2's comparison of LazyAR with plain decoding)."""
+    model (0 = every layer autoregressive, section 3.2's comparison of LazyAR with plain decoding).
+    value: number of eCPM buckets of a value step appended to the model (section 3.3); None or 0 = none."""
     if cfg == 1:
         w = Workload("tiny-f32", "f32", 4, 64, 128, 2, 1, 4, 512, 3, [256] * 3, [16] * 3)
     elif cfg == 2:
@@ -78,6 +80,9 @@ def workload(cfg, scale=1.0, batch=None, lazy=None):
             raise ValueError("lazy must be in [0, L)")
         w.K = lazy
         w.name += "-K%d" % lazy
+    if value:
+        w.Ve = int(value)
+        w.name += "-value%d" % w.Ve
     return w
 
 
@@ -145,6 +150,14 @@ def make_weights(w: Workload, seed=None, gain_jitter=0.1):
     if w.zipf_bias:
         # Zipf(1.1) popularity: bias = -1.1 ln(rank), rank a seeded permutation of 1..V
         out["cls_bias"] = [(-1.1 * np.log(rng().permutation(w.V[t]) + 1.0)).astype(np.float32) for t in range(T)]
+    if w.Ve > 0:
+        # eCPM-token step: position T+1, the embedding of s_T, a classifier over the V_e buckets.  Drawn from generators
+        # of their own so that the other weights are the same with and without the step.
+        vr = [np.random.default_rng(seed + 500 + i) for i in range(3)]
+        out["value_pos"] = _store(vr[0].standard_normal(d).astype(np.float32), w.dtype)
+        out["value_emb"] = _store(vr[1].standard_normal((w.V[T - 1], d)).astype(np.float32), w.dtype)
+        out["value_cls"] = _store(_xavier(vr[2], w.Ve, d), w.dtype)
+        out["value_bias"] = None
     # storage rounding (biases stay fp32 on both sides)
     for key in ("pos", "bos", "w_g", "w_f", "ln_out"):
         out[key] = _store(out[key], w.dtype)
@@ -152,6 +165,22 @@ def make_weights(w: Workload, seed=None, gain_jitter=0.1):
     out["cls"] = [_store(a, w.dtype) for a in out["cls"]]
     out["layers"] = [{n: _store(a, w.dtype) for n, a in lw.items()} for lw in out["layers"]]
     return out
+
+
+def value_model(w: Workload, W):
+    """The eCPM-token step is one more prediction step after s_T: the same decoder seen as a model of T+1 levels whose
+    last codebook is the value vocabulary.  Returns (model_kwargs, weights) of that model; no arithmetic, only
+    the weights of the step appended to the per-level lists."""
+    assert w.Ve > 0
+    kw = w.model_kwargs()
+    kw["T"], kw["V"] = w.T + 1, list(w.V) + [w.Ve]
+    X = dict(W)
+    X["pos"] = np.concatenate([W["pos"], W["value_pos"][None, :]], axis=0)
+    X["emb"] = list(W["emb"]) + [W["value_emb"]]
+    X["cls"] = list(W["cls"]) + [W["value_cls"]]
+    cb, vb = W.get("cls_bias"), W.get("value_bias")
+    X["cls_bias"] = None if cb is None and vb is None else (list(cb) if cb is not None else [None] * w.T) + [vb]
+    return kw, X
 
 
 def make_lengths(w: Workload, seed=None):

@@ -13,21 +13,29 @@ TOL_LOGPROB = {"f32": 1e-4, "bf16": 2e-2}
 # also holds is reported by judge_decode ("strict_ok").
 MARGIN = {"f32": 1e-3, "bf16": 4e-2}
 STRICT_MARGIN = 1e-3
+# Value step: all V_e log-probabilities of all b_T rows are output and judged, not only the k survivors of a level, so the
+# largest error is taken over some hundred times more values of the same rounding noise (measured at configuration 3 with 256
+# buckets: mean 4.5e-3, largest of 262144 values 2.9e-2, against 1.4e-2 for the largest of its 1792 survivor scores).  Every
+# value must lie within twice the survivor tolerance, and each row's distribution within 1e-2 of the oracle's in total
+# variation (what re-ranking by the predicted value sees).
+TOL_VALUE = {"f32": 1e-4, "bf16": 4e-2}
+TOL_VALUE_TV = {"f32": 1e-4, "bf16": 1e-2}
 
 
-def gpu_decode(w, W, X, lens, beam=None, trace=True, max_beam=None):
-    """Decode on the GPU.  Returns sid, logprob (numpy) and the per-level trace."""
+def gpu_decode(w, W, X, lens, beam=None, trace=True, max_beam=None, value=False):
+    """Decode on the GPU.  Returns sid, logprob (numpy) and the per-level trace; with value=True also, fourth, the
+    value step's log-probabilities [B, b_T, V_e]."""
     beam = list(w.beam if beam is None else beam)
     dec = binding.decoder_for(w, W, max_beam=max_beam or beam)
     ctx = torch.from_numpy(X).to("cuda", dtype=binding.torch_dtype(w.dtype)).contiguous()
     cl = None if lens is None else torch.from_numpy(np.asarray(lens, np.int32)).cuda()
     tr = dec.enable_trace(ctx.shape[0], beam) if trace else None
-    sid, lp = dec.decode_batch(ctx, cl, beam)
+    res = dec.decode_batch(ctx, cl, beam, value=value)
     torch.cuda.synchronize()
-    out = sid.cpu().numpy(), lp.cpu().numpy()
+    out = [t.cpu().numpy() for t in res]
     trace_np = None if tr is None else {k: [t.cpu().numpy() for t in v] for k, v in tr.items()}
     dec.close()
-    return out[0], out[1], trace_np
+    return (out[0], out[1], trace_np) + ((out[2],) if value else ())
 
 
 def prefixes_from_trace(trace, r, T):
@@ -98,3 +106,28 @@ def judge_decode(w, W, X, lens, sid, lp, trace, requests, beam=None, tol=None, m
         assert np.array_equal(lp[r], trace["score"][-1][r])
         assert (np.diff(lp[r]) <= 0).all()
     return stats
+
+
+def judge_value(w, W, X, lens, sid, lp, val, requests, tol=None):
+    """eCPM-token step: for the listed requests the oracle, teacher-forced on the SIDs the GPU returned, gives
+    log p(v | y, X) of every returned SID (the decoder as a model of T+1 levels); the GPU's rows must agree within
+    the log-probability tolerance, and so must the SID scores.  Returns the largest and the mean error seen."""
+    tol_sid = TOL_LOGPROB[w.dtype] if tol is None else tol
+    tol = TOL_VALUE[w.dtype] if tol is None else 2 * tol
+    kw, Wv = synth.value_model(w, W)
+    o = oracle.Oracle(weights=Wv, **kw)
+    worst, total, count = 0.0, 0.0, 0
+    for r in requests:
+        rq = o.request(X[r], None if lens is None else int(lens[r]))
+        cum, dist = rq.prefix_dists(w.T + 1, sid[r])
+        assert val[r].shape == dist.shape
+        assert np.abs(np.exp(val[r].astype(np.float64)).sum(axis=1) - 1).max() < 1e-4, "value rows are not distributions"
+        err = float(np.abs(val[r] - dist).max())
+        assert err <= tol, "request %d: value log-probability error %.3g > %.3g" % (r, err, tol)
+        assert np.abs(cum - lp[r]).max() <= tol_sid
+        tv = 0.5 * np.abs(np.exp(val[r].astype(np.float64)) - np.exp(dist)).sum(axis=1).max()
+        assert tv <= TOL_VALUE_TV[w.dtype] * (tol_sid / TOL_LOGPROB[w.dtype]), "request %d: total variation %.3g" % (r, tv)
+        worst = max(worst, err)
+        total += float(np.abs(val[r] - dist).sum())
+        count += dist.size
+    return worst, total / count

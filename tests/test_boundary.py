@@ -37,6 +37,7 @@ def test_strerror_and_null_handling():
     assert L.gr4ad_decode_workspace_bytes(None, 1, 1, beam) == 0
     assert L.gr4ad_decode_batch(None, None, None, 1, 1, beam, None, 0, None, None, None) == -1
     assert L.gr4ad_decode_set_trace(None, None, None, None) == -1
+    assert L.gr4ad_decode_set_value_output(None, None) == -1
 
 
 def _desc(**over):
@@ -61,6 +62,8 @@ def _desc(**over):
     (dict(d_model=48, n_heads=2), -2, "head width"),
     (dict(max_beam=[4, 5000, 4]), -2, "max_beam"),
     (dict(codebook=[8, 8, 20000]), -2, "codebook"),
+    (dict(n_value_buckets=-1), -1, "n_value_buckets"),
+    (dict(n_value_buckets=16, n_levels=8, codebook=[8] * 8, max_beam=[4] * 8), -2, "value step"),
 ])
 def test_init_rejects_bad_descriptions_without_a_gpu(over, status, needle):
     L = binding.lib()
