@@ -91,6 +91,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="beam scale of configuration 5")
     ap.add_argument("--lazy", type=int, default=None, help="number of lazy layers K of the same model (default: the configuration's; 0 = plain autoregressive decoding)")
     ap.add_argument("--value", type=int, default=0, help="append an eCPM-token step with this many value buckets to the model and run it in every call (default: none)")
+    ap.add_argument("--beam", type=str, default=None, help="comma-separated beam widths per level instead of the configuration's (Dynamic Beam Width schedules)")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
@@ -109,6 +110,13 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     w = synth.workload(args.config, scale=args.scale, batch=args.batch, lazy=args.lazy, value=args.value)
+    if args.beam:
+        beam = [int(b) for b in args.beam.split(",")]
+        if len(beam) != w.T or min(beam) < 1:
+            print("bench.py: --beam needs %d positive widths" % w.T, file=sys.stderr)
+            sys.exit(2)
+        w.beam = beam
+        w.name += "-beam" + "/".join(map(str, beam))
     W = synth.make_weights(w)
     lens = synth.make_lengths(w)
     dev = torch.device("cuda:0")

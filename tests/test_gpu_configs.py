@@ -19,8 +19,10 @@ def weights_of(w):
     return _weights[w.cfg_id]
 
 
-def run_config(cfg, sample, batch=None, scale=1.0, lazy=None):
+def run_config(cfg, sample, batch=None, scale=1.0, lazy=None, beam=None):
     w = synth.workload(cfg, scale=scale, batch=batch, lazy=lazy)
+    if beam is not None:
+        w.beam = list(beam)
     W = weights_of(w)
     lens = synth.make_lengths(w)
     X = synth.make_context(w, lens)
@@ -65,3 +67,10 @@ def test_config3_other_lazy_depths(lazy):
     # section 3.2: the same model decoded with no lazy layer (plain autoregressive decoding, every layer per beam and
     # level) and with all but one layer lazy; bench.py --lazy times these against the configuration's own depth
     run_config(3, sample=[7], lazy=lazy)
+
+
+@pytest.mark.parametrize("beam", [[512, 512, 512], [512, 128, 512]])
+def test_config3_other_beam_width_schedules(beam):
+    # section 4.2.1 (Dynamic Beam Width): the fixed-width baseline and a schedule that narrows in the middle, which bench.py
+    # --beam times against the configuration's own progressively increasing 128/256/512
+    run_config(3, sample=[33], beam=beam)
