@@ -22,7 +22,7 @@ _LP = C.POINTER(C.c_int64)
 
 
 class _Desc(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("d", "H", "F", "L", "K", "T")] + [("V", _IP), ("eps", C.c_float)]
+    _fields_ = [(n, C.c_int32) for n in ("d", "H", "F", "L", "K", "T")] + [("V", _IP), ("eps", C.c_float), ("fp8", C.c_int32)]
 
 
 class _Layer(C.Structure):
@@ -67,6 +67,8 @@ def _lib(precision):
         lib.orc_prim_fuse.argtypes = [_DP, _DP, _DP, _DP, _DP, C.c_int]
         lib.orc_prim_topk.argtypes = [_DP, C.c_int, C.c_int, C.c_int, _LP, _DP, C.c_int]
         lib.orc_prim_layer_seq.argtypes = [C.c_void_p, C.c_void_p, C.c_int, _DP, C.c_int]
+        lib.orc_prim_e4m3.argtypes = [_DP, _DP, C.c_int]
+        lib.orc_prim_quant_rows.argtypes = [_DP, _DP, C.c_int, C.c_int]
         lib.orc_real_bytes.restype = C.c_int
         _libs[precision] = lib
     return _libs[precision]
@@ -94,7 +96,7 @@ MODE_CACHED, MODE_PLAIN, MODE_PLAIN_PRECUT = 0, 1, 2
 class Oracle:
     """One model (shapes + weights) loaded into the oracle."""
 
-    def __init__(self, d, H, F, L, K, T, V, weights, eps=1e-6, precision="f64"):
+    def __init__(self, d, H, F, L, K, T, V, weights, eps=1e-6, precision="f64", fp8=False):
         self.lib = _lib(precision)
         self.d, self.H, self.F, self.L, self.K, self.T, self.V, self.eps = d, H, F, L, K, T, list(V), eps
         keep = []  # keeps the float32 copies alive during orc_model_create
@@ -106,7 +108,7 @@ class Oracle:
 
         w = weights
         Varr = _i32(self.V)
-        desc = _Desc(d, H, F, L, K, T, _p(Varr, _IP), eps)
+        desc = _Desc(d, H, F, L, K, T, _p(Varr, _IP), eps, int(bool(fp8)))
         emb = (_FP * max(T - 1, 1))(*[fp(e) for e in w["emb"]]) if T > 1 else (_FP * 1)()
         cls = (_FP * T)(*[fp(c) for c in w["cls"]])
         cb = w.get("cls_bias")
@@ -255,3 +257,19 @@ def prim_topk(score, k, precut=False, precision="f64"):
     flat, ks = np.zeros(k, np.int64), np.zeros(k)
     _lib(precision).orc_prim_topk(_p(score, _DP), n, V, k, _p(flat, _LP), _p(ks, _DP), int(precut))
     return flat, ks
+
+
+def prim_e4m3(x, precision="f64"):
+    """Nearest value of the OCP E4M3 grid (saturating at 448), element by element."""
+    x = _f64(x)
+    y = np.zeros_like(x)
+    _lib(precision).orc_prim_e4m3(_p(y, _DP), _p(x, _DP), x.size)
+    return y
+
+
+def prim_quant_rows(x, precision="f64"):
+    """Rows as FP8 operands: scale amax(row)/448, E4M3 rounding, scaled back."""
+    x = _f64(x)
+    y = np.zeros_like(x)
+    _lib(precision).orc_prim_quant_rows(_p(y, _DP), _p(x, _DP), x.shape[0], x.shape[1])
+    return y

@@ -33,6 +33,19 @@
  *   Fuse weights shared by all levels; beam score = sum of log-probabilities;
  *   equal scores ordered by ascending flat candidate index i*V_t + v.
  *
+ * FP8 mode (orc_desc.fp8 != 0; appendix A.2, "Low-Precision Inference": the
+ * deployed model computes in FP8).  The paper names neither the format nor the
+ * scaling; the reading taken here: the matrix products that run once per beam
+ * row - the projections of the autoregressive layers (all but the context
+ * key/value projections, which run once per request), the W_f[:, :d] half of
+ * Fuse and the level classifiers - take both operands on the OCP E4M3 grid
+ * (4 exponent bits, bias 7, 3 mantissa bits, largest value 448, round to
+ * nearest even, saturating).  A weight matrix has one scale amax(W)/448 for
+ * the whole matrix (the three self-attention input projections count as one
+ * matrix); an activation row has its own scale amax(row)/448, taken when the
+ * product is formed.  Products and sums are exact in `real`; everything else
+ * (norms, attention, residuals, softmax, the lazy layers) is unchanged.
+ *
  * Parity with the authors' trained model: parity unpinned (no weights exist).
  */
 #include <math.h>
@@ -65,6 +78,7 @@ typedef struct {
     int32_t d, H, F, L, K, T;
     const int32_t *V; /* [T] codebook size per level */
     float eps;
+    int32_t fp8;      /* != 0: FP8 mode (see the header comment) */
 } orc_desc;
 
 typedef struct {
@@ -93,6 +107,7 @@ typedef struct orc_model {
     int d, H, F, L, K, T;
     int V[ORC_MAX_LEVELS];
     real eps;
+    int fp8;
     real *pos, *bos, *emb[ORC_MAX_LEVELS], *w_g, *w_f, *ln_out, *cls[ORC_MAX_LEVELS], *cls_bias[ORC_MAX_LEVELS];
     layer_r *layers;
 } orc_model;
@@ -145,6 +160,48 @@ static void rmsnorm(real *y, const real *x, const real *g, int rows, int d, real
 
 static real silu(real x) { return x / (1 + R_EXP(-x)); }
 
+/* nearest value of the OCP E4M3 grid: +-m * 2^(e-3), m in 8..15, e in -6..8 (normal) or m in 0..7, e = -6 (subnormal),
+ * largest value 448; ties go to the even m; magnitudes beyond the grid saturate at 448 */
+static real e4m3_round(real v) {
+    double a = fabs((double)v);
+    if (a == 0) return 0;
+    int e;
+    (void)frexp(a, &e); /* a = f * 2^e with f in [0.5, 1): binary exponent e - 1 */
+    int ex = e - 1 < -6 ? -6 : e - 1;
+    double ulp = ldexp(1.0, ex - 3);
+    double q = nearbyint(a / ulp) * ulp; /* default rounding mode: ties to even */
+    if (q > 448) q = 448;
+    return (real)copysign(q, (double)v);
+}
+
+/* per-row FP8 operand: y = s * e4m3(x / s) with s = amax(row) / 448 (a zero row stays zero) */
+static void quant_rows(real *y, const real *x, int rows, int n) {
+    for (int r = 0; r < rows; r++) {
+        const real *xr = x + (size_t)r * n;
+        real amax = 0;
+        for (int i = 0; i < n; i++) if (fabs((double)xr[i]) > amax) amax = (real)fabs((double)xr[i]);
+        real sc = amax > 0 ? amax / 448 : 1;
+        for (int i = 0; i < n; i++) y[(size_t)r * n + i] = e4m3_round(xr[i] / sc) * sc;
+    }
+}
+
+/* per-matrix FP8 operand, in place, one scale for all the listed pieces of one matrix */
+static void quant_matrix(real **pieces, const size_t *sizes, int count) {
+    real amax = 0;
+    for (int c = 0; c < count; c++)
+        for (size_t i = 0; i < sizes[c]; i++) if (fabs((double)pieces[c][i]) > amax) amax = (real)fabs((double)pieces[c][i]);
+    real sc = amax > 0 ? amax / 448 : 1;
+    for (int c = 0; c < count; c++)
+        for (size_t i = 0; i < sizes[c]; i++) pieces[c][i] = e4m3_round(pieces[c][i] / sc) * sc;
+}
+
+/* operand of a per-beam-row product: the rows themselves, or their FP8 image in FP8 mode (into `tmp`) */
+static const real *operand(int fp8, real *tmp, const real *x, int rows, int n) {
+    if (!fp8) return x;
+    quant_rows(tmp, x, rows, n);
+    return tmp;
+}
+
 /* out[v] = z[v] - log(sum_u exp(z[u])) */
 static void log_softmax(real *out, const real *z, int n) {
     real mx = z[0];
@@ -191,10 +248,11 @@ static void mha(real *out, const real *q, const real *k, const real *v, int nq, 
 }
 
 /* Fuse(m, s) = W_f [ m * (W_g s) ; s ]   (section 3.2, gated projection) */
-static void fuse(real *out, const real *m, const real *s, const real *w_g, const real *w_f, int d) {
+static void fuse(real *out, const real *m, const real *s, const real *w_g, const real *w_f, int d, int fp8) {
     real *cat = ralloc(2 * (size_t)d);
     linear(cat, s, w_g, 1, d, d);
     for (int i = 0; i < d; i++) cat[i] *= m[i];
+    if (fp8) quant_rows(cat, cat, 1, d); /* the gated half meets the FP8 half of W_f; W_g s and W_f[:, d:] s depend on the token alone */
     for (int i = 0; i < d; i++) cat[d + i] = s[i];
     linear(out, cat, w_f, 1, 2 * d, d);
     free(cat);
@@ -209,27 +267,30 @@ static void layer_seq(const orc_model *m, int l, real *x, int n, const real *Kc,
     size_t nd = (size_t)n * d;
     real *a = ralloc(nd), *q = ralloc(nd), *k = ralloc(nd), *v = ralloc(nd), *o = ralloc(nd);
     real *f = ralloc((size_t)n * F);
+    const int q8 = m->fp8 && l >= m->K; /* FP8 mode: the autoregressive layers' per-row products take FP8 operands */
+    real *tq = ralloc((size_t)n * (F > d ? F : d));
     /* cross-attention */
     rmsnorm(a, x, w->ln_x, n, d, m->eps);
-    linear(q, a, w->wq_x, n, d, d);
+    linear(q, operand(q8, tq, a, n, d), w->wq_x, n, d, d);
     mha(o, q, Kc, Vc, n, len, d, m->H, 0);
-    linear(a, o, w->wo_x, n, d, d);
+    linear(a, operand(q8, tq, o, n, d), w->wo_x, n, d, d);
     for (size_t i = 0; i < nd; i++) x[i] += a[i];
     /* causal self-attention over the decoder states */
     rmsnorm(a, x, w->ln_s, n, d, m->eps);
-    linear(q, a, w->wq_s, n, d, d);
-    linear(k, a, w->wk_s, n, d, d);
-    linear(v, a, w->wv_s, n, d, d);
+    const real *as = operand(q8, tq, a, n, d);
+    linear(q, as, w->wq_s, n, d, d);
+    linear(k, as, w->wk_s, n, d, d);
+    linear(v, as, w->wv_s, n, d, d);
     mha(o, q, k, v, n, n, d, m->H, 1);
-    linear(a, o, w->wo_s, n, d, d);
+    linear(a, operand(q8, tq, o, n, d), w->wo_s, n, d, d);
     for (size_t i = 0; i < nd; i++) x[i] += a[i];
     /* feed-forward */
     rmsnorm(a, x, w->ln_f, n, d, m->eps);
-    linear(f, a, w->w1, n, d, F);
+    linear(f, operand(q8, tq, a, n, d), w->w1, n, d, F);
     for (size_t i = 0; i < (size_t)n * F; i++) f[i] = silu(f[i]);
-    linear(a, f, w->w2, n, F, d);
+    linear(a, operand(q8, tq, f, n, F), w->w2, n, F, d);
     for (size_t i = 0; i < nd; i++) x[i] += a[i];
-    free(a); free(q); free(k); free(v); free(o); free(f);
+    free(a); free(q); free(k); free(v); free(o); free(f); free(tq);
 }
 
 /* classifier of level t (0-based): lp = log_softmax(W_t N_out(h) + bias_t) */
@@ -237,6 +298,7 @@ static void classify(const orc_model *m, int t, const real *h, real *lp) {
     int d = m->d, V = m->V[t];
     real *a = ralloc(d);
     rmsnorm(a, h, m->ln_out, 1, d, m->eps);
+    if (m->fp8) quant_rows(a, a, 1, d);
     linear(lp, a, m->cls[t], 1, d, V);
     if (m->cls_bias[t]) for (int v = 0; v < V; v++) lp[v] += m->cls_bias[t][v];
     log_softmax(lp, lp, V);
@@ -255,6 +317,7 @@ orc_model *orc_model_create(const orc_desc *ds, const orc_weights *w) {
     if (!ds || !w || ds->T < 1 || ds->T > ORC_MAX_LEVELS || ds->K < 0 || ds->K >= ds->L || ds->d % ds->H) return NULL;
     orc_model *m = (orc_model *)calloc(1, sizeof(orc_model));
     m->d = ds->d; m->H = ds->H; m->F = ds->F; m->L = ds->L; m->K = ds->K; m->T = ds->T; m->eps = (real)ds->eps;
+    m->fp8 = ds->fp8 != 0;
     size_t d = ds->d, F = ds->F;
     for (int t = 0; t < m->T; t++) m->V[t] = ds->V[t];
     m->pos = rcopy_f(w->pos, m->T * d);
@@ -276,6 +339,24 @@ orc_model *orc_model_create(const orc_desc *ds, const orc_weights *w) {
         r->ln_s = rcopy_f(s->ln_s, d); r->wq_s = rcopy_f(s->wq_s, d * d); r->wk_s = rcopy_f(s->wk_s, d * d);
         r->wv_s = rcopy_f(s->wv_s, d * d); r->wo_s = rcopy_f(s->wo_s, d * d);
         r->ln_f = rcopy_f(s->ln_f, d); r->w1 = rcopy_f(s->w1, F * d); r->w2 = rcopy_f(s->w2, d * F);
+    }
+    if (m->fp8) { /* the weights of the per-beam-row products move onto the FP8 grid once, here */
+        const size_t dd = d * d, dF = d * F;
+        for (int l = m->K; l < m->L; l++) {
+            layer_r *r = &m->layers[l];
+            real *qkv[3] = {r->wq_s, r->wk_s, r->wv_s};
+            const size_t qkv_n[3] = {dd, dd, dd};
+            quant_matrix(&r->wq_x, &dd, 1); quant_matrix(&r->wo_x, &dd, 1);
+            quant_matrix(qkv, qkv_n, 3); quant_matrix(&r->wo_s, &dd, 1);
+            quant_matrix(&r->w1, &dF, 1); quant_matrix(&r->w2, &dF, 1);
+        }
+        for (int t = 0; t < m->T; t++) { const size_t n = (size_t)m->V[t] * d; quant_matrix(&m->cls[t], &n, 1); }
+        /* W_f[:, :d]: the first d entries of each of its d rows */
+        real *half = ralloc(dd);
+        for (size_t o = 0; o < d; o++) memcpy(half + o * d, m->w_f + o * 2 * d, d * sizeof(real));
+        quant_matrix(&half, &dd, 1);
+        for (size_t o = 0; o < d; o++) memcpy(m->w_f + o * 2 * d, half + o * d, d * sizeof(real));
+        free(half);
     }
     return m;
 }
@@ -332,7 +413,7 @@ void orc_forward_seq(const orc_model *m, const orc_req *rq, int t, const int32_t
     for (int l = 0; l < m->K; l++) layer_seq(m, l, x, t, rq->Kc[l], rq->Vc[l], rq->len);
     /* late injection (eq. fuse) */
     real *h = ralloc((size_t)t * d);
-    for (int p = 0; p < t; p++) fuse(h + (size_t)p * d, x + (size_t)p * d, prev_embedding(m, p, tokens), m->w_g, m->w_f, d);
+    for (int p = 0; p < t; p++) fuse(h + (size_t)p * d, x + (size_t)p * d, prev_embedding(m, p, tokens), m->w_g, m->w_f, d, m->fp8);
     /* autoregressive head (eq. head) */
     for (int l = m->K; l < m->L; l++) layer_seq(m, l, h, t, rq->Kc[l], rq->Vc[l], rq->len);
     size_t off = 0;
@@ -354,7 +435,7 @@ void orc_forward_seq(const orc_model *m, const orc_req *rq, int t, const int32_t
 void orc_plain_ar_seq(const orc_model *m, const orc_req *rq, int t, const int32_t *tokens, double *lp_last) {
     int d = m->d;
     real *h = ralloc((size_t)t * d);
-    for (int p = 0; p < t; p++) fuse(h + (size_t)p * d, m->pos + (size_t)p * d, prev_embedding(m, p, tokens), m->w_g, m->w_f, d);
+    for (int p = 0; p < t; p++) fuse(h + (size_t)p * d, m->pos + (size_t)p * d, prev_embedding(m, p, tokens), m->w_g, m->w_f, d, m->fp8);
     for (int l = 0; l < m->L; l++) layer_seq(m, l, h, t, rq->Kc[l], rq->Vc[l], rq->len);
     real *lp = ralloc(m->V[t - 1]);
     classify(m, t - 1, h + (size_t)(t - 1) * d, lp);
@@ -464,24 +545,27 @@ static void layer_step(const orc_model *m, int l, real *x, int p, const real *Kc
     const layer_r *w = &m->layers[l];
     int d = m->d, F = m->F;
     real *a = ralloc(d), *q = ralloc(d), *o = ralloc(d), *f = ralloc(F);
+    const int q8 = m->fp8 && l >= m->K;
+    real *tq = ralloc(F > d ? F : d);
     rmsnorm(a, x, w->ln_x, 1, d, m->eps);
-    linear(q, a, w->wq_x, 1, d, d);
+    linear(q, operand(q8, tq, a, 1, d), w->wq_x, 1, d, d);
     mha(o, q, Kc, Vc, 1, len, d, m->H, 0);
-    linear(a, o, w->wo_x, 1, d, d);
+    linear(a, operand(q8, tq, o, 1, d), w->wo_x, 1, d, d);
     for (int i = 0; i < d; i++) x[i] += a[i];
     rmsnorm(a, x, w->ln_s, 1, d, m->eps);
-    linear(q, a, w->wq_s, 1, d, d);
-    linear(selfK + (size_t)p * d, a, w->wk_s, 1, d, d);
-    linear(selfV + (size_t)p * d, a, w->wv_s, 1, d, d);
+    const real *as = operand(q8, tq, a, 1, d);
+    linear(q, as, w->wq_s, 1, d, d);
+    linear(selfK + (size_t)p * d, as, w->wk_s, 1, d, d);
+    linear(selfV + (size_t)p * d, as, w->wv_s, 1, d, d);
     mha(o, q, selfK, selfV, 1, p + 1, d, m->H, 0);
-    linear(a, o, w->wo_s, 1, d, d);
+    linear(a, operand(q8, tq, o, 1, d), w->wo_s, 1, d, d);
     for (int i = 0; i < d; i++) x[i] += a[i];
     rmsnorm(a, x, w->ln_f, 1, d, m->eps);
-    linear(f, a, w->w1, 1, d, F);
+    linear(f, operand(q8, tq, a, 1, d), w->w1, 1, d, F);
     for (int i = 0; i < F; i++) f[i] = silu(f[i]);
-    linear(a, f, w->w2, 1, F, d);
+    linear(a, operand(q8, tq, f, 1, F), w->w2, 1, F, d);
     for (int i = 0; i < d; i++) x[i] += a[i];
-    free(a); free(q); free(o); free(f);
+    free(a); free(q); free(o); free(f); free(tq);
 }
 
 int orc_decode_cached(const orc_model *m, const orc_req *rq, const int32_t *beam, int32_t *out_sid, double *out_logprob,
@@ -503,7 +587,7 @@ int orc_decode_cached(const orc_model *m, const orc_req *rq, const int32_t *beam
 #pragma omp parallel for schedule(dynamic) if (!omp_in_parallel() && n >= 4)
         for (int i = 0; i < n; i++) {
             real *h = ralloc(d), *lp = ralloc(V);
-            fuse(h, trunk + (size_t)t * d, prev_embedding(m, t, paths + (size_t)i * T), m->w_g, m->w_f, d);
+            fuse(h, trunk + (size_t)t * d, prev_embedding(m, t, paths + (size_t)i * T), m->w_g, m->w_f, d, m->fp8);
             for (int a = 0; a < A; a++) {
                 int l = m->K + a;
                 layer_step(m, l, h, t, rq->Kc[l], rq->Vc[l], rq->len, sK + i * kvsz + (size_t)a * T * d, sV + i * kvsz + (size_t)a * T * d);
@@ -613,7 +697,7 @@ void orc_prim_mha(double *out, const double *q, const double *k, const double *v
 }
 void orc_prim_fuse(double *out, const double *mvec, const double *s, const double *w_g, const double *w_f, int d) {
     real *mr = from_d(mvec, d), *sr = from_d(s, d), *g = from_d(w_g, (size_t)d * d), *f = from_d(w_f, (size_t)2 * d * d), *o = ralloc(d);
-    fuse(o, mr, sr, g, f, d); to_d(out, o, d); free(mr); free(sr); free(g); free(f); free(o);
+    fuse(o, mr, sr, g, f, d, 0); to_d(out, o, d); free(mr); free(sr); free(g); free(f); free(o);
 }
 /* mode 0 global full sort, 1 pre-cut */
 void orc_prim_topk(const double *score, int n, int V, int k, int64_t *out_flat, double *out_score, int precut) {
@@ -625,5 +709,10 @@ void orc_prim_topk(const double *score, int n, int V, int k, int64_t *out_flat, 
 void orc_prim_layer_seq(const orc_model *m, const orc_req *rq, int l, double *x, int n) {
     real *xr = from_d(x, (size_t)n * m->d);
     layer_seq(m, l, xr, n, rq->Kc[l], rq->Vc[l], rq->len); to_d(x, xr, (size_t)n * m->d); free(xr);
+}
+void orc_prim_e4m3(double *y, const double *x, int n) { for (int i = 0; i < n; i++) y[i] = (double)e4m3_round((real)x[i]); }
+void orc_prim_quant_rows(double *y, const double *x, int rows, int n) {
+    real *xr = from_d(x, (size_t)rows * n), *yr = ralloc((size_t)rows * n);
+    quant_rows(yr, xr, rows, n); to_d(y, yr, (size_t)rows * n); free(xr); free(yr);
 }
 int orc_real_bytes(void) { return (int)sizeof(real); }
