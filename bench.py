@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA = 2.5e15   # dense bf16 MFMA, FLOP/s
+PEAK_FP8_MFMA = 5.0e15    # dense fp8 MFMA, FLOP/s
 PEAK_F32_VALU = 157.3e12  # fp32 vector FLOP/s
 PEAK_HBM = 8.0e12         # HBM3E, B/s
 
@@ -90,6 +91,7 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest-batch one)")
     ap.add_argument("--scale", type=float, default=1.0, help="beam scale of configuration 5")
     ap.add_argument("--lazy", type=int, default=None, help="number of lazy layers K of the same model (default: the configuration's; 0 = plain autoregressive decoding)")
+    ap.add_argument("--fp8", action="store_true", help="low-precision inference: FP8 (E4M3) operands for the per-beam-row products (default: bf16)")
     ap.add_argument("--value", type=int, default=0, help="append an eCPM-token step with this many value buckets to the model and run it in every call (default: none)")
     ap.add_argument("--beam", type=str, default=None, help="comma-separated beam widths per level instead of the configuration's (Dynamic Beam Width schedules)")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size")
@@ -109,7 +111,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    w = synth.workload(args.config, scale=args.scale, batch=args.batch, lazy=args.lazy, value=args.value)
+    w = synth.workload(args.config, scale=args.scale, batch=args.batch, lazy=args.lazy, value=args.value, fp8=args.fp8)
     if args.beam:
         beam = [int(b) for b in args.beam.split(",")]
         if len(beam) != w.T or min(beam) < 1:
@@ -171,7 +173,10 @@ def main():
         fl = rec["flops"]
         if name.startswith("cross_attn"):
             fl *= float(np.mean(lens)) / w.S  # the library counts the padded length; the method needs the valid keys only
-        if fl > 0 and (name.startswith("gemm_bf16") or name.startswith("cross_attn_flash")):
+        if fl > 0 and name.startswith("gemm_fp8"):
+            k.update(bound="mfma", achieved=fl / sec / 1e12, peak=PEAK_FP8_MFMA / 1e12, unit="TFLOP/s", frac=fl / sec / PEAK_FP8_MFMA,
+                     flops_per_launch=fl / rec["launches"])
+        elif fl > 0 and (name.startswith("gemm_bf16") or name.startswith("cross_attn_flash")):
             k.update(bound="mfma", achieved=fl / sec / 1e12, peak=PEAK_BF16_MFMA / 1e12, unit="TFLOP/s", frac=fl / sec / PEAK_BF16_MFMA,
                      flops_per_launch=fl / rec["launches"])
         elif fl > 0 and name.startswith("gemm"):
@@ -195,7 +200,7 @@ def main():
     out = {
         "metric": "requests_per_s", "value": req_s, "unit": "requests/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
+        "dtype": "fp8" if w.fp8 else w.dtype, "data": "synthetic",
         "config": {"workload": "config %d %s: B=%d S=%d d=%d L=%d K=%d H=%d F=%d T=%d V=%s beam=%s ctx_len=%s" % (
             w.cfg_id, w.name, w.B, w.S, w.d, w.L, w.K, w.H, w.F, w.T, w.V[0], "/".join(map(str, w.beam)),
             "all %d" % w.S if w.len_min is None else "U[%d,%d]" % (w.len_min, w.S)), "batch": w.B, "beam": list(w.beam)},
@@ -205,7 +210,7 @@ def main():
         "workspace_gib": ws_bytes / 2**30,
         "roofline": roofline, "kernels": kernels,
     }
-    if not args.no_cpu and w.Ve == 0:  # the oracle's batch decode ends at the last SID level
+    if not args.no_cpu and w.Ve == 0 and not w.fp8:  # (the baseline is the oracle as it stands, in its default mode)  # the oracle's batch decode ends at the last SID level
         budget = {1: 4, 2: 64, 3: 16, 4: 2, 5: 2}[w.cfg_id]
         out["cpu_baseline"] = cpu_baseline(w, W, lens, budget)
     print(json.dumps(out))

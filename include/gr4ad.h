@@ -61,6 +61,13 @@ typedef struct {
     float rms_eps;           /* epsilon inside every RMSNorm */
     int32_t n_value_buckets; /* V_e: size of the eCPM-token vocabulary of the value step (section 3.3), 0 = no value step;
                               * with a value step T <= GR4AD_MAX_LEVELS - 1 */
+    int32_t fp8_gemm;        /* != 0: low-precision inference (appendix A.2).  dtype must be GR4AD_BF16; weights are still
+                              * handed over in bf16.  The matrix products that run once per beam row - the projections of the
+                              * autoregressive layers except the context key/value projections, the W_f[:, :d] half of Fuse and
+                              * the classifiers - take both operands as OCP E4M3 bytes with float32 accumulation: init
+                              * quantises those weights with one scale amax/448 per matrix (the three self-attention input
+                              * projections count as one matrix), decode quantises every activation row with its own scale
+                              * amax(row)/448.  Everything else (lazy layers, attention, norms, softmax, scores) is unchanged. */
 } gr4ad_model_desc;
 
 /* One decoder layer (section 3.2: cross-attention over X, self-attention over
@@ -178,6 +185,22 @@ const char *gr4ad_last_error(const gr4ad_decoder *dec);
  * out_f32 != 0: C is float32, else C has the storage dtype. */
 int gr4ad_op_linear(gr4ad_dtype dtype, const void *A_dev, const void *W_dev, const float *bias_dev, void *C_dev, int32_t M,
                     int32_t N, int32_t K, int32_t out_f32, void *hip_stream);
+
+/*
+ * gr4ad_op_quantize_rows -- rows of bf16 values as FP8 operands (appendix A.2; the quantiser of fp8_gemm mode):
+ *   q[r, :] = nearest OCP E4M3 value (ties to even) of x[r, :] / scale[r],  scale[r] = max|x[r, :]| / 448 (1 for a zero row).
+ * x [rows, n] bf16, q [rows, n] bytes, scale [rows] float32, all device; n a multiple of 8, x 16-byte and q 8-byte aligned.
+ */
+int gr4ad_op_quantize_rows(const void *x_dev, void *q_dev, float *scale_dev, int32_t rows, int32_t n, void *hip_stream);
+
+/*
+ * gr4ad_op_linear_fp8 -- C[M,N] = (a_scale[m] * w_scale) * Aq[M,K] Wq[N,K]^T (+ bias[n]) with E4M3 operands and float32
+ * accumulation (the product fp8_gemm mode runs).  Aq, Wq device bytes, row-major, K contiguous; a_scale [M] and bias [N] (or
+ * NULL) device float32; C device, float32 if out_f32 else bf16.  Shapes with M >= 64, N >= 256, K a multiple of 128 and
+ * >= 384 and 16-byte aligned rows run on the matrix cores, the rest on a plain kernel.
+ */
+int gr4ad_op_linear_fp8(const void *Aq_dev, const float *a_scale_dev, const void *Wq_dev, float w_scale, const float *bias_dev, void *C_dev,
+                        int32_t M, int32_t N, int32_t K, int32_t out_f32, void *hip_stream);
 
 /* Log-softmax + cumulative score + top-k (appendix A.2, TopK Pre-Cut):
  * logits [B, n, V] float32, cum [B, n] float32 (NULL = zeros); keeps for each

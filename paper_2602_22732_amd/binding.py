@@ -18,6 +18,7 @@ LAYER_FIELDS = ["ln_x", "wq_x", "wk_x", "wv_x", "wo_x", "ln_s", "wq_s", "wk_s", 
 EXPORTS = ["gr4ad_decode_init", "gr4ad_decode_workspace_bytes", "gr4ad_decode_batch", "gr4ad_decode_set_trace",
            "gr4ad_decode_set_value_output",
            "gr4ad_decode_free", "gr4ad_strerror", "gr4ad_last_error", "gr4ad_op_linear", "gr4ad_op_select_workspace_bytes",
+           "gr4ad_op_quantize_rows", "gr4ad_op_linear_fp8",
            "gr4ad_op_select", "gr4ad_op_cross_attention_workspace_bytes", "gr4ad_op_cross_attention", "gr4ad_op_gather_rows",
            "gr4ad_profile_enable",
            "gr4ad_profile_kernel_count", "gr4ad_profile_kernel_name", "gr4ad_profile_read"]
@@ -30,7 +31,7 @@ class ModelDesc(C.Structure):
     _fields_ = [("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ffn", C.c_int32), ("n_layers", C.c_int32),
                 ("n_lazy", C.c_int32), ("n_levels", C.c_int32), ("codebook", _IP), ("max_beam", _IP),
                 ("max_batch", C.c_int32), ("max_ctx", C.c_int32), ("dtype", C.c_int), ("rms_eps", C.c_float),
-                ("n_value_buckets", C.c_int32)]
+                ("n_value_buckets", C.c_int32), ("fp8_gemm", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -78,6 +79,10 @@ def lib():
         L.gr4ad_last_error.argtypes = [_VP]
         L.gr4ad_op_linear.restype = C.c_int
         L.gr4ad_op_linear.argtypes = [C.c_int, _VP, _VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP]
+        L.gr4ad_op_quantize_rows.restype = C.c_int
+        L.gr4ad_op_quantize_rows.argtypes = [_VP, _VP, _VP, C.c_int32, C.c_int32, _VP]
+        L.gr4ad_op_linear_fp8.restype = C.c_int
+        L.gr4ad_op_linear_fp8.argtypes = [_VP, _VP, _VP, C.c_float, _VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP]
         L.gr4ad_op_select_workspace_bytes.restype = C.c_size_t
         L.gr4ad_op_select_workspace_bytes.argtypes = [C.c_int32] * 4
         L.gr4ad_op_select.restype = C.c_int
@@ -163,13 +168,13 @@ def weights_to_device(weights, dtype, device="cuda"):
 class Decoder:
     """gr4ad_decode_init / gr4ad_decode_batch / gr4ad_decode_free."""
 
-    def __init__(self, d, H, F, L, K, T, V, dev_weights, dtype, max_beam, max_batch, max_ctx, eps=1e-6, Ve=0):
+    def __init__(self, d, H, F, L, K, T, V, dev_weights, dtype, max_beam, max_batch, max_ctx, eps=1e-6, Ve=0, fp8=False):
         self.L_ = lib()
         self.handle = None
         self.T, self.V, self.d, self.dtype, self.Ve = T, list(V), d, dtype_code(dtype), int(Ve)
         V_arr, V_ptr = _i32arr(self.V)
         mb_arr, mb_ptr = _i32arr(max_beam)
-        desc = ModelDesc(d, H, F, L, K, T, V_ptr, mb_ptr, max_batch, max_ctx, self.dtype, eps, self.Ve)
+        desc = ModelDesc(d, H, F, L, K, T, V_ptr, mb_ptr, max_batch, max_ctx, self.dtype, eps, self.Ve, int(bool(fp8)))
         w = dev_weights
         ptr = lambda t: C.c_void_p(t.data_ptr())
         emb = (_VP * max(T - 1, 1))(*[t.data_ptr() for t in w["emb"]])
@@ -250,7 +255,7 @@ def decoder_for(workload, weights, max_beam=None, device="cuda"):
     """Decoder for a synth.Workload and its numpy weight dict."""
     w = workload
     dev_w = weights_to_device(weights, w.dtype, device)
-    dec = Decoder(w.d, w.H, w.F, w.L, w.K, w.T, w.V, dev_w, w.dtype, max_beam or list(w.beam), w.B, w.S, eps=w.eps, Ve=w.Ve)
+    dec = Decoder(w.d, w.H, w.F, w.L, w.K, w.T, w.V, dev_w, w.dtype, max_beam or list(w.beam), w.B, w.S, eps=w.eps, Ve=w.Ve, fp8=w.fp8)
     dec._keep = dev_w  # init copies the weights; kept only so callers may inspect them
     return dec
 
@@ -263,6 +268,24 @@ def op_linear(A, W, bias=None, out_f32=False, stream=None):
     Cout = torch.empty(M, N, dtype=torch.float32 if out_f32 else A.dtype, device=A.device)
     _check(lib().gr4ad_op_linear(dt, A.data_ptr(), W.data_ptr(), None if bias is None else bias.data_ptr(), Cout.data_ptr(), M, N, K,
                                  int(out_f32), _stream_ptr(stream)))
+    return Cout
+
+
+def op_quantize_rows(x, stream=None):
+    """x [rows, n] bf16 -> (q [rows, n] uint8 holding E4M3 bytes, scale [rows] float32)."""
+    rows, n = x.shape
+    q = torch.empty(rows, n, dtype=torch.uint8, device=x.device)
+    scale = torch.empty(rows, dtype=torch.float32, device=x.device)
+    _check(lib().gr4ad_op_quantize_rows(x.data_ptr(), q.data_ptr(), scale.data_ptr(), rows, n, _stream_ptr(stream)))
+    return q, scale
+
+
+def op_linear_fp8(Aq, a_scale, Wq, w_scale, bias=None, out_f32=False, stream=None):
+    M, K = Aq.shape
+    N = Wq.shape[0]
+    Cout = torch.empty(M, N, dtype=torch.float32 if out_f32 else torch.bfloat16, device=Aq.device)
+    _check(lib().gr4ad_op_linear_fp8(Aq.data_ptr(), a_scale.data_ptr(), Wq.data_ptr(), float(w_scale), None if bias is None else bias.data_ptr(),
+                                     Cout.data_ptr(), M, N, K, int(out_f32), _stream_ptr(stream)))
     return Cout
 
 

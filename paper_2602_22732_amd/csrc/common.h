@@ -56,6 +56,8 @@ struct GemmEpilogue {
     int64_t norm_ld;
     float *norm_ss;
     const float *row_inv;
+    const float *a_scale;      // launch_gemm_f8 only (set by it): per-row scale of the FP8 A operand
+    float w_scale;             // launch_gemm_f8 only (set by it): scale of the FP8 W operand
     const int32_t *batch_len;  // launch_gemm_batched only: valid length per batch (NULL = none)
     int len_bounds;            // 1: the length bounds the columns of C that are needed, 2: it bounds K
 };
@@ -65,6 +67,12 @@ int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, in
 // true if launch_gemm would run this product on the persistent kernel (the one that supports the folded RMSNorm)
 bool gemm_on_persistent_kernel(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K,
                                const GemmEpilogue &epi);
+
+// FP8 (OCP E4M3) operands: C = (a_scale[row] * w_scale) * Aq Wq^T followed by the same epilogues; lda, ldw in elements (bytes);
+// C is bf16 unless epi.out_f32.  Large shapes run on the persistent kernel's FP8 form, the rest on the plain kernel.
+int launch_gemm_f8(const void *A, int64_t lda, const float *a_scale, const void *W, int64_t ldw, float w_scale, int64_t M, int N, int K,
+                   const GemmEpilogue &epi, hipStream_t st);
+bool gemm_f8_on_persistent_kernel(const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K, const GemmEpilogue &epi);
 
 // batched small products (bf16 operands, 128x128 MFMA tiles): see gemm.hip
 int launch_gemm_batched(const void *A, int64_t lda, int64_t batch_a, const void *W, int64_t ldw, int64_t batch_w, void *C, int64_t ldc,
@@ -92,6 +100,13 @@ int launch_gather_rows(gr4ad_dtype dtype, const void *src, const int32_t *parent
 
 // out[r, :] = logits[r, :] - log(sum(exp(logits[r, :])))   (float32 rows of V values)
 int launch_log_softmax_rows(const float *logits, float *out, int64_t rows, int V, hipStream_t st);
+
+// FP8 (OCP E4M3) operands.  Rows: yq[r, :] = e4m3(x[r, :] / scale[r]), scale[r] = amax(row) / 448 (1 for a zero row);
+// launch_rmsnorm_quant takes the float32 residual stream and quantises g * x / rms(x), launch_quantize_rows a bf16 row as it is.
+int launch_rmsnorm_quant(const void *x, const void *g, void *yq, float *scale, int64_t rows, int d, float eps, hipStream_t st);
+int launch_quantize_rows(const void *x, void *yq, float *scale, int64_t rows, int n, hipStream_t st);
+// init time, synchronises the stream: one scale for the whole bf16 matrix of `count` elements, returned on the host
+int launch_quantize_matrix(const void *w, void *wq, int64_t count, unsigned *amax_dev, float *scale_host, hipStream_t st);
 
 // out[h][j][c] = w[h*dh + c][j] for a bf16 [d, d] weight (init-time)
 int launch_head_transpose(const void *w, void *out, int d, int H, hipStream_t st);
@@ -129,7 +144,7 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
 
 // ---- optional per-kernel event timing ----------------------------------------
 enum KernelClass { KC_GEMM_256 = 0, KC_GEMM_128, KC_GEMM_SIMPLE, KC_XATTN_FLASH, KC_XATTN_SIMPLE, KC_SELF_STEP, KC_TRUNK_SELF,
-                   KC_RMSNORM, KC_FUSE_GATE, KC_SELECT_ROWS, KC_SELECT_REQUEST, KC_GATHER, KC_BROADCAST, KC_V_TRANSPOSE, KC_GEMM_RING, KC_SOFTMAX, KC_COUNT };
+                   KC_RMSNORM, KC_FUSE_GATE, KC_SELECT_ROWS, KC_SELECT_REQUEST, KC_GATHER, KC_BROADCAST, KC_V_TRANSPOSE, KC_GEMM_RING, KC_SOFTMAX, KC_GEMM_RING_F8, KC_QUANTIZE, KC_COUNT };
 // Declared around a kernel launch: records an event before and (on scope exit) after it when timing is on.
 struct ProfScope {
     ProfScope(int cls, hipStream_t st, double flops = 0.0, double bytes = 0.0);  // algorithmic work of the launch

@@ -18,6 +18,9 @@ struct LayerPacked {
     void *ln_s, *wqkv_s, *wo_s;         // wqkv_s [3d,d]
     void *ln_f, *w1, *w2;
     void *wkT_x;  // lazy layers in absorbed form only: [H][d][dh], the key projection transposed per head
+    // FP8 mode, autoregressive layers only: E4M3 copies of the per-row projections, one scale per matrix
+    void *wq_x8, *wo_x8, *wqkv_s8, *wo_s8, *w1_8, *w2_8;
+    float s_wq_x, s_wo_x, s_wqkv_s, s_wo_s, s_w1, s_w2;
 };
 
 thread_local char g_init_error[512] = "";
@@ -44,6 +47,9 @@ struct gr4ad_decoder {
     float *tr_score[GR4AD_MAX_LEVELS];
     bool trace;
     bool absorbed;  // lazy layers' cross-attention runs in absorbed form (see decode_batch)
+    bool fp8;       // FP8 mode: the per-beam-row products take E4M3 operands (see decode_batch)
+    void *wf1_8, *cls8[GR4AD_MAX_LEVELS];
+    float s_wf1, s_cls[GR4AD_MAX_LEVELS];
     char err[512];
 };
 
@@ -62,6 +68,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Everything decode_batch carves out of the caller's workspace.
 struct Plan {
+    size_t aq, ascale;  // FP8 mode: the quantised operand of the next product [rows_max, max(d, F)] bytes and its row scales
     size_t kv_ar, kv_lazy, vt_ar, vt_lazy, vt_bytes, xt, qp, zb, sc, pb, ss, trunk, h, xn, q, o, qkv, f, logits, selws, qkv_lvl[GR4AD_MAX_LEVELS], cum[2], par, tok[2], sid[2], anc[2], total;
     int64_t rows_max, nmax, bmax;
     size_t qkv_lvl_layer_bytes[GR4AD_MAX_LEVELS];  // one layer's [B*n_t, 3d] buffer of level t
@@ -123,6 +130,8 @@ Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *be
     p.qkv = take((size_t)B * Tp * 3 * d * e);  // lazy layers; the autoregressive layers keep one buffer per (level, layer), below
     p.f = take((size_t)p.rows_max * dec->F * e);
     p.logits = take((size_t)B * logit_max * sizeof(float));
+    p.aq = take(dec->fp8 ? (size_t)p.rows_max * (dec->F > d ? dec->F : d) : 0);
+    p.ascale = take(dec->fp8 ? (size_t)p.rows_max * sizeof(float) : 0);
     p.selws = take(selmax);
     // q/k/v of every level stay resident: they are the self-attention cache of the later levels, read through the
     // beams' ancestor table.  No level follows the last one, so its layers share one buffer.
@@ -204,6 +213,7 @@ int validate_desc(const gr4ad_model_desc *ds) {
     if (!(ds->rms_eps >= 0.0f)) return fail(nullptr, GR4AD_EINVAL, "rms_eps must be >= 0");
     if (ds->n_value_buckets < 0 || ds->n_value_buckets > GR4AD_MAX_CODEBOOK)
         return fail(nullptr, GR4AD_EINVAL, "n_value_buckets %d outside [0,%d]", ds->n_value_buckets, GR4AD_MAX_CODEBOOK);
+    if (ds->fp8_gemm && ds->dtype != GR4AD_BF16) return fail(nullptr, GR4AD_EUNSUPPORTED, "fp8_gemm needs the bf16 storage dtype");
     if (ds->n_value_buckets > 0 && ds->n_levels + 1 > GR4AD_MAX_LEVELS)
         return fail(nullptr, GR4AD_EUNSUPPORTED, "a value step needs n_levels <= %d", GR4AD_MAX_LEVELS - 1);
     for (int t = 0; t < ds->n_levels; t++) {
@@ -296,6 +306,28 @@ int init_impl(gr4ad_decoder *dec, const gr4ad_model_desc *ds, const gr4ad_weight
         OP_TRY(dec, launch_gemm(dec->dtype, emb, d, wg, d, rows, (int)d, (int)d, f32_epilogue(dec->G[t], d), 0), "Fuse gate table");
         OP_TRY(dec, launch_gemm(dec->dtype, emb, d, wf2, d, rows, (int)d, (int)d, f32_epilogue(dec->P[t], d), 0), "Fuse token table");
     }
+    if (dec->fp8) {
+        unsigned *amax = nullptr;
+        if ((s = dev_alloc(dec, (void **)&amax, 256))) return s;
+        auto quant = [&](const void *wsrc, size_t count, void **out, float *scale) -> int {
+            int r = dev_alloc(dec, out, count);
+            if (r) return r;
+            r = launch_quantize_matrix(wsrc, *out, (int64_t)count, amax, scale, 0);
+            return r ? fail(dec, r, "FP8 weight quantisation failed: %s", gr4ad_strerror(r)) : GR4AD_OK;
+        };
+        for (int l = dec->K; l < dec->L; l++) {
+            LayerPacked &p = dec->layers[l];
+            if ((s = quant(p.wq_x, d * d, &p.wq_x8, &p.s_wq_x))) return s;
+            if ((s = quant(p.wo_x, d * d, &p.wo_x8, &p.s_wo_x))) return s;
+            if ((s = quant(p.wqkv_s, 3 * d * d, &p.wqkv_s8, &p.s_wqkv_s))) return s;
+            if ((s = quant(p.wo_s, d * d, &p.wo_s8, &p.s_wo_s))) return s;
+            if ((s = quant(p.w1, F * d, &p.w1_8, &p.s_w1))) return s;
+            if ((s = quant(p.w2, d * F, &p.w2_8, &p.s_w2))) return s;
+        }
+        if ((s = quant(dec->wf1, d * d, &dec->wf1_8, &dec->s_wf1))) return s;
+        for (int t = 0; t < dec->Tp; t++)
+            if ((s = quant(dec->cls[t], (size_t)dec->V[t] * d, &dec->cls8[t], &dec->s_cls[t]))) return s;
+    }
     HIP_TRY(dec, hipDeviceSynchronize());
     return GR4AD_OK;
 }
@@ -330,6 +362,7 @@ int gr4ad_decode_init(const gr4ad_model_desc *ds, const gr4ad_weights *w, gr4ad_
     dec->T = ds->n_levels; dec->A = dec->L - dec->K; dec->max_batch = ds->max_batch; dec->max_ctx = ds->max_ctx;
     dec->dtype = ds->dtype; dec->esz = ds->dtype == GR4AD_BF16 ? 2 : 4; dec->eps = ds->rms_eps;
     dec->trace = false; dec->err[0] = 0;
+    dec->fp8 = ds->fp8_gemm != 0;
     dec->Ve = ds->n_value_buckets; dec->Tp = dec->T + (dec->Ve > 0 ? 1 : 0); dec->value_out = nullptr;
     {
         // The lazy layers attend with only T queries per request, so projecting every context row to keys and values
@@ -439,7 +472,22 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         if (fold && next_gain) { g.norm_gain = next_gain; g.norm_out = xn; g.norm_ld = d; g.norm_ss = ss; emitted = next_gain; }
         return g;
     };
+    // FP8 mode (autoregressive levels only; f8 is set there): a per-row projection reads its operand from aq, E4M3 bytes with
+    // one scale per row.  The norm in front of a projection writes it directly; a bf16 operand (attention output, FFN
+    // hidden rows, gated embedding) is quantised by its own pass over the rows.
+    bool f8 = false;
+    uint8_t *aq = (uint8_t *)(ws + p.aq);
+    float *ascale = (float *)(ws + p.ascale);
+    auto quant_act = [&](const void *act, int64_t rows, int width) { return launch_quantize_rows(act, aq, ascale, rows, width, st); };
+    auto gemm8 = [&](int64_t M, const void *W8, float wscale, int N, int Kdim, const GemmEpilogue &epi) {
+        return launch_gemm_f8(aq, Kdim, ascale, W8, Kdim, wscale, M, N, Kdim, epi, st);
+    };
     auto norm = [&](void *x, const void *gain, int64_t rows) -> int {
+        if (f8) {
+            emitted = nullptr;
+            scaled = false;
+            return launch_rmsnorm_quant(x, gain, aq, ascale, rows, d, dec->eps, st);
+        }
         if (emitted && emitted == gain) {
             emitted = nullptr;
             scaled = true;
@@ -458,13 +506,24 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     auto cross_block = [&](const LayerPacked &lw, void *x, int64_t rows, int n, const void *kvbuf, const void *vtbuf) -> int {
         int s;
         if ((s = norm(x, lw.ln_x, rows))) return s;
-        if ((s = gemm(xn, rows, lw.wq_x, d, d, reads_norm(plain_epilogue(q, d))))) return s;
+        if (f8) s = gemm8(rows, lw.wq_x8, lw.s_wq_x, d, d, plain_epilogue(q, d));
+        else s = gemm(xn, rows, lw.wq_x, d, d, reads_norm(plain_epilogue(q, d)));
+        if (s) return s;
         if ((s = launch_cross_attention(dt, q, d, kvbuf, vtbuf, ctx_len, o, d, B, n, S, d, H, st))) return s;
+        if (f8) {
+            if ((s = quant_act(o, rows, d))) return s;
+            return gemm8(rows, lw.wo_x8, lw.s_wo_x, d, d, resid_epi(x, d));
+        }
         return gemm(o, rows, lw.wo_x, d, d, emit_norm(resid_epi(x, d), lw.ln_s));
     };
     auto ffn_block = [&](const LayerPacked &lw, void *x, int64_t rows, const void *next_gain) -> int {
         int s;
         if ((s = norm(x, lw.ln_f, rows))) return s;
+        if (f8) {
+            if ((s = gemm8(rows, lw.w1_8, lw.s_w1, F, d, silu_epi(f, F)))) return s;
+            if ((s = quant_act(f, rows, F))) return s;
+            return gemm8(rows, lw.w2_8, lw.s_w2, d, F, resid_epi(x, d));
+        }
         if ((s = gemm(xn, rows, lw.w1, F, d, reads_norm(silu_epi(f, F))))) return s;
         return gemm(f, rows, lw.w2, d, F, emit_norm(resid_epi(x, d), next_gain));
     };
@@ -541,7 +600,8 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         const int64_t rows = (int64_t)B * n;
         const int bt = t < T ? beam[t] : n;  // the value step keeps every beam
         const int32_t *tok_prev = t == 0 ? nullptr : (const int32_t *)(ws + p.tok[cur]);
-        fold = fold_ok(rows, dec->V[t]);
+        f8 = dec->fp8;
+        fold = !f8 && fold_ok(rows, dec->V[t]);
         scaled = false;
         emitted = nullptr;
         {
@@ -552,7 +612,12 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
             g.out_f32 = 1;
             g.table = (const float *)dec->P[t];
             g.tok = tok_prev;
-            OP_TRY(dec, gemm(gated, rows, dec->wf1, d, d, emit_norm(g, dec->layers[K].ln_x)), "Fuse projection");
+            if (f8) {
+                OP_TRY(dec, quant_act(gated, rows, d), "Fuse operand quantisation");
+                OP_TRY(dec, gemm8(rows, dec->wf1_8, dec->s_wf1, d, d, g), "Fuse projection");
+            } else {
+                OP_TRY(dec, gemm(gated, rows, dec->wf1, d, d, emit_norm(g, dec->layers[K].ln_x)), "Fuse projection");
+            }
         }
         for (int a = 0; a < A; a++) {
             const LayerPacked &lw = dec->layers[K + a];
@@ -563,10 +628,16 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
                 prev.p[u] = u < t ? qkv_lvl(u, a) : nullptr;
                 prev.rows[u] = u < t ? (int64_t)B * (u == 0 ? 1 : beam[u - 1]) : 0;
             }
-            OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, reads_norm(plain_epilogue(qkv_lvl(t, a), 3 * d))), "self-attention qkv");
+            if (f8) OP_TRY(dec, gemm8(rows, lw.wqkv_s8, lw.s_wqkv_s, 3 * d, d, plain_epilogue(qkv_lvl(t, a), 3 * d)), "self-attention qkv");
+            else OP_TRY(dec, gemm(xn, rows, lw.wqkv_s, 3 * d, d, reads_norm(plain_epilogue(qkv_lvl(t, a), 3 * d))), "self-attention qkv");
             OP_TRY(dec, launch_self_attention_step(dt, qkv_lvl(t, a), prev, (const int32_t *)(ws + p.anc[cur]), o, rows, t, T, d, H, st),
                    "self-attention");
-            OP_TRY(dec, gemm(o, rows, lw.wo_s, d, d, emit_norm(resid_epi(h, d), lw.ln_f)), "self-attention output");
+            if (f8) {
+                OP_TRY(dec, quant_act(o, rows, d), "self-attention output quantisation");
+                OP_TRY(dec, gemm8(rows, lw.wo_s8, lw.s_wo_s, d, d, resid_epi(h, d)), "self-attention output");
+            } else {
+                OP_TRY(dec, gemm(o, rows, lw.wo_s, d, d, emit_norm(resid_epi(h, d), lw.ln_f)), "self-attention output");
+            }
             OP_TRY(dec, ffn_block(lw, h, rows, a + 1 < A ? dec->layers[K + a + 1].ln_x : dec->ln_out), "FFN");
         }
         OP_TRY(dec, norm(h, dec->ln_out, rows), "final norm");
@@ -574,7 +645,8 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
             GemmEpilogue g = plain_epilogue(logits, dec->V[t]);
             g.out_f32 = 1;
             g.bias = dec->cls_bias[t];
-            OP_TRY(dec, gemm(xn, rows, dec->cls[t], dec->V[t], d, reads_norm(g)), "classifier");
+            if (f8) OP_TRY(dec, gemm8(rows, dec->cls8[t], dec->s_cls[t], dec->V[t], d, g), "classifier");
+            else OP_TRY(dec, gemm(xn, rows, dec->cls[t], dec->V[t], d, reads_norm(g)), "classifier");
         }
         if (t == T) {  // value step: log p(v | y, X) for every surviving beam, in the order of out_sid
             OP_TRY(dec, launch_log_softmax_rows(logits, dec->value_out, rows, dec->Ve, st), "value log-softmax");
@@ -610,6 +682,20 @@ int gr4ad_op_linear(gr4ad_dtype dtype, const void *A, const void *W, const float
     e.bias = bias;
     e.out_f32 = out_f32 ? 1 : 0;
     return launch_gemm(dtype, A, K, W, K, M, N, K, e, (hipStream_t)hip_stream);
+}
+
+int gr4ad_op_quantize_rows(const void *x, void *q, float *scale, int32_t rows, int32_t n, void *hip_stream) {
+    if (!x || !q || !scale || rows < 1 || n < 8 || n % 8) return GR4AD_EINVAL;
+    return launch_quantize_rows(x, q, scale, rows, n, (hipStream_t)hip_stream);
+}
+
+int gr4ad_op_linear_fp8(const void *Aq, const float *a_scale, const void *Wq, float w_scale, const float *bias, void *C, int32_t M, int32_t N,
+                        int32_t K, int32_t out_f32, void *hip_stream) {
+    if (!Aq || !a_scale || !Wq || !C || M < 1 || N < 1 || K < 1 || !(w_scale > 0.0f)) return GR4AD_EINVAL;
+    GemmEpilogue e = plain_epilogue(C, N);
+    e.bias = bias;
+    e.out_f32 = out_f32 ? 1 : 0;
+    return launch_gemm_f8(Aq, K, a_scale, Wq, K, w_scale, M, N, K, e, (hipStream_t)hip_stream);
 }
 
 size_t gr4ad_op_select_workspace_bytes(int32_t B, int32_t n, int32_t V, int32_t k) {

@@ -1,6 +1,8 @@
 // Row-wise HBM-bound kernels: RMSNorm, the gate half of Fuse, trunk input
 // broadcast, and the beam reorder (row gather).  All move 16-byte vectors with
 // consecutive lanes on consecutive addresses.
+#include <string.h>
+
 #include "common.h"
 
 template <typename T> struct Vec16;  // 16 bytes of T
@@ -258,5 +260,136 @@ int launch_log_softmax_rows(const float *logits, float *out, int64_t rows, int V
     ProfScope ps(KC_SOFTMAX, st, 0.0, (double)rows * V * 2 * sizeof(float));
     hipLaunchKernelGGL(log_softmax_rows_kernel, dim3((unsigned)grid), dim3(256), 0, st, logits, out, rows, V);
     GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// FP8 operands (low-precision inference, appendix A.2): rows become OCP E4M3 bytes with one scale per row,
+// scale = amax(row) / 448, q = round_to_nearest_even(x / scale); a weight matrix gets one scale for the whole matrix.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint2 pack8_e4m3(const float (&v)[8], float qinv) {
+    int w0 = 0, w1 = 0;
+    w0 = __builtin_amdgcn_cvt_pk_fp8_f32(v[0] * qinv, v[1] * qinv, w0, false);
+    w0 = __builtin_amdgcn_cvt_pk_fp8_f32(v[2] * qinv, v[3] * qinv, w0, true);
+    w1 = __builtin_amdgcn_cvt_pk_fp8_f32(v[4] * qinv, v[5] * qinv, w1, false);
+    w1 = __builtin_amdgcn_cvt_pk_fp8_f32(v[6] * qinv, v[7] * qinv, w1, true);
+    return make_uint2((unsigned)w0, (unsigned)w1);
+}
+
+// One wavefront per row, the row stays in registers.  NORM: x is the float32 residual stream and the row is
+// g * x / rms(x) (the RMSNorm in front of a projection); otherwise x is a bf16 activation row taken as it is.
+template <bool NORM, int MAXV>  // MAXV: 8-element vectors per lane
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const void *__restrict__ xin, const bf16 *__restrict__ g, uint8_t *__restrict__ yq,
+                                                            float *__restrict__ scale, int64_t rows, int n, float eps) {
+    const int lane = threadIdx.x % 64;
+    const int64_t row = (int64_t)blockIdx.x * 4 + threadIdx.x / 64;
+    if (row >= rows) return;
+    const int nvec = n / 8;
+    float v[MAXV][8];
+    float ss = 0.0f, amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < MAXV; i++) {
+        const int c = lane + i * 64;
+        if (c < nvec) {
+            if (NORM) {
+                load16<float>((const float *)xin + row * n + (int64_t)c * 8, &v[i][0]);
+                load16<float>((const float *)xin + row * n + (int64_t)c * 8 + 4, &v[i][4]);
+#pragma unroll
+                for (int e = 0; e < 8; e++) ss += v[i][e] * v[i][e];
+            } else {
+                load16<bf16>((const bf16 *)xin + row * n + (int64_t)c * 8, v[i]);
+#pragma unroll
+                for (int e = 0; e < 8; e++) amax = fmaxf(amax, fabsf(v[i][e]));
+            }
+        }
+    }
+    if (NORM) {
+        ss = wave_sum(ss);
+        const float inv = 1.0f / sqrtf(ss / (float)n + eps);
+#pragma unroll
+        for (int i = 0; i < MAXV; i++) {
+            const int c = lane + i * 64;
+            if (c < nvec) {
+                float gg[8];
+                load16<bf16>(g + (int64_t)c * 8, gg);
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    v[i][e] = gg[e] * v[i][e] * inv;
+                    amax = fmaxf(amax, fabsf(v[i][e]));
+                }
+            }
+        }
+    }
+    amax = wave_max(amax);
+    const float qinv = amax > 0.0f ? 448.0f / amax : 1.0f;
+#pragma unroll
+    for (int i = 0; i < MAXV; i++) {
+        const int c = lane + i * 64;
+        if (c < nvec) *(uint2 *)(yq + row * n + (int64_t)c * 8) = pack8_e4m3(v[i], qinv);
+    }
+    if (lane == 0) scale[row] = amax > 0.0f ? amax / 448.0f : 1.0f;
+}
+
+template <bool NORM>
+static int launch_quantize_rows_any(const void *x, const void *g, void *yq, float *scale, int64_t rows, int n, float eps, hipStream_t st) {
+    if (!x || !yq || !scale || rows < 1 || n < 8 || n % 8 || (NORM && !g)) return GR4AD_EINVAL;
+    if (((uintptr_t)x % 16) || ((uintptr_t)yq % 8)) return GR4AD_EUNSUPPORTED;
+    const int64_t grid = ceil_div64(rows, 4);
+    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    const int nvec = n / 8;
+    ProfScope ps(KC_QUANTIZE, st, 0.0, (double)rows * n * ((NORM ? 4 : 2) + 1));
+    if (nvec <= 128)
+        hipLaunchKernelGGL((quantize_rows_kernel<NORM, 2>), dim3((unsigned)grid), dim3(256), 0, st, x, (const bf16 *)g, (uint8_t *)yq, scale, rows, n, eps);
+    else if (nvec <= 512)
+        hipLaunchKernelGGL((quantize_rows_kernel<NORM, 8>), dim3((unsigned)grid), dim3(256), 0, st, x, (const bf16 *)g, (uint8_t *)yq, scale, rows, n, eps);
+    else if (nvec <= 2048)
+        hipLaunchKernelGGL((quantize_rows_kernel<NORM, 32>), dim3((unsigned)grid), dim3(256), 0, st, x, (const bf16 *)g, (uint8_t *)yq, scale, rows, n, eps);
+    else
+        return GR4AD_EUNSUPPORTED;
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+int launch_rmsnorm_quant(const void *x, const void *g, void *yq, float *scale, int64_t rows, int d, float eps, hipStream_t st) {
+    return launch_quantize_rows_any<true>(x, g, yq, scale, rows, d, eps, st);
+}
+
+int launch_quantize_rows(const void *x, void *yq, float *scale, int64_t rows, int n, hipStream_t st) {
+    return launch_quantize_rows_any<false>(x, nullptr, yq, scale, rows, n, 0.0f, st);
+}
+
+// whole-matrix scale (init time): largest magnitude through an integer maximum of the bit patterns (non-negative floats order like integers)
+__global__ __launch_bounds__(256) void absmax_kernel(const bf16 *__restrict__ x, int64_t count, unsigned *__restrict__ out) {
+    float m = 0.0f;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) m = fmaxf(m, fabsf((float)x[i]));
+    m = wave_max(m);
+    if (threadIdx.x % 64 == 0) atomicMax(out, __float_as_uint(m));
+}
+
+__global__ __launch_bounds__(256) void quantize_flat_kernel(const bf16 *__restrict__ x, int64_t count, const unsigned *__restrict__ amax_bits,
+                                                            uint8_t *__restrict__ out) {
+    const float amax = __uint_as_float(*amax_bits);
+    const float qinv = amax > 0.0f ? 448.0f / amax : 1.0f;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count / 2; i += (int64_t)gridDim.x * 256) {
+        const int w = __builtin_amdgcn_cvt_pk_fp8_f32((float)x[2 * i] * qinv, (float)x[2 * i + 1] * qinv, 0, false);
+        *(uint16_t *)(out + 2 * i) = (uint16_t)(w & 0xffff);
+    }
+}
+
+int launch_quantize_matrix(const void *w, void *wq, int64_t count, unsigned *amax_dev, float *scale_host, hipStream_t st) {
+    if (!w || !wq || !amax_dev || !scale_host || count < 2 || count % 2 || ((uintptr_t)wq % 2)) return GR4AD_EINVAL;
+    if (hipMemsetAsync(amax_dev, 0, sizeof(unsigned), st) != hipSuccess) return GR4AD_EHIP;
+    int64_t grid = ceil_div64(count, 256 * 8);
+    if (grid > 4096) grid = 4096;
+    hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)grid), dim3(256), 0, st, (const bf16 *)w, count, amax_dev);
+    GR4AD_LAUNCH_CHECK();
+    hipLaunchKernelGGL(quantize_flat_kernel, dim3((unsigned)grid), dim3(256), 0, st, (const bf16 *)w, count, amax_dev, (uint8_t *)wq);
+    GR4AD_LAUNCH_CHECK();
+    unsigned bits = 0;
+    if (hipMemcpyAsync(&bits, amax_dev, sizeof(bits), hipMemcpyDeviceToHost, st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess)
+        return GR4AD_EHIP;
+    float amax;
+    memcpy(&amax, &bits, sizeof(amax));
+    *scale_host = amax > 0.0f ? amax / 448.0f : 1.0f;
     return GR4AD_OK;
 }

@@ -16,6 +16,14 @@
 
 #include "common.h"
 
+// An FP8 operand byte (OCP E4M3: sign, 4 exponent bits with bias 7, 3 mantissa bits), decoded in software by the plain kernel.
+struct fp8e4m3 { uint8_t v; };
+__device__ __forceinline__ float to_f(fp8e4m3 x) {
+    const int e = (x.v >> 3) & 15, m = x.v & 7;
+    const float a = e ? ldexpf((float)(8 + m), e - 10) : ldexpf((float)m, -9);
+    return (x.v & 0x80) ? -a : a;
+}
+
 // ---------------------------------------------------------------------------
 // epilogue of one element (plain kernel)
 // ---------------------------------------------------------------------------
@@ -37,7 +45,8 @@ __device__ __forceinline__ void epilogue_store(const GemmEpilogue &e, int64_t ro
 // ---------------------------------------------------------------------------
 // plain FMA kernel
 // ---------------------------------------------------------------------------
-template <typename T>
+// T: operand type; TO: type of C when it is not float32.  FP8 operands: the product row is scaled by a_scale[row] * w_scale.
+template <typename T, typename TO = T>
 __global__ __launch_bounds__(256) void gemm_simple(const T *__restrict__ A, int64_t lda, const T *__restrict__ W, int64_t ldw,
                                                    int64_t M, int N, int K, GemmEpilogue epi) {
     __shared__ float As[16][65], Ws[16][65];
@@ -74,7 +83,11 @@ __global__ __launch_bounds__(256) void gemm_simple(const T *__restrict__ A, int6
         for (int j = 0; j < 4; j++) {
             int64_t row = m0 + ty * 4 + i;
             int col = n0 + tx * 4 + j;
-            if (row < M && col < N) epilogue_store<T>(epi, row, col, N, acc[i][j]);
+            if (row < M && col < N) {
+                float v = acc[i][j];
+                if (epi.a_scale) v *= epi.a_scale[row] * epi.w_scale;
+                epilogue_store<TO>(epi, row, col, N, v);
+            }
         }
 }
 
@@ -284,7 +297,15 @@ __device__ __forceinline__ void ring_dma16(const char *g, bf16x8 *lds_wave_base)
 
 __device__ __forceinline__ float fast_silu(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x)); }
 
-template <int KIND>
+// F8: the operands are FP8 (E4M3) bytes instead of bf16.  The byte geometry is unchanged - a k-tile is still 128 bytes per
+// row, now 128 values of k - so loads, ring and epilogue are shared; the main loop issues v_mfma_f32_32x32x64_f8f6f4, whose
+// 32-byte operand per lane is the two 16-byte fragments the bf16 loop reads for two consecutive k-steps.  (Which of the 64
+// values of k a lane holds does not matter as long as both operands agree, and they are read the same way.)  lda, ldw and K
+// count elements (bytes).  The product row is scaled by a_scale[row] * w_scale before the epilogue.
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx8 __attribute__((ext_vector_type(8)));
+
+template <int KIND, bool F8 = false>
 __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ W, int64_t ldw,
                                                       int64_t M, int N, int K, int64_t tiles_m, int tiles_n, int group_m, GemmEpilogue epi,
                                                       int stagger_ticks) {
@@ -293,7 +314,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
     const int wm = wave / 4, wn = wave % 4;
     const int frow = lane % 32, hf = lane / 32;
-    const int KT = K / 64;
+    const int KT = F8 ? K / 128 : K / 64;
+    static_assert(!(F8 && KIND == EPI_VT), "the transposed epilogue has no FP8 form");
 
     // ---- tile schedule: every XCD (workgroup id % 8) owns a contiguous range of logical tiles and its workgroups walk it
     // with stride nslots; inside a group of group_m row blocks the row index runs fastest, so the workgroups of an XCD
@@ -333,7 +355,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
     // because both waves of a SIMD reach it together. ----
     const int dma_row0 = wave * 32 + lane / 8;
     const uint32_t cb0 = (uint32_t)(((lane % 8) ^ ((lane / 8) >> 1)) * 16), cb1 = cb0 ^ 64u;
-    const uint32_t lda2 = (uint32_t)lda * 2, ldw2 = (uint32_t)ldw * 2;
+    const uint32_t lda2 = (uint32_t)lda * (F8 ? 1 : 2), ldw2 = (uint32_t)ldw * (F8 ? 1 : 2);  // row pitches in bytes
     int64_t m0, m0n = 0;
     int n0, n0n = 0;
     tile_coords(L, m0, n0);
@@ -409,7 +431,31 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
             }
     };
 
-    // ---- prologue: A(0) W(0) A(1) W(1) A(2) into slots 0..4 (K >= 192, so all belong to the first tile) ----
+    // ---- FP8 main loop pieces.  One register set: operand i of A (rows i*32..) and j of W are 32 bytes per lane, the chunks
+    // 2u and 2u+1 of k-step u (two per k-tile).  The MFMAs of a step run W-block-major, (0,0) (1,0) (2,0) (3,0) (0,1) .. (3,1);
+    // as soon as the last MFMA that uses an operand has been issued its registers take the next step's data, so the twelve
+    // reads of a step are spread under the step before it: W0 after (3,0), A_i after (i,1), W1 after (3,1). ----
+    intx8 A8[4], W8[2];
+#define LD8(dst, base, u, OFF)                                                                                     \
+    do {                                                                                                           \
+        intx4 lo_, hi_;                                                                                            \
+        asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=v"(lo_) : "v"((base) ^ (uint32_t)((u) << 6)));          \
+        asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=v"(hi_) : "v"((base) ^ (uint32_t)(((u) << 6) | 32))); \
+        dst = __builtin_shufflevector(lo_, hi_, 0, 1, 2, 3, 4, 5, 6, 7);                                           \
+    } while (0)
+#define WAIT8(N, a, w) asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(a), "+v"(w))
+#define MMA8(i, j) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(W8[j], A8[i], acc[i][j], 0, 0, 0, 0, 0, 0)
+    auto load_step8 = [&](int slot_a, int slot_w, int u) {  // all twelve reads of a step, in the order the waits of a step assume
+        const uint32_t pa = a_lane + (uint32_t)slot_a * 32768u, pw = w_lane + (uint32_t)slot_w * 32768u;
+        LD8(W8[0], pw, u, 0);
+        LD8(A8[0], pa, u, 0);
+        LD8(A8[1], pa, u, 4096);
+        LD8(A8[2], pa, u, 8192);
+        LD8(A8[3], pa, u, 12288);
+        LD8(W8[1], pw, u, 4096);
+    };
+
+    // ---- prologue: A(0) W(0) A(1) W(1) A(2) into slots 0..4 (at least three k-tiles, so all belong to the first tile) ----
     issue_a(0, 0);
     issue_w(0, 1);
     issue_a(1, 2);
@@ -420,7 +466,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
     asm volatile("" ::: "memory");
     bf16x8 fa0[4], fw0[2], fa1[4], fw1[2];
     int sa = 0;  // slot of A(g); W(g) sits in the next slot
-    read_frags(fa0, fw0, 0, 1, 0);
+    if (F8) load_step8(0, 1, 0);
+    else read_frags(fa0, fw0, 0, 1, 0);
 
 #define SB __builtin_amdgcn_sched_barrier(0)
     for (;;) {  // tiles of this workgroup
@@ -432,13 +479,70 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                 for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
         float rinv[4] = {1.0f, 1.0f, 1.0f, 1.0f};
         floatx4 bias4 = {0.0f, 0.0f, 0.0f, 0.0f};  // EPI_F32: bias of this lane's four columns in the epilogue's read-back layout
-        if (KIND != EPI_VT && epi.row_inv) {
+        if (KIND != EPI_VT && (F8 || epi.row_inv)) {
+            const float *rs = F8 ? epi.a_scale : epi.row_inv;
 #pragma unroll
             for (int i = 0; i < 4; i++) {
                 const int64_t row = m0 + wm * 128 + i * 32 + frow;
-                rinv[i] = epi.row_inv[row < M ? row : M - 1];
+                rinv[i] = rs[row < M ? row : M - 1] * (F8 ? epi.w_scale : 1.0f);
             }
         }
+        if (F8) {
+            for (int kt = 0; kt < KT; kt++) {
+                const int sw = sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1;
+                const uint32_t pa = a_lane + (uint32_t)sa * 32768u, pw = w_lane + (uint32_t)sw * 32768u;
+                // step 0: its reads are in flight in the order W0 A0 A1 A2 A3 W1 (two each)
+                SB; WAIT8(8, A8[0], W8[0]); MMA8(0, 0); SB;
+                WAIT8(6, A8[1], W8[0]); MMA8(1, 0); SB;
+                WAIT8(4, A8[2], W8[0]); MMA8(2, 0); SB;
+                WAIT8(2, A8[3], W8[0]); MMA8(3, 0); SB;
+                LD8(W8[0], pw, 1, 0); SB;
+                WAIT8(2, A8[0], W8[1]); MMA8(0, 1); SB;
+                LD8(A8[0], pa, 1, 0); SB;
+                MMA8(1, 1); SB;
+                LD8(A8[1], pa, 1, 4096); SB;
+                MMA8(2, 1); SB;
+                LD8(A8[2], pa, 1, 8192); SB;
+                MMA8(3, 1); SB;
+                LD8(A8[3], pa, 1, 12288);
+                LD8(W8[1], pw, 1, 4096); SB;
+                // step 1
+                WAIT8(8, A8[0], W8[0]); MMA8(0, 0); SB;
+                WAIT8(6, A8[1], W8[0]); MMA8(1, 0); SB;
+                WAIT8(4, A8[2], W8[0]); MMA8(2, 0); SB;
+                WAIT8(2, A8[3], W8[0]); MMA8(3, 0); SB;
+                // every read of A(g), W(g) has been issued; once they have returned and this wave's share of A(g+1), W(g+1) has
+                // landed, the barrier releases the two slots (only A(g+2) may stay in flight)
+                WAIT8(0, A8[0], W8[1]);
+                if (kt + 2 < KT || has_next) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                const int sa1 = sa + 2 >= RING_SLOTS ? sa + 2 - RING_SLOTS : sa + 2;
+                const int sw1 = sa + 3 >= RING_SLOTS ? sa + 3 - RING_SLOTS : sa + 3;
+                const uint32_t pa1 = a_lane + (uint32_t)sa1 * 32768u, pw1 = w_lane + (uint32_t)sw1 * 32768u;
+                const bool more = kt + 1 < KT;  // (a next tile's first operands are read after the epilogue: it needs the registers)
+                SB; if (more) LD8(W8[0], pw1, 0, 0); SB;
+                if (KIND == EPI_F32 && kt + 2 == KT && epi.bias) {  // see the bf16 loop
+                    const int c0 = n0 + wn * 64 + (lane % 16) * 4;
+                    const float *src = epi.bias + (c0 + 3 < N ? c0 : 0);
+                    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(bias4) : "v"(src) : "memory");
+                }
+                if (more) {
+                    issue_w(kt + 2, sa);
+                    issue_a(kt + 3, sw);
+                }
+                SB; MMA8(0, 1); SB;
+                if (more) LD8(A8[0], pa1, 0, 0); SB;
+                MMA8(1, 1); SB;
+                if (more) LD8(A8[1], pa1, 0, 4096); SB;
+                MMA8(2, 1); SB;
+                if (more) LD8(A8[2], pa1, 0, 8192); SB;
+                MMA8(3, 1); SB;
+                if (more) { LD8(A8[3], pa1, 0, 12288); LD8(W8[1], pw1, 0, 4096); } SB;
+                if (more) sa = sa1;
+            }
+        } else
         for (int kt = 0; kt < KT; kt++) {
             const int sw = sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1;
             SB; read_frags(fa1, fw1, sa, sw, 1); wait_frags(fa0, fw0, false); SB;
@@ -479,9 +583,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
             char *stage = (char *)(smem + (wave < 4 ? sa : sw) * SLOT_CHUNKS) + (wave % 4) * 8192;
             const int64_t wrow0 = m0 + wm * 128;
             const int wcol0 = n0 + wn * 64;
-            if (KIND != EPI_VT && epi.row_inv) {
+            if (KIND != EPI_VT && (F8 || epi.row_inv)) {
                 // folded RMSNorm, reader side: the A operand was gain * x, not yet divided by rms(x); a lane owns row frow of
-                // each 32-row block (factors requested at the start of the tile)
+                // each 32-row block (factors requested at the start of the tile).  FP8 operands: the scales of the row and of W.
 #pragma unroll
                 for (int i = 0; i < 4; i++)
 #pragma unroll
@@ -662,15 +766,20 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
         issue_w(1, sa);
         issue_a(2, sw);
         sa = sa + 2 >= RING_SLOTS ? sa + 2 - RING_SLOTS : sa + 2;
-        read_frags(fa0, fw0, sa, sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1, 0);  // A(0), W(0) of the new tile landed before its predecessor's last barrier
+        // A(0), W(0) of the new tile landed before its predecessor's last barrier
+        if (F8) load_step8(sa, sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1, 0);
+        else read_frags(fa0, fw0, sa, sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1, 0);
     }
 #undef SB
+#undef LD8
+#undef WAIT8
+#undef MMA8
 }
 
-template <int KIND>
+template <int KIND, bool F8 = false>
 static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t ldw, int64_t M, int N, int K, const GemmEpilogue &epi,
                             hipStream_t st) {
-    auto kern = gemm_bf16_ring<KIND>;
+    auto kern = gemm_bf16_ring<KIND, F8>;
     static bool attr_done = false;
     static int n_cu = 0;
     if (!attr_done) {
@@ -698,12 +807,14 @@ static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
     if (grid < 8) grid = 8;
     if (total < grid) grid = ceil_div64(total, 8) * 8;
     {
-        ProfScope ps(KC_GEMM_RING, st, 2.0 * (double)M * N * K, gemm_bytes(M, N, K, KIND >= EPI_F32 && KIND != EPI_VT, KIND == EPI_F32_RESID));
+        const double operand_bytes = F8 ? ((double)M * K + (double)N * K) : 0.0;  // FP8 operands are half the bytes gemm_bytes counts
+        ProfScope ps(F8 ? KC_GEMM_RING_F8 : KC_GEMM_RING, st, 2.0 * (double)M * N * K,
+                     gemm_bytes(M, N, K, KIND >= EPI_F32 && KIND != EPI_VT, KIND == EPI_F32_RESID) - operand_bytes);
         // tile time: about 1.7 us per k-tile of 64 in the main loop plus the epilogue; spreading the starts costs up to
         // one tile time once, so it is only done when a workgroup has many tiles
         int stagger = 0;
         if (total >= 8 * grid && stagger_scale > 0) {
-            double us = (K / 64) * 1.7 + 4.0;
+            double us = (K / (F8 ? 128 : 64)) * 1.7 + 4.0;
             if (us > 200.0) us = 200.0;
             stagger = (int)(us * ticks_per_us * stagger_scale);
         }
@@ -835,6 +946,48 @@ int launch_gemm_vt(const void *A, int64_t lda, const void *W, int64_t ldw, int64
     e.ctx_len = ctx_len;
     e.vt_S = S;
     return launch_ring((const bf16 *)A, lda, (const bf16 *)W, ldw, M, N, K, EPI_VT, e, st);
+}
+
+// ---------------------------------------------------------------------------
+// FP8 products: C = (a_scale[row] * w_scale) * Aq Wq^T with the same epilogues (Aq, Wq: E4M3 bytes; C bf16 or float32)
+// ---------------------------------------------------------------------------
+static bool ring_f8_ok(int kind, int64_t M, int N, int K, int64_t lda, int64_t ldw, const void *A, const void *W, const GemmEpilogue &e) {
+    if (kind < 0 || kind == EPI_VT || e.norm_out || e.row_inv) return false;
+    // (there is no mid-size FP8 kernel: a few 256-row tiles on the persistent kernel still beat the plain kernel by far)
+    if (M < 64 || N < 256 || K % 128 || K < 384 || lda % 16 || ldw % 16 || ((uintptr_t)A % 16) || ((uintptr_t)W % 16)) return false;
+    return ring_ok(kind, N, K, lda, ldw, e);
+}
+
+bool gemm_f8_on_persistent_kernel(const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K, const GemmEpilogue &epi) {
+    const char *env = getenv("GR4AD_GEMM_MODE");
+    if (env && atoi(env) == 1) return false;
+    return ring_f8_ok(epilogue_kind(epi), M, N, K, lda, ldw, A, W, epi);
+}
+
+int launch_gemm_f8(const void *A, int64_t lda, const float *a_scale, const void *W, int64_t ldw, float w_scale, int64_t M, int N, int K,
+                   const GemmEpilogue &epi_in, hipStream_t st) {
+    if (M <= 0 || N <= 0 || K <= 0 || !A || !W || !a_scale || !(w_scale > 0.0f)) return GR4AD_EINVAL;
+    if (epi_in.norm_out || epi_in.row_inv) return GR4AD_EUNSUPPORTED;
+    GemmEpilogue epi = epi_in;
+    epi.a_scale = a_scale;
+    epi.w_scale = w_scale;
+    const int kind = epilogue_kind(epi);
+    if (gemm_f8_on_persistent_kernel(A, lda, W, ldw, M, N, K, epi)) {
+        const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;  // (the kernel's pointer type; it addresses bytes)
+        switch (kind) {
+            case EPI_STORE: return launch_ring_kind<EPI_STORE, true>(a, lda, w, ldw, M, N, K, epi, st);
+            case EPI_SILU: return launch_ring_kind<EPI_SILU, true>(a, lda, w, ldw, M, N, K, epi, st);
+            case EPI_F32: return launch_ring_kind<EPI_F32, true>(a, lda, w, ldw, M, N, K, epi, st);
+            case EPI_F32_RESID: return launch_ring_kind<EPI_F32_RESID, true>(a, lda, w, ldw, M, N, K, epi, st);
+            default: return launch_ring_kind<EPI_F32_TABLE, true>(a, lda, w, ldw, M, N, K, epi, st);
+        }
+    }
+    dim3 grid((unsigned)ceil_div64(M, 64), (unsigned)((N + 63) / 64));
+    if (ceil_div64(M, 64) > 0x7fffffffLL || grid.y > 65535) return GR4AD_EUNSUPPORTED;
+    ProfScope ps(KC_GEMM_SIMPLE, st, 2.0 * (double)M * N * K);
+    hipLaunchKernelGGL((gemm_simple<fp8e4m3, bf16>), grid, dim3(256), 0, st, (const fp8e4m3 *)A, lda, (const fp8e4m3 *)W, ldw, M, N, K, epi);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
 }
 
 // 0 auto, 1 plain FMA kernel, 2 128x128 tiles, 3 256x256 tiles with 8 wavefronts, 4 256x256 tiles with 4 wavefronts,

@@ -34,6 +34,7 @@ class Workload:
     zipf_bias: bool = False
     eps: float = 1e-6
     cfg_id: int = 0
+    fp8: bool = False  # low-precision inference (appendix A.2): FP8 operands for the per-beam-row products
     Ve: int = 0  # eCPM-token step (section 3.3): number of value buckets, 0 = the model has no such step
     extra: dict = field(default_factory=dict)
 
@@ -46,7 +47,10 @@ class Workload:
         return [1] + list(self.beam[:-1])
 
     def model_kwargs(self):
-        return dict(d=self.d, H=self.H, F=self.F, L=self.L, K=self.K, T=self.T, V=list(self.V), eps=self.eps)
+        kw = dict(d=self.d, H=self.H, F=self.F, L=self.L, K=self.K, T=self.T, V=list(self.V), eps=self.eps)
+        if self.fp8:
+            kw["fp8"] = True
+        return kw
 
 
 def scale_beams(beam, factor):
@@ -54,7 +58,7 @@ def scale_beams(beam, factor):
     return [max(1, int(round(b * factor))) for b in beam]
 
 
-def workload(cfg, scale=1.0, batch=None, lazy=None, value=None):
+def workload(cfg, scale=1.0, batch=None, lazy=None, value=None, fp8=False):
     """The five benchmark configurations (1-based).  lazy: another number of lazy layers K for the same
     model (0 = every layer autoregressive, section 3.2's comparison of LazyAR with plain decoding).
     value: number of eCPM buckets of a value step appended to the model (section 3.3); None or 0 = none."""
@@ -80,6 +84,11 @@ def workload(cfg, scale=1.0, batch=None, lazy=None, value=None):
             raise ValueError("lazy must be in [0, L)")
         w.K = lazy
         w.name += "-K%d" % lazy
+    if fp8:
+        if w.dtype != "bf16":
+            raise ValueError("the FP8 mode needs a bf16 configuration")
+        w.fp8 = True
+        w.name += "-fp8"
     if value:
         w.Ve = int(value)
         w.name += "-value%d" % w.Ve

@@ -1,0 +1,142 @@
+"""GPU parity of the FP8 mode (appendix A.2, low-precision inference) against the oracle's FP8 mode: the row quantiser,
+the FP8 product on both kernels, and whole decodes (through the C ABI)."""
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_common import gpu_decode, judge_decode, judge_value
+from helpers import tiny
+from paper_2602_22732_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+F8 = torch.float8_e4m3fn
+
+
+def decode_bytes(q):
+    """E4M3 bytes (uint8 tensor) -> float64 numpy, by PyTorch's own float8 type."""
+    return q.cpu().view(F8).to(torch.float64).numpy()
+
+
+@pytest.mark.parametrize("rows,n", [(5, 8), (33, 64), (300, 1024), (64, 4096), (7, 520), (3, 16384)])
+def test_quantize_rows_matches_oracle(rows, n):
+    rng = np.random.default_rng(zlib.crc32(b"q%d_%d" % (rows, n)))
+    x = rng.standard_normal((rows, n)) * np.exp(rng.uniform(-6, 6, (rows, 1)))
+    if rows > 4:
+        x[3] = 0.0                      # a zero row
+        x[4, 1:] = 0.0                  # a row with one non-zero value
+    xb = torch.tensor(x, dtype=torch.float32).to(torch.bfloat16).cuda().contiguous()
+    q, scale = binding.op_quantize_rows(xb)
+    torch.cuda.synchronize()
+    xr = xb.cpu().to(torch.float64).numpy()
+    amax = np.abs(xr).max(axis=1)
+    want_scale = np.where(amax > 0, amax / 448, 1.0)
+    np.testing.assert_allclose(scale.cpu().numpy(), want_scale, rtol=2e-7)
+    got = decode_bytes(q) * want_scale[:, None]
+    want = oracle.prim_quant_rows(xr)
+    # the GPU scales in float32 (x * (448 / amax)), the oracle in float64 (x / (amax / 448)): a value within rounding of a
+    # tie may land on the neighbouring grid point.  bf16 inputs have 8 significant bits, so near-ties are not rare (a few
+    # per thousand); nothing may be further off than one grid step.
+    step = np.maximum(np.abs(want) * 2.0 ** -3, want_scale[:, None] * 2.0 ** -9)
+    diff = np.abs(got - want)
+    assert (diff <= step * (1 + 1e-6)).all()
+    assert (diff > 1e-6 * np.maximum(np.abs(want), 1e-30)).mean() < 1e-2
+    assert np.isfinite(got).all()
+
+
+def random_e4m3(rng, shape):
+    b = rng.integers(0, 256, shape, dtype=np.uint8)
+    b[(b & 0x7F) == 0x7F] = 0x3A        # the two NaN codes
+    return b
+
+
+@pytest.mark.parametrize("M,N,K,out_f32,bias", [
+    (37, 50, 72, True, True),            # plain kernel, ragged everywhere
+    (300, 256, 384, False, False),       # matrix-core kernel, two row tiles, the second ragged
+    (63, 256, 384, True, False),         # plain kernel (too few rows)
+    (8192 + 77, 256, 384, True, True),   # matrix-core kernel: shortest K it takes, ragged last row tile
+    (8192, 384, 1024, False, False),     # ragged column tile, bf16 output
+    (16384 + 5, 1024, 4096, True, False),
+])
+def test_linear_fp8_matches_exact_product(M, N, K, out_f32, bias):
+    rng = np.random.default_rng(zlib.crc32(b"l%d_%d_%d" % (M, N, K)))
+    A, W = random_e4m3(rng, (M, K)), random_e4m3(rng, (N, K))
+    a_scale = np.exp(rng.uniform(-3, 3, M)).astype(np.float32)
+    w_scale = 0.0123
+    b = rng.standard_normal(N).astype(np.float32) if bias else None
+    Aq, Wq = torch.from_numpy(A).cuda(), torch.from_numpy(W).cuda()
+    C = binding.op_linear_fp8(Aq, torch.from_numpy(a_scale).cuda(), Wq, w_scale, None if b is None else torch.from_numpy(b).cuda(), out_f32=out_f32)
+    torch.cuda.synchronize()
+    C = C.float().cpu().numpy()
+    rows = np.unique(np.concatenate([np.arange(0, M, max(1, M // 41)), np.arange(max(0, M - 70), M)]))   # sampled rows, and the ragged tail
+    Ad, Wd = decode_bytes(Aq[torch.from_numpy(rows).cuda()]), decode_bytes(Wq)
+    want = oracle.prim_linear(Ad, Wd) * (a_scale[rows].astype(np.float64)[:, None] * np.float64(np.float32(w_scale)))
+    if b is not None:
+        want = want + b
+    # Products of E4M3 values are exact in float32; what remains is the accumulation (and bf16 rounding of the output).  The
+    # plain kernel adds in float32, term by term.  A matrix-core instruction adds its 64 products in one step and keeps a
+    # limited number of bits below the largest of them (measured on these operands, which span the format's whole range of
+    # 2^-9 .. 448: 7e-5 of the sum of magnitudes; a dropped or doubled term would show as 3e-3 at K = 384).
+    mag = np.abs(Ad) @ np.abs(Wd).T * (a_scale[rows][:, None] * w_scale) + 1e-30
+    on_matrix_cores = M >= 64 and N >= 256 and K % 128 == 0 and K >= 384
+    tol = mag * ((2e-4 if on_matrix_cores else 2e-6) if out_f32 else 0) + ((np.abs(want) * 2.0 ** -8 + mag * 2e-4) if not out_f32 else 0)
+    assert (np.abs(C[rows] - want) <= tol + 1e-12).all(), float((np.abs(C[rows] - want) / mag).max())
+    assert np.isfinite(C).all()
+
+
+# Two FP8 pipelines that differ by bf16-level rounding upstream do not stay that close: an activation that differs by delta
+# from the oracle's lands on the neighbouring E4M3 code with probability |delta| / step and then differs by a whole step, an
+# RMS deviation of sqrt(|delta| * step) - for delta = 2^-9 and step = 2^-3.5 of the value that is 1.3 % of it, half of the
+# quantisation noise itself (step / sqrt(12) = 2.5 %).  So the GPU is held to the oracle's FP8 mode within a tolerance of the
+# size of the FP8 effect: on these toy models the oracle's FP8 and full-precision log-probabilities differ by up to 0.8 at a
+# level (mean 0.05 to 0.25), the GPU's cumulative scores were measured up to 0.30 from the FP8 oracle's and are held to 0.5.
+# A wrong scale, operand or weight shows as an error of the size of the logits themselves (a range of 4 to 6 here).  The
+# benchmark-shaped configuration below is held to its own, measured and much smaller, figure.
+TOY_FP8_TOL = 0.5
+
+
+@pytest.mark.parametrize("shape", [
+    dict(T=3, V=[40, 33, 50], d=64, H=2, F=96, L=3, K=1, S=37, B=5, beam=[7, 13, 9], len_min=5),        # plain kernels, ragged
+    dict(T=2, V=[520, 130], d=256, H=2, F=64, L=2, K=0, S=9, B=2, beam=[300, 77]),                   # no lazy layer
+    dict(T=3, V=[40, 33, 50], d=128, H=2, F=96, L=3, K=2, S=37, B=5, beam=[7, 13, 9], len_min=1),       # absorbed lazy attention beside FP8 levels
+    dict(T=2, V=[512, 512], d=512, H=8, F=1024, L=3, K=1, S=64, B=48, beam=[192, 256]),              # rows and widths of the matrix-core kernel
+])
+def test_fp8_decode_matches_fp8_oracle(shape):
+    w, W, X = tiny(dtype="bf16", gain_jitter=0.1, **shape)
+    w.fp8 = True
+    lens = synth.make_lengths(w, seed=11)
+    sid, lp, tr = gpu_decode(w, W, X, lens)
+    sample = range(w.B) if w.B <= 8 else [0, 17, w.B - 1]
+    print(shape["V"], judge_decode(w, W, X, lens, sid, lp, tr, sample, tol=TOY_FP8_TOL, margin=2 * TOY_FP8_TOL))
+
+
+def test_fp8_value_step_and_flag_validation():
+    w, W, X = tiny(dtype="bf16", gain_jitter=0.1, T=2, V=[64, 50], Ve=32, d=128, H=2, F=128, L=2, K=1, S=20, B=3, beam=[8, 12])
+    w.fp8 = True
+    sid, lp, tr, val = gpu_decode(w, W, X, None, value=True)
+    judge_decode(w, W, X, None, sid, lp, tr, range(w.B), tol=TOY_FP8_TOL, margin=2 * TOY_FP8_TOL)
+    print("value:", judge_value(w, W, X, None, sid, lp, val, range(w.B), tol=TOY_FP8_TOL))
+    # float32 storage has no FP8 mode
+    w32, W32, _ = tiny(dtype="f32", T=2, V=[8, 8], d=64, H=2, F=64, L=2, K=1, S=4, B=1, beam=[2, 2])
+    w32.fp8 = True
+    with pytest.raises(binding.Gr4adError, match="bf16"):
+        binding.decoder_for(w32, W32)
+
+
+# Configuration 3: the oracle's FP8 and full-precision log-probabilities differ by up to 0.12 at a level (mean 0.024; 0.08 among
+# the 256 likeliest codes); the GPU's cumulative survivor scores were measured up to 0.15 from the FP8 oracle's over three levels.
+CONFIG_FP8_TOL = 0.2
+
+
+def test_config3_fp8_sampled_requests():
+    w = synth.workload(3, fp8=True)
+    W = synth.make_weights(w)
+    lens = synth.make_lengths(w)
+    X = synth.make_context(w, lens)
+    sid, lp, tr = gpu_decode(w, W, X, lens)
+    assert np.isfinite(lp).all() and (lp <= 0).all() and (np.diff(lp, axis=1) <= 0).all()
+    stats = judge_decode(w, W, X, lens, sid, lp, tr, [0, 130], tol=CONFIG_FP8_TOL, margin=2 * CONFIG_FP8_TOL)
+    print("config 3 fp8:", stats)
