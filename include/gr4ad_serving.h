@@ -47,7 +47,8 @@ void gr4ad_tabs_free(gr4ad_tabs *ctl); /* NULL is a no-op */
 
 /* n_requests arrived at time t_s (t_s must not run backwards: EINVAL).  Updates the traffic estimate
  *   Q <- Q * exp(-dt/tau) + (n/dt) * (1 - exp(-dt/tau)),  dt = t_s - time of the previous update
- * (arrivals that share a time stamp are added to the next interval). */
+ * Reports that share a time stamp belong to the same interval: the last update is redone with their sum.  Arrivals
+ * stamped with the controller's very first time are counted in the first interval. */
 int gr4ad_tabs_observe(gr4ad_tabs *ctl, double t_s, int32_t n_requests);
 
 /* Q_t as of the last update; negative on a NULL controller. */

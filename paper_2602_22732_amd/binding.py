@@ -23,6 +23,10 @@ EXPORTS = ["gr4ad_decode_init", "gr4ad_decode_workspace_bytes", "gr4ad_decode_ba
            "gr4ad_profile_enable",
            "gr4ad_profile_kernel_count", "gr4ad_profile_kernel_name", "gr4ad_profile_read"]
 
+SERVING_EXPORTS = ["gr4ad_tabs_create", "gr4ad_tabs_free", "gr4ad_tabs_observe", "gr4ad_tabs_qps", "gr4ad_tabs_schedule",
+                   "gr4ad_cache_create", "gr4ad_cache_free", "gr4ad_cache_insert", "gr4ad_cache_lookup", "gr4ad_cache_lookup_batch",
+                   "gr4ad_cache_stats"]
+
 _IP = C.POINTER(C.c_int32)
 _VP = C.c_void_p
 
@@ -43,6 +47,11 @@ class Weights(C.Structure):
                 ("layers", C.POINTER(LayerWeights)), ("ln_out_dev", _VP), ("cls_dev", C.POINTER(_VP)),
                 ("cls_bias_dev", C.POINTER(_VP)),
                 ("value_pos_dev", _VP), ("value_emb_dev", _VP), ("value_cls_dev", _VP), ("value_bias_dev", _VP)]
+
+
+class TabsConfig(C.Structure):
+    _fields_ = [("n_levels", C.c_int32), ("beam_base", _IP), ("max_beam", _IP), ("codebook", _IP), ("qps_peak", C.c_double),
+                ("scale_min", C.c_double), ("scale_max", C.c_double), ("step", C.c_double), ("tau_s", C.c_double)]
 
 
 class Gr4adError(RuntimeError):
@@ -101,6 +110,29 @@ def lib():
         L.gr4ad_profile_kernel_name.argtypes = [C.c_int]
         L.gr4ad_profile_read.restype = C.c_int
         L.gr4ad_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
+        _I64P, _U64P = C.POINTER(C.c_int64), C.POINTER(C.c_uint64)
+        L.gr4ad_tabs_create.restype = C.c_int
+        L.gr4ad_tabs_create.argtypes = [C.POINTER(TabsConfig), C.POINTER(_VP)]
+        L.gr4ad_tabs_free.restype = None
+        L.gr4ad_tabs_free.argtypes = [_VP]
+        L.gr4ad_tabs_observe.restype = C.c_int
+        L.gr4ad_tabs_observe.argtypes = [_VP, C.c_double, C.c_int32]
+        L.gr4ad_tabs_qps.restype = C.c_double
+        L.gr4ad_tabs_qps.argtypes = [_VP]
+        L.gr4ad_tabs_schedule.restype = C.c_int
+        L.gr4ad_tabs_schedule.argtypes = [_VP, C.c_double, C.c_double, _IP, C.POINTER(C.c_double)]
+        L.gr4ad_cache_create.restype = C.c_int
+        L.gr4ad_cache_create.argtypes = [C.c_int64, C.c_double, C.c_int32, C.c_int32, C.POINTER(_VP)]
+        L.gr4ad_cache_free.restype = None
+        L.gr4ad_cache_free.argtypes = [_VP]
+        L.gr4ad_cache_insert.restype = C.c_int
+        L.gr4ad_cache_insert.argtypes = [_VP, C.c_uint64, C.c_double, _IP, C.POINTER(C.c_float), C.c_int32]
+        L.gr4ad_cache_lookup.restype = C.c_int
+        L.gr4ad_cache_lookup.argtypes = [_VP, C.c_uint64, C.c_double, _IP, C.POINTER(C.c_float), _IP]
+        L.gr4ad_cache_lookup_batch.restype = C.c_int
+        L.gr4ad_cache_lookup_batch.argtypes = [_VP, _U64P, C.c_int32, C.c_double, C.POINTER(C.c_uint8), _IP, _IP]
+        L.gr4ad_cache_stats.restype = C.c_int
+        L.gr4ad_cache_stats.argtypes = [_VP, _I64P, _I64P, _I64P, _I64P, _I64P]
         _lib = L
     return _lib
 
@@ -321,3 +353,86 @@ def op_gather_rows(src, parent, k=None, row_elems=None, stream=None):
     _check(lib().gr4ad_op_gather_rows(dtype_code(src.dtype), src.data_ptr(), parent.data_ptr(), dst.data_ptr(), B, n, k,
                                       stride if row_elems is None else row_elems, stride, _stream_ptr(stream)))
     return dst
+
+
+# ---- host-side serving policies (include/gr4ad_serving.h) ------------------------------
+class TabsController:
+    """gr4ad_tabs_*: the beam schedule of a call from the traffic (Traffic-Aware Adaptive Beam Search)."""
+
+    def __init__(self, beam_base, max_beam, codebook, qps_peak, scale_min=1.0, scale_max=1.6, step=0.1, tau_s=10.0):
+        self.L_ = lib()
+        self.T = len(beam_base)
+        arrs = [_i32arr(a) for a in (beam_base, max_beam, codebook)]
+        cfg = TabsConfig(self.T, arrs[0][1], arrs[1][1], arrs[2][1], qps_peak, scale_min, scale_max, step, tau_s)
+        h = _VP()
+        _check(self.L_.gr4ad_tabs_create(C.byref(cfg), C.byref(h)))
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.L_.gr4ad_tabs_free(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+    def observe(self, t_s, n_requests):
+        _check(self.L_.gr4ad_tabs_observe(self.handle, t_s, n_requests))
+
+    def qps(self):
+        return float(self.L_.gr4ad_tabs_qps(self.handle))
+
+    def schedule(self, t_s, c_avail=1.0):
+        beam = (C.c_int32 * self.T)()
+        scale = C.c_double()
+        _check(self.L_.gr4ad_tabs_schedule(self.handle, t_s, c_avail, beam, C.byref(scale)))
+        return list(beam), scale.value
+
+
+class ResultCache:
+    """gr4ad_cache_*: per-user results reused inside a time window (Reco Result Cache)."""
+
+    def __init__(self, capacity, ttl_s, n_levels, max_items):
+        self.L_ = lib()
+        self.T, self.max_items = n_levels, max_items
+        h = _VP()
+        _check(self.L_.gr4ad_cache_create(capacity, ttl_s, n_levels, max_items, C.byref(h)))
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.L_.gr4ad_cache_free(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+    def insert(self, key, now_s, sid, logprob):
+        sid = np.ascontiguousarray(sid, dtype=np.int32)
+        logprob = np.ascontiguousarray(logprob, dtype=np.float32)
+        _check(self.L_.gr4ad_cache_insert(self.handle, key, now_s, sid.ctypes.data_as(_IP), logprob.ctypes.data_as(C.POINTER(C.c_float)),
+                                          logprob.shape[0]))
+
+    def lookup(self, key, now_s):
+        """(sid [n,T], logprob [n]) or None."""
+        sid = np.empty((self.max_items, self.T), np.int32)
+        lp = np.empty(self.max_items, np.float32)
+        n = C.c_int32()
+        r = self.L_.gr4ad_cache_lookup(self.handle, key, now_s, sid.ctypes.data_as(_IP), lp.ctypes.data_as(C.POINTER(C.c_float)), C.byref(n))
+        if r < 0:
+            _check(r)
+        return (sid[:n.value], lp[:n.value]) if r == 1 else None
+
+    def lookup_batch(self, keys, now_s):
+        """(hit [B] uint8, indices of the requests to decode)."""
+        keys = np.ascontiguousarray(keys, dtype=np.uint64)
+        B = keys.shape[0]
+        hit = np.empty(B, np.uint8)
+        miss = np.empty(B, np.int32)
+        n = C.c_int32()
+        _check(self.L_.gr4ad_cache_lookup_batch(self.handle, keys.ctypes.data_as(C.POINTER(C.c_uint64)), B, now_s,
+                                                hit.ctypes.data_as(C.POINTER(C.c_uint8)), miss.ctypes.data_as(_IP), C.byref(n)))
+        return hit, miss[:n.value].copy()
+
+    def stats(self):
+        v = [C.c_int64() for _ in range(5)]
+        _check(self.L_.gr4ad_cache_stats(self.handle, *[C.byref(x) for x in v]))
+        return dict(zip(("lookups", "hits", "entries", "evictions", "expired"), (x.value for x in v)))
