@@ -140,3 +140,16 @@ def test_config3_fp8_sampled_requests():
     assert np.isfinite(lp).all() and (lp <= 0).all() and (np.diff(lp, axis=1) <= 0).all()
     stats = judge_decode(w, W, X, lens, sid, lp, tr, [0, 130], tol=CONFIG_FP8_TOL, margin=2 * CONFIG_FP8_TOL)
     print("config 3 fp8:", stats)
+
+
+def test_config5_fp8_full_batch_sampled_request():
+    # the workload bench.py --fp8 times: 2048 requests, beams 256/512/512/1024, Zipf bias; one request judged by the FP8 oracle
+    w = synth.workload(5, fp8=True)
+    W = synth.make_weights(w)
+    lens = synth.make_lengths(w)
+    X = synth.make_context(w, lens)
+    sid, lp, tr = gpu_decode(w, W, X, lens)
+    assert np.isfinite(lp).all() and (lp <= 0).all() and (np.diff(lp, axis=1) <= 0).all()
+    for r in range(0, w.B, 64):
+        assert len({tuple(p) for p in sid[r]}) == w.beam[-1]
+    print("config 5 fp8:", judge_decode(w, W, X, lens, sid, lp, tr, [777], tol=CONFIG_FP8_TOL, margin=2 * CONFIG_FP8_TOL))

@@ -76,3 +76,15 @@ def test_config3_with_value_step_sampled_requests():
     print("config 3 + value:", judge_decode(w, W, X, lens, sid, lp, tr, sample), "max, mean value error",
           judge_value(w, W, X, lens, sid, lp, val, sample))
     assert np.isfinite(val).all() and (val <= 0).all()
+
+
+def test_config4_with_value_step_full_batch_sampled_request():
+    # the workload bench.py --config 4 --value 256 times: 1024 requests, 1024 returned SIDs each
+    w = synth.workload(4, value=256)
+    W = synth.make_weights(w)
+    lens = synth.make_lengths(w)
+    X = synth.make_context(w, lens)
+    sid, lp, tr, val = gpu_decode(w, W, X, lens, value=True)
+    assert val.shape == (w.B, w.beam[-1], 256) and np.isfinite(val).all() and (val <= 0).all()
+    assert np.abs(np.exp(val[::97].astype(np.float64)).sum(axis=2) - 1).max() < 1e-4
+    print("config 4 + value:", judge_decode(w, W, X, lens, sid, lp, tr, [511]), "max, mean value error", judge_value(w, W, X, lens, sid, lp, val, [511]))
