@@ -274,10 +274,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(con
 // five half-tiles, filled by global_load_lds_dwordx4 (every lane moves 16 bytes straight into LDS; one wave
 // instruction fills 8 rows; chunk c of row r sits at position c ^ ((r >> 1) & 7), which keeps both the 1 KB
 // writes and the fragment reads conflict-free, and the swizzle is applied on the global side).  In item order
-// A0 W0 A1 W1 A2 ... item q lives in slot q % 5, so after the barrier that ends k-tile g its two slots take
-// W(g+2) and A(g+3): the operand that streams from HBM is requested two k-tiles ahead, the L2-resident weights
-// one k-tile ahead.  The item stream runs on into the next tile of the workgroup, so a tile's first operands
-// arrive while the previous tile is still being multiplied and stored.
+// A0 W0 A1 W1 A2 ... item q lives in slot q % 5.  The bf16 loop requests A(g+2) under the first MFMAs of k-tile g (into
+// the slot W(g-1) left at the previous barrier) and W(g+2) under the MFMAs that follow the barrier ending k-tile g (into
+// the slot A(g) just left), one load after every second MFMA: a burst of eight loads per wave right after the barrier
+// holds up the MFMAs queued behind it.  (The FP8 loop still requests W(g+2) and A(g+3) together after the barrier.)
+// The item stream runs on into the next tile of the workgroup, so a tile's first operands arrive while the previous
+// tile is still being multiplied and stored.
 // Per k-tile: four k-steps of 8 MFMAs; the fragments of step s+1 are read while step s multiplies.  Fragment
 // reads are inline assembly so that their waits can be exact (lgkmcnt(6): the six reads just issued may still
 // be in flight); one bare s_barrier per k-tile separates "every wave has read A(g), W(g)" from "everybody's
@@ -349,10 +351,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
 
     // ---- loads: load j of this wave fills rows (wave*4+j)*8 .. +7 of a half-tile, lane -> row lane/8, position lane%8.
     // The chunk that lives at position p of row r is p ^ ((r >> 1) & 7), and (r >> 1) & 7 = 4*(j&1) + (lane/8 >> 1).
-    // Per tile: a wave-uniform base pointer (row block; a k-tile adds 128 bytes) and per-lane 32-bit offsets (row inside
-    // the block, clamped at the matrix edge so rows past the end re-read the last row, times the pitch, plus the chunk).
-    // A load then costs one scalar add: whatever else sits between the barrier and the MFMAs idles the matrix cores,
-    // because both waves of a SIMD reach it together. ----
+    // Per tile: a wave-uniform base pointer (row block; a k-tile adds 128 bytes) and the last valid row of the block (rows
+    // past the matrix edge re-read it).  The lane's byte offset - clamped row times the pitch plus the chunk - is computed
+    // when the load is issued (three vector instructions that run beside the MFMAs) instead of being kept per tile. ----
     const int dma_row0 = wave * 32 + lane / 8;
     const uint32_t cb0 = (uint32_t)(((lane % 8) ^ ((lane / 8) >> 1)) * 16), cb1 = cb0 ^ 64u;
     const uint32_t lda2 = (uint32_t)lda * (F8 ? 1 : 2), ldw2 = (uint32_t)ldw * (F8 ? 1 : 2);  // row pitches in bytes
@@ -361,42 +362,42 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
     tile_coords(L, m0, n0);
     bool has_next = L + nslots < xcd_end;
     if (has_next) tile_coords(L + nslots, m0n, n0n);
-    typedef uint32_t offvec __attribute__((ext_vector_type(4)));
-    offvec offA, offW, offAn, offWn;
-    const char *baseA, *baseW, *baseAn = nullptr, *baseWn = nullptr;
-    auto tile_sources = [&](int64_t tm0, int tn0, const char *&bA, const char *&bW, offvec &oA, offvec &oW) {
+    const char *baseA, *baseW, *baseAn, *baseWn;
+    int maxa, maxw, maxan, maxwn;
+    auto tile_sources = [&](int64_t tm0, int tn0, const char *&bA, const char *&bW, int &mA, int &mW) {
         bA = (const char *)A + tm0 * lda2;
         bW = (const char *)W + (int64_t)tn0 * ldw2;
-        const int maxa = (int)(M - 1 - tm0 < 255 ? M - 1 - tm0 : 255), maxw = N - 1 - tn0 < 255 ? N - 1 - tn0 : 255;
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const int r = dma_row0 + j * 8;
-            oA[j] = (uint32_t)(r < maxa ? r : maxa) * lda2 + ((j & 1) ? cb1 : cb0);
-            oW[j] = (uint32_t)(r < maxw ? r : maxw) * ldw2 + ((j & 1) ? cb1 : cb0);
-        }
+        mA = (int)(M - 1 - tm0 < 255 ? M - 1 - tm0 : 255);
+        mW = N - 1 - tn0 < 255 ? N - 1 - tn0 : 255;
     };
-    tile_sources(m0, n0, baseA, baseW, offA, offW);
-    offAn = offA; offWn = offW;
-    if (has_next) tile_sources(m0n, n0n, baseAn, baseWn, offAn, offWn);
-    // k-tile gk of the current tile (gk < KT) or of the workgroup's next tile (gk >= KT).  The offsets of the two tiles are
-    // blended arithmetically: a select between the two variables would make the compiler keep them in scratch memory.
+    tile_sources(m0, n0, baseA, baseW, maxa, maxw);
+    // Without a next tile the loads that would fetch its first k-tiles re-read the current tile's instead (valid memory, into
+    // slots nobody reads again and the epilogue does not stage in; all of them have landed at the tile's last barrier): the
+    // load sequence stays free of branches, which the register allocation of this kernel depends on.
+    baseAn = baseA; baseWn = baseW; maxan = maxa; maxwn = maxw;
+    if (has_next) tile_sources(m0n, n0n, baseAn, baseWn, maxan, maxwn);
+    // piece j (8 rows) of this wave's share of a half-tile
+    auto load_piece = [&](const char *base, int mx, uint32_t pitch, bf16x8 *dst, int j) {
+        const int r = dma_row0 + j * 8;
+        const uint32_t off = (uint32_t)(r < mx ? r : mx) * pitch + ((j & 1) ? cb1 : cb0);
+        ring_dma16(base + off, dst + j * 64);
+    };
+    // k-tile gk of the current tile (gk < KT) or of the workgroup's next tile (gk >= KT)
     auto issue_a = [&](int gk, int slot) {
         const bool cur = gk < KT;
-        if (!cur && !has_next) return;
         const char *base = cur ? baseA + gk * 128 : baseAn + (gk - KT) * 128;
-        const offvec off = offA + (offAn - offA) * (cur ? 0u : 1u);
+        const int mx = cur ? maxa : maxan;
         bf16x8 *dst = smem + slot * SLOT_CHUNKS + wave * 256;
 #pragma unroll
-        for (int j = 0; j < 4; j++) ring_dma16(base + off[j], dst + j * 64);
+        for (int j = 0; j < 4; j++) load_piece(base, mx, lda2, dst, j);
     };
     auto issue_w = [&](int gk, int slot) {
         const bool cur = gk < KT;
-        if (!cur && !has_next) return;
         const char *base = cur ? baseW + gk * 128 : baseWn + (gk - KT) * 128;
-        const offvec off = offW + (offWn - offW) * (cur ? 0u : 1u);
+        const int mx = cur ? maxw : maxwn;
         bf16x8 *dst = smem + slot * SLOT_CHUNKS + wave * 256;
 #pragma unroll
-        for (int j = 0; j < 4; j++) ring_dma16(base + off[j], dst + j * 64);
+        for (int j = 0; j < 4; j++) load_piece(base, mx, ldw2, dst, j);
     };
 
     // ---- fragments: lane reads row frow of a 32-row block, chunk 2s + hf of k-step s, i.e. position (hf ^ fx) ^ 2s ----
@@ -431,6 +432,21 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
             }
     };
 
+    // the eight MFMAs of a step with the four direct loads of one half-tile between them, one after every second MFMA: a burst of
+    // loads right after the barrier would hold up the MFMAs behind it while the loads queue
+    auto mma_dma = [&](const bf16x8 (&af)[4], const bf16x8 (&wf)[2], bool doit, const char *base, int mx, uint32_t pitch, bf16x8 *dst) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+#pragma unroll
+            for (int j = 0; j < 2; j++) {
+                if (KIND == EPI_VT) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
+                else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (doit) load_piece(base, mx, pitch, dst, i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
     // ---- FP8 main loop pieces.  One register set: operand i of A (rows i*32..) and j of W are 32 bytes per lane, the chunks
     // 2u and 2u+1 of k-step u (two per k-tile).  The MFMAs of a step run W-block-major, (0,0) (1,0) (2,0) (3,0) (0,1) .. (3,1);
     // as soon as the last MFMA that uses an operand has been issued its registers take the next step's data, so the twelve
@@ -455,13 +471,17 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
         LD8(W8[1], pw, u, 4096);
     };
 
-    // ---- prologue: A(0) W(0) A(1) W(1) A(2) into slots 0..4 (at least three k-tiles, so all belong to the first tile) ----
+    // ---- prologue: A(0) W(0) A(1) W(1) (and A(2) for the FP8 loop) into slots 0..4 (at least three k-tiles, so all belong to the first tile) ----
     issue_a(0, 0);
     issue_w(0, 1);
     issue_a(1, 2);
     issue_w(1, 3);
-    issue_a(2, 4);
-    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    if (F8) {
+        issue_a(2, 4);
+        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    } else {  // (the bf16 loop requests A(2) under its first MFMAs)
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    }
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     bf16x8 fa0[4], fw0[2], fa1[4], fw1[2];
@@ -546,7 +566,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
         for (int kt = 0; kt < KT; kt++) {
             const int sw = sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1;
             SB; read_frags(fa1, fw1, sa, sw, 1); wait_frags(fa0, fw0, false); SB;
-            mma(fa0, fw0); SB;
+            {   // A(g+2) into the slot W(g-1) left at the previous barrier
+                const int gk = kt + 2;
+                const bool cur = gk < KT;
+                mma_dma(fa0, fw0, true, cur ? baseA + gk * 128 : baseAn + (gk - KT) * 128, cur ? maxa : maxan, lda2,
+                        smem + (sa == 0 ? RING_SLOTS - 1 : sa - 1) * SLOT_CHUNKS + wave * 256);
+            }
+            SB;
             read_frags(fa0, fw0, sa, sw, 2); wait_frags(fa1, fw1, false); SB;
             mma(fa1, fw1); SB;
             read_frags(fa1, fw1, sa, sw, 3); wait_frags(fa0, fw0, false); SB;
@@ -569,11 +595,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                 const float *src = epi.bias + (c0 + 3 < N ? c0 : 0);
                 asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(bias4) : "v"(src) : "memory");
             }
-            if (kt + 1 < KT) {  // the two slots just released take W(g+2) and A(g+3); after a tile's last k-tile they first stage C
-                issue_w(kt + 2, sa);
-                issue_a(kt + 3, sw);
+            {   // the slot A(g) left takes W(g+2); after a tile's last k-tile the released slots first stage C
+                const int gk = kt + 2;
+                const bool cur = gk < KT;
+                SB;
+                mma_dma(fa1, fw1, kt + 1 < KT, cur ? baseW + gk * 128 : baseWn + (gk - KT) * 128, cur ? maxw : maxwn, ldw2,
+                        smem + sa * SLOT_CHUNKS + wave * 256);
+                SB;
             }
-            SB; mma(fa1, fw1); SB;
             if (kt + 1 < KT) sa = sa1;
         }
         // ---- epilogue: slots sa (waves 0..3) and sa+1 (waves 4..7) are free, 8 KB per wave ----
@@ -757,14 +786,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
         asm volatile("" ::: "memory");
         L += nslots;
         m0 = m0n; n0 = n0n; baseA = baseAn; baseW = baseWn;
-        offA = offAn; offW = offWn;
+        maxa = maxan; maxw = maxwn;
         has_next = L + nslots < xcd_end;
-        if (has_next) {
+        if (has_next) {  // (else the "next" sources stay on what is now the current tile)
             tile_coords(L + nslots, m0n, n0n);
-            tile_sources(m0n, n0n, baseAn, baseWn, offAn, offWn);
+            tile_sources(m0n, n0n, baseAn, baseWn, maxan, maxwn);
         }
         issue_w(1, sa);
-        issue_a(2, sw);
+        if (F8) issue_a(2, sw);
         sa = sa + 2 >= RING_SLOTS ? sa + 2 - RING_SLOTS : sa + 2;
         // A(0), W(0) of the new tile landed before its predecessor's last barrier
         if (F8) load_step8(sa, sa + 1 >= RING_SLOTS ? sa + 1 - RING_SLOTS : sa + 1, 0);
