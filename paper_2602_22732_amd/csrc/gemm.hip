@@ -277,7 +277,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_mfma(con
 // A0 W0 A1 W1 A2 ... item q lives in slot q % 5.  The bf16 loop requests A(g+2) under the first MFMAs of k-tile g (into
 // the slot W(g-1) left at the previous barrier) and W(g+2) under the MFMAs that follow the barrier ending k-tile g (into
 // the slot A(g) just left), one load after every second MFMA: a burst of eight loads per wave right after the barrier
-// holds up the MFMAs queued behind it.  (The FP8 loop still requests W(g+2) and A(g+3) together after the barrier.)
+// holds up the MFMAs queued behind it.  (The FP8 loop requests W(g+2) and A(g+3) under the four MFMAs after the barrier.)
 // The item stream runs on into the next tile of the workgroup, so a tile's first operands arrive while the previous
 // tile is still being multiplied and stored.
 // Per k-tile: four k-steps of 8 MFMAs; the fragments of step s+1 are read while step s multiplies.  Fragment
@@ -548,18 +548,21 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                     const float *src = epi.bias + (c0 + 3 < N ? c0 : 0);
                     asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(bias4) : "v"(src) : "memory");
                 }
-                if (more) {
-                    issue_w(kt + 2, sa);
-                    issue_a(kt + 3, sw);
-                }
+                // the two slots just released take W(g+2) and A(g+3), two loads after each MFMA (not in one burst, which would hold
+                // up the MFMAs queued behind it)
+                const int gw = kt + 2, ga = kt + 3;
+                const char *srcw = gw < KT ? baseW + gw * 128 : baseWn + (gw - KT) * 128;
+                const char *srca = ga < KT ? baseA + ga * 128 : baseAn + (ga - KT) * 128;
+                const int mxw = gw < KT ? maxw : maxwn, mxa = ga < KT ? maxa : maxan;
+                bf16x8 *dstw = smem + sa * SLOT_CHUNKS + wave * 256, *dsta = smem + sw * SLOT_CHUNKS + wave * 256;
                 SB; MMA8(0, 1); SB;
-                if (more) LD8(A8[0], pa1, 0, 0); SB;
+                if (more) { LD8(A8[0], pa1, 0, 0); load_piece(srcw, mxw, ldw2, dstw, 0); load_piece(srcw, mxw, ldw2, dstw, 1); } SB;
                 MMA8(1, 1); SB;
-                if (more) LD8(A8[1], pa1, 0, 4096); SB;
+                if (more) { LD8(A8[1], pa1, 0, 4096); load_piece(srcw, mxw, ldw2, dstw, 2); load_piece(srcw, mxw, ldw2, dstw, 3); } SB;
                 MMA8(2, 1); SB;
-                if (more) LD8(A8[2], pa1, 0, 8192); SB;
+                if (more) { LD8(A8[2], pa1, 0, 8192); load_piece(srca, mxa, lda2, dsta, 0); load_piece(srca, mxa, lda2, dsta, 1); } SB;
                 MMA8(3, 1); SB;
-                if (more) { LD8(A8[3], pa1, 0, 12288); LD8(W8[1], pw1, 0, 4096); } SB;
+                if (more) { LD8(A8[3], pa1, 0, 12288); LD8(W8[1], pw1, 0, 4096); load_piece(srca, mxa, lda2, dsta, 2); load_piece(srca, mxa, lda2, dsta, 3); } SB;
                 if (more) sa = sa1;
             }
         } else
