@@ -822,7 +822,7 @@ static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
         n_cu = prop.multiProcessorCount;
         attr_done = true;
     }
-    static double ticks_per_us = -1.0, stagger_scale = 1.0;
+    static double ticks_per_us = -1.0, stagger_scale = 0.0;  // (measured neutral: off unless asked for)
     if (ticks_per_us < 0) {
         int khz = 0, dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return GR4AD_EHIP;
