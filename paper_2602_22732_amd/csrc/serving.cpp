@@ -277,10 +277,23 @@ int gr4ad_cache_lookup(gr4ad_cache *c, uint64_t key, double now_s, int32_t *out_
 int gr4ad_cache_lookup_batch(gr4ad_cache *c, const uint64_t *keys, int32_t B, double now_s, uint8_t *hit, int32_t *miss_index, int32_t *n_miss) {
     if (!c || !keys || !hit || !miss_index || !n_miss || B < 1 || !(now_s == now_s)) return GR4AD_EINVAL;
     std::lock_guard<std::mutex> g(c->mu);
+    // users of this batch whose request is already on the list to decode: a small open-addressing set of indices into keys
+    int64_t cap = 16;
+    while (cap < 2 * (int64_t)B) cap <<= 1;
+    std::vector<int32_t> pending;
+    try {
+        pending.assign((size_t)cap, -1);
+    } catch (const std::bad_alloc &) {
+        return GR4AD_ENOMEM;
+    }
     int32_t m = 0;
     for (int32_t i = 0; i < B; i++) {
         bool dup = false;  // an earlier request of this batch is being decoded for the same user
-        for (int32_t j = 0; j < m && !dup; j++) dup = keys[miss_index[j]] == keys[i];
+        int64_t h = (int64_t)(mix(keys[i]) & (uint64_t)(cap - 1));
+        while (pending[h] >= 0 && !dup) {
+            dup = keys[pending[h]] == keys[i];
+            if (!dup) h = (h + 1) & (cap - 1);
+        }
         if (dup) {
             c->lookups++;
             c->hits++;
@@ -290,6 +303,7 @@ int gr4ad_cache_lookup_batch(gr4ad_cache *c, const uint64_t *keys, int32_t B, do
         } else {
             hit[i] = 0;
             miss_index[m++] = i;
+            pending[h] = i;  // h is the empty slot the probe ended on
         }
     }
     *n_miss = m;
