@@ -97,6 +97,8 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the batch size")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the decode call in a HIP graph once and time replays (no per-kernel events: implies --no-profile)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three device-to-device copies of 1 GiB before the warm-up (a kernel of known HBM traffic for counter runs)")
     args = ap.parse_args()
@@ -147,6 +149,21 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.graph:
+        args.no_profile = True
+        eager_step = step
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            eager_step()  # (the capture stream's own warm-up)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            eager_step()
+        step = graph.replay
+        step()
+        torch.cuda.synchronize()
     binding.profile_read(reset=True)
     binding.profile_enable(not args.no_profile)
     torch.cuda.synchronize()
@@ -203,7 +220,7 @@ def main():
         "dtype": "fp8" if w.fp8 else w.dtype, "data": "synthetic",
         "config": {"workload": "config %d %s: B=%d S=%d d=%d L=%d K=%d H=%d F=%d T=%d V=%s beam=%s ctx_len=%s" % (
             w.cfg_id, w.name, w.B, w.S, w.d, w.L, w.K, w.H, w.F, w.T, w.V[0], "/".join(map(str, w.beam)),
-            "all %d" % w.S if w.len_min is None else "U[%d,%d]" % (w.len_min, w.S)), "batch": w.B, "beam": list(w.beam)},
+            "all %d" % w.S if w.len_min is None else "U[%d,%d]" % (w.len_min, w.S)), "batch": w.B, "beam": list(w.beam), "hip_graph": bool(args.graph)},
         "candidates_per_s": req_s * w.beam[-1], "beam_rows_per_s": req_s * sum(w.rows),
         "algorithmic_tflop_per_step": total_flops / 1e12, "whole_path_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "whole_path_frac_of_bf16_mfma_peak": total_flops / (ms_per_step * 1e-3) / PEAK_BF16_MFMA,
