@@ -88,3 +88,18 @@ def test_config4_with_value_step_full_batch_sampled_request():
     assert val.shape == (w.B, w.beam[-1], 256) and np.isfinite(val).all() and (val <= 0).all()
     assert np.abs(np.exp(val[::97].astype(np.float64)).sum(axis=2) - 1).max() < 1e-4
     print("config 4 + value:", judge_decode(w, W, X, lens, sid, lp, tr, [511]), "max, mean value error", judge_value(w, W, X, lens, sid, lp, val, [511]))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_value_step_random_shapes_fp32(seed):
+    from test_gpu_decode import random_shape
+    shape = random_shape(100 + seed)
+    rng = np.random.default_rng(seed)
+    shape["Ve"] = int(rng.integers(2, 300))
+    w, W, X = tiny(dtype="f32", seed=77 + seed, **shape)
+    if seed % 2:
+        W["value_bias"] = rng.standard_normal(shape["Ve"]).astype(np.float32)
+    lens = synth.make_lengths(w, seed=seed)
+    sid, lp, tr, val = gpu_decode(w, W, X, lens, value=True)
+    judge_decode(w, W, X, lens, sid, lp, tr, range(w.B))
+    print(shape, "max, mean value error", judge_value(w, W, X, lens, sid, lp, val, range(w.B)))
