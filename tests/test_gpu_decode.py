@@ -172,3 +172,21 @@ def test_dynamic_beam_schedule_changes_per_call():
         trn = {k: [t.cpu().numpy() for t in v] for k, v in tr.items()}
         judge_decode(w, W, X, None, sid.cpu().numpy(), lp.cpu().numpy(), trn, range(w.B), beam=beam)
     dec.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_largest_codebook_and_beam_the_library_takes(dtype):
+    # GR4AD_MAX_CODEBOOK = 16384 codes per level and GR4AD_MAX_BEAM = 4096 beams, on a narrow model
+    w, W, X = tiny(dtype=dtype, gain_jitter=0.1, T=2, V=[16384, 16384], d=64, H=1, F=64, L=2, K=1, S=20, B=2, beam=[4096, 4096], len_min=4)
+    lens = synth.make_lengths(w, seed=2)
+    sid, lp, tr = gpu_decode(w, W, X, lens)
+    assert sid.shape == (2, 4096, 2) and sid.min() >= 0 and sid.max() < 16384 and (np.diff(lp, axis=1) <= 0).all()
+    for r in range(w.B):
+        assert len({tuple(p) for p in sid[r]}) == 4096
+    tol = TOY_BF16_TOL if dtype == "bf16" else None
+    print(judge_decode(w, W, X, lens, sid, lp, tr, [1], tol=tol, margin=None if tol is None else 2 * tol))
+    # one more than the limits is refused at init
+    for over in (dict(V=[16385, 8]), dict(beam=[4097, 8], max_beam=[4097, 8])):
+        w2, W2, _ = tiny(dtype=dtype, T=2, d=64, H=1, F=64, L=2, K=1, S=4, B=1, V=over.get("V", [8192, 8]), beam=over.get("beam", [4, 4]))
+        with pytest.raises(binding.Gr4adError):
+            binding.decoder_for(w2, W2, max_beam=over.get("max_beam"))

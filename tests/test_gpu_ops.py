@@ -63,7 +63,8 @@ def test_select_matches_oracle(B, n, V, k):
 
 
 @pytest.mark.parametrize("profile", ["steep", "flat", "first_row_worst", "first_row_minus_inf"])
-@pytest.mark.parametrize("B,n,V,k", [(2, 24, 8192, 1024), (1, 9, 5000, 600), (2, 6, 4096, 4096), (1, 300, 512, 200)])
+@pytest.mark.parametrize("B,n,V,k", [(2, 24, 8192, 1024), (1, 9, 5000, 600), (2, 6, 4096, 4096), (1, 300, 512, 200),
+                                     (1, 3, 16384, 4096), (2, 5, 16384, 700)])   # the last two: the largest codebook (and beam) the library takes
 def test_select_request_bound_regimes(profile, B, n, V, k):
     # The per-row cut is tightened by a bound taken from each request's first row: rows far below it contribute
     # nothing, rows level with it contribute about k each, and any row may be the first one.
