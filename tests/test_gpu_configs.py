@@ -55,7 +55,7 @@ def test_config4_large_bf16_full_batch_sampled_requests():
 @pytest.mark.parametrize("scale,batch,sample", [
     (0.25, 2048, [2047]),   # the full batch of 2048 at every schedule of the sweep; one sampled request each
     (0.5, 2048, [5]),
-    (1.0, 2048, [1095]),    # the workload bench.py times by default
+    (1.0, 2048, [0, 1095, 1800, 2047]),    # the workload bench.py times by default
     (1.0, 96, [95]),        # and a slice of the batch: same model, same per-request work, another batch composition
 ])
 def test_config5_load_adaptive_sweep_with_zipf_bias(scale, batch, sample):
