@@ -86,8 +86,8 @@ def cpu_baseline(w, W, lens, budget_requests):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest-batch one)")
     ap.add_argument("--scale", type=float, default=1.0, help="beam scale of configuration 5")
     ap.add_argument("--lazy", type=int, default=None, help="number of lazy layers K of the same model (default: the configuration's; 0 = plain autoregressive decoding)")
