@@ -190,6 +190,9 @@ def main():
         fl = rec["flops"]
         if name.startswith("cross_attn"):
             fl *= float(np.mean(lens)) / w.S  # the library counts the padded length; the method needs the valid keys only
+        if name == "gemm_bf16_ring":
+            # likewise the context key/value projections of the A autoregressive layers: counted on B*S rows, needed on the valid ones
+            fl -= args.steps * w.A * (w.B * w.S - float(np.sum(lens))) * 2.0 * (2 * w.d) * w.d
         if fl > 0 and name.startswith("gemm_fp8"):
             k.update(bound="mfma", achieved=fl / sec / 1e12, peak=PEAK_FP8_MFMA / 1e12, unit="TFLOP/s", frac=fl / sec / PEAK_FP8_MFMA,
                      flops_per_launch=fl / rec["launches"])

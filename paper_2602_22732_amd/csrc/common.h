@@ -56,6 +56,10 @@ struct GemmEpilogue {
     int64_t norm_ld;
     float *norm_ss;
     const float *row_inv;
+    // persistent kernel only (ignored elsewhere): the rows of A are requests of skip_S rows each of which only the first
+    // skip_len[b] are valid; output tiles whose rows all lie in one request's padding are not computed (their C is not written)
+    const int32_t *skip_len;
+    int skip_S;
     const float *a_scale;      // launch_gemm_f8 only (set by it): per-row scale of the FP8 A operand
     float w_scale;             // launch_gemm_f8 only (set by it): scale of the FP8 W operand
     const int32_t *batch_len;  // launch_gemm_batched only: valid length per batch (NULL = none)

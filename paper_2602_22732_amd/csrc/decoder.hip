@@ -536,7 +536,12 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     auto context_kv = [&](const LayerPacked &lw, void *kvbuf, void *vtbuf) -> int {
         const void *wv = (const char *)lw.wkv_x + (size_t)d * d * e;
         if (vtbuf && gemm_vt_supported(dt, ctx, d, wv, d, (int64_t)B * S, d, d, S, vtbuf, S)) {
-            int s = gemm(ctx, (int64_t)B * S, lw.wkv_x, d, d, plain_epilogue(kvbuf, 2 * d));
+            // (keys and values of rows past a request's length are never read: whole tiles of them are not computed)
+            GemmEpilogue ke = plain_epilogue(kvbuf, 2 * d);
+            const char *env = getenv("GR4AD_CTX_SKIP");
+            ke.skip_len = env && !strcmp(env, "0") ? nullptr : ctx_len;
+            ke.skip_S = S;
+            int s = gemm(ctx, (int64_t)B * S, lw.wkv_x, d, d, ke);
             if (s) return s;
             return launch_gemm_vt(ctx, d, wv, d, (int64_t)B * S, d, d, S, ctx_len, vtbuf, S, st);
         }

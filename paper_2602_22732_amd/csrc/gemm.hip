@@ -327,8 +327,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
     const int xcd = blockIdx.x % 8, wslot = blockIdx.x / 8;
     const int64_t per_xcd = (total + 7) / 8;
     const int64_t xcd_end = (xcd + 1) * per_xcd < total ? (xcd + 1) * per_xcd : total;
-    int64_t L = xcd * per_xcd + wslot;
-    if (L >= xcd_end) return;
     // All workgroups start together and every tile takes the same time, so without help they would all reach their
     // epilogues together: HBM idles while everybody multiplies and the matrix cores idle while everybody stores.
     // Workgroup slot i of an XCD therefore starts i/nslots of one tile time late (wall-clock ticks, a bounded wait).
@@ -348,6 +346,26 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
         m0 = (int64_t)(first_m + (in - nn * gm)) * 256;
         n0 = (int)nn * 256;
     };
+    // Rows of A beyond a request's valid length (epi.skip_len[b] of every skip_S rows) are padding nobody reads the product
+    // of: a tile whose 256 rows all lie in one request's padding is passed over.
+    auto tile_live = [&](int64_t l) -> bool {
+        if (!epi.skip_len) return true;
+        int64_t tm0;
+        int tn0;
+        tile_coords(l, tm0, tn0);
+        const uint32_t r0 = (uint32_t)tm0, rows_per = (uint32_t)epi.skip_S;
+        const uint32_t b0 = r0 / rows_per, b1 = (r0 + 255u) / rows_per;
+        if (b0 != b1) return true;  // straddles two requests
+        int len = epi.skip_len[b0];
+        len = len < 1 ? 1 : len;
+        return r0 - b0 * rows_per < (uint32_t)len;
+    };
+    auto next_live = [&](int64_t l) {
+        while (l < xcd_end && !tile_live(l)) l += nslots;
+        return l;
+    };
+    int64_t L = next_live(xcd * per_xcd + wslot);
+    if (L >= xcd_end) return;
 
     // ---- loads: load j of this wave fills rows (wave*4+j)*8 .. +7 of a half-tile, lane -> row lane/8, position lane%8.
     // The chunk that lives at position p of row r is p ^ ((r >> 1) & 7), and (r >> 1) & 7 = 4*(j&1) + (lane/8 >> 1).
@@ -360,8 +378,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
     int64_t m0, m0n = 0;
     int n0, n0n = 0;
     tile_coords(L, m0, n0);
-    bool has_next = L + nslots < xcd_end;
-    if (has_next) tile_coords(L + nslots, m0n, n0n);
+    int64_t Lnext = next_live(L + nslots);
+    bool has_next = Lnext < xcd_end;
+    if (has_next) tile_coords(Lnext, m0n, n0n);
     const char *baseA, *baseW, *baseAn, *baseWn;
     int maxa, maxw, maxan, maxwn;
     auto tile_sources = [&](int64_t tm0, int tn0, const char *&bA, const char *&bW, int &mA, int &mW) {
@@ -787,12 +806,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();  // every wave has read its staged rows back before the slots are overwritten
         asm volatile("" ::: "memory");
-        L += nslots;
+        L = Lnext;
         m0 = m0n; n0 = n0n; baseA = baseAn; baseW = baseWn;
         maxa = maxan; maxw = maxwn;
-        has_next = L + nslots < xcd_end;
+        Lnext = next_live(L + nslots);
+        has_next = Lnext < xcd_end;
         if (has_next) {  // (else the "next" sources stay on what is now the current tile)
-            tile_coords(L + nslots, m0n, n0n);
+            tile_coords(Lnext, m0n, n0n);
             tile_sources(m0n, n0n, baseAn, baseWn, maxan, maxwn);
         }
         issue_w(1, sa);
@@ -860,6 +880,7 @@ static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
 // at least three k-tiles, and row pitches whose byte offsets inside a 256-row block fit 32 bits.
 static bool ring_ok(int kind, int N, int K, int64_t lda, int64_t ldw, const GemmEpilogue &e) {
     const bool f32 = kind >= EPI_F32;
+    if (e.skip_len && e.skip_S < 1) return false;
     if (K < 192 || lda >= (1 << 22) || ldw >= (1 << 22)) return false;
     if (e.ldc % (f32 ? 4 : 8) || ((uintptr_t)e.C % 16)) return false;
     if (kind == EPI_F32 && e.bias && ((uintptr_t)e.bias % 16)) return false;
@@ -977,6 +998,13 @@ int launch_gemm_vt(const void *A, int64_t lda, const void *W, int64_t ldw, int64
     e.ldc = ld_out;
     e.ctx_len = ctx_len;
     e.vt_S = S;
+    static int skip = -1;
+    if (skip < 0) {
+        const char *env = getenv("GR4AD_CTX_SKIP");  // "0": compute the padded rows too (for comparison)
+        skip = !(env && !strcmp(env, "0"));
+    }
+    e.skip_len = skip ? ctx_len : nullptr;  // key tiles beyond ceil(len / 64) * 64 are never read by the attention kernel
+    e.skip_S = S;
     return launch_ring((const bf16 *)A, lda, (const bf16 *)W, ldw, M, N, K, EPI_VT, e, st);
 }
 
@@ -1042,6 +1070,7 @@ bool gemm_on_persistent_kernel(gr4ad_dtype dtype, const void *A, int64_t lda, co
           ((uintptr_t)W % 16) == 0))
         return false;
     const bool big = (M >= 8192 && N >= 256);
+    if (epi.skip_len && M > 0x7fffff00LL) return false;  // (the tile test works on 32-bit row numbers)
     return (mode == 5 || (mode == 0 && big)) && ring_ok(kind, N, K, lda, ldw, epi);
 }
 
@@ -1056,7 +1085,8 @@ int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, in
         ((uintptr_t)W % 16) == 0) {
         const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
         const bool big = (M >= 8192 && N >= 256);
-        if ((mode == 5 || (mode == 0 && big)) && ring_ok(kind, N, K, lda, ldw, epi)) return launch_ring(a, lda, w, ldw, M, N, K, kind, epi, st);
+        if ((mode == 5 || (mode == 0 && big)) && !(epi.skip_len && M > 0x7fffff00LL) && ring_ok(kind, N, K, lda, ldw, epi))
+            return launch_ring(a, lda, w, ldw, M, N, K, kind, epi, st);
         if (mode == 4) return launch_mfma<256, 256, 128, 128>(a, lda, w, ldw, M, N, K, kind, epi, st);
         if ((mode == 0 && big) || mode == 3) return launch_mfma<256, 256, 128, 64>(a, lda, w, ldw, M, N, K, kind, epi, st);
         return launch_mfma<128, 128, 64, 64>(a, lda, w, ldw, M, N, K, kind, epi, st);
