@@ -92,10 +92,10 @@ def test_linear_fp8_matches_exact_product(M, N, K, out_f32, bias):
 # RMS deviation of sqrt(|delta| * step) - for delta = 2^-9 and step = 2^-3.5 of the value that is 1.3 % of it, half of the
 # quantisation noise itself (step / sqrt(12) = 2.5 %).  So the GPU is held to the oracle's FP8 mode within a tolerance of the
 # size of the FP8 effect: on these toy models the oracle's FP8 and full-precision log-probabilities differ by up to 0.8 at a
-# level (mean 0.05 to 0.25), the GPU's cumulative scores were measured up to 0.30 from the FP8 oracle's and are held to 0.5.
+# level (mean 0.05 to 0.25), the GPU's cumulative scores were measured up to 0.49 from the FP8 oracle's and are held to 0.6.
 # A wrong scale, operand or weight shows as an error of the size of the logits themselves (a range of 4 to 6 here).  The
 # benchmark-shaped configuration below is held to its own, measured and much smaller, figure.
-TOY_FP8_TOL = 0.5
+TOY_FP8_TOL = 0.6
 
 
 @pytest.mark.parametrize("shape", [
