@@ -90,6 +90,11 @@ def test_random_shapes_match_oracle(dtype, seed):
         # separates rounding from a wrong operand or index (errors of the size of the logits, 4 to 6 here).
         sid, lp, tr = gpu_decode(w, W, X, lens)
         stats = judge_decode(w, W, X, lens, sid, lp, tr, range(w.B), tol=0.35, margin=0.7)
+    elif dtype == "bf16":
+        # cumulative scores add the levels' errors: the toy bound, set on three-level models, grows with the number of levels
+        tol = TOY_BF16_TOL * max(1.0, w.T / 3.0)
+        sid, lp, tr = gpu_decode(w, W, X, lens)
+        stats = judge_decode(w, W, X, lens, sid, lp, tr, range(w.B), tol=tol, margin=2 * tol)
     else:
         sid, lp, tr, stats = run_and_judge(w, W, X, lens)
     print(dtype, shape, stats)
