@@ -115,7 +115,7 @@ template <int DH, int QT, int NW, int SUBS>
 __global__ __launch_bounds__(NW * 64, (QT == 1 && SUBS == 1) ? 4 : 1) void cross_attn_flash_bf16(const bf16 *__restrict__ q, int64_t ldq, const bf16 *__restrict__ kv,
                                                                  const bf16 *__restrict__ vt, const int32_t *__restrict__ ctx_len,
                                                                  bf16 *__restrict__ out, int64_t ldo, int n, int S, int Spad, int d,
-                                                                 int H, float scale_log2e) {
+                                                                 int H, float scale_log2e, int beam_blocks, int64_t total_blocks) {
     constexpr int KCH = DH / 8;                   // 16-byte chunks per K row
     constexpr int K_CHUNKS = 64 * KCH, V_CHUNKS = DH * 8;
     constexpr int STAGE = K_CHUNKS + V_CHUNKS;    // one 64-key tile
@@ -124,13 +124,21 @@ __global__ __launch_bounds__(NW * 64, (QT == 1 && SUBS == 1) ? 4 : 1) void cross
     extern __shared__ bf16x8 smem[];              // 2 * MACRO chunks
     const int tid = threadIdx.x, lane = tid % 64;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
-    const int b = blockIdx.z, h = blockIdx.y;
+    // Workgroup ids are dealt to the 8 XCDs in turn, each with an L2 of its own.  The beam blocks of one (request, head) read the
+    // same keys and values, so they get consecutive slots of ONE XCD: XCD x owns the contiguous range [x*per, (x+1)*per) of the
+    // logical blocks (beam block fastest, then head, then request) and its blocks of one (request, head) start together.
+    const int64_t per_xcd = (total_blocks + 7) / 8;
+    const int64_t logical = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (logical >= total_blocks) return;
+    const int beam_block = (int)(logical % beam_blocks);
+    const int h = (int)((logical / beam_blocks) % H);
+    const int b = (int)(logical / ((int64_t)beam_blocks * H));
     const int frow = lane % 32, hf = lane / 32;
     int len = ctx_len ? ctx_len[b] : S;
     len = len < 1 ? 1 : (len > S ? S : len);
     const int ntiles = (len + 63) / 64;
     const int nmacro = (ntiles + SUBS - 1) / SUBS;
-    const int q0 = (blockIdx.x * NW + wave) * (QT * 32);
+    const int q0 = (beam_block * NW + wave) * (QT * 32);
 
     // query fragments stay in registers for the whole kernel
     bf16x8 qf[QT][KSTEPS];
@@ -400,11 +408,15 @@ static int launch_flash(const bf16 *q, int64_t ldq, const bf16 *kv, const bf16 *
         attr_done = true;
     }
     const int per_block = NW * QT * 32;
-    dim3 grid((n + per_block - 1) / per_block, H, B);
+    const int beam_blocks = (n + per_block - 1) / per_block;
+    const int64_t total_blocks = (int64_t)beam_blocks * H * B;
+    const int64_t grid = (total_blocks + 7) / 8 * 8;
+    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
     // flops on the padded length S; bytes: queries and outputs once, keys and values once per request (beam-shared)
     ProfScope ps(KC_XATTN_FLASH, st, 4.0 * B * (double)n * S * d, (2.0 * B * n * d + 2.0 * B * (double)S * d) * sizeof(bf16));
-    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), LDS_BYTES, st, q, ldq, kv, vt, ctx_len, out, ldo, n, S, (S + 63) / 64 * 64, d, H, scale_log2e);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), LDS_BYTES, st, q, ldq, kv, vt, ctx_len, out, ldo, n, S, (S + 63) / 64 * 64, d, H, scale_log2e,
+                       beam_blocks, total_blocks);
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }
@@ -415,7 +427,7 @@ int launch_cross_attention(gr4ad_dtype dtype, const void *q, int64_t ldq, const 
     const int dh = d / H;
     if (dh > 128) return GR4AD_EUNSUPPORTED;
     if (vt && cross_attention_workspace_bytes(dtype, B, S, d, H) && ldq % 8 == 0 && ldo % 4 == 0 && ((uintptr_t)q % 16) == 0 &&
-        ((uintptr_t)out % 8) == 0 && B <= 65535 && H <= 65535) {
+        ((uintptr_t)out % 8) == 0) {
         const bf16 *qq = (const bf16 *)q, *kk = (const bf16 *)kv, *vv = (const bf16 *)vt;
         bf16 *oo = (bf16 *)out;
         if (dh == 64) {

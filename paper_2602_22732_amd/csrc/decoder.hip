@@ -367,9 +367,8 @@ int gr4ad_decode_init(const gr4ad_model_desc *ds, const gr4ad_weights *w, gr4ad_
     {
         // The lazy layers attend with only T queries per request, so projecting every context row to keys and values
         // would dominate them.  Where the batched matrix-core kernel covers the shapes they use the absorbed form instead.
-        const char *env = getenv("GR4AD_LAZY_XATTN");  // "kv": always project keys and values (for comparison)
         const int dh = dec->d / dec->H;
-        dec->absorbed = dec->K > 0 && dec->dtype == GR4AD_BF16 && dh % 64 == 0 && !(env && !strcmp(env, "kv"));
+        dec->absorbed = dec->K > 0 && dec->dtype == GR4AD_BF16 && dh % 64 == 0;
     }
     for (int t = 0; t < dec->T; t++) { dec->V[t] = ds->codebook[t]; dec->max_beam[t] = ds->max_beam[t]; }
     if (dec->Ve > 0) dec->V[dec->T] = dec->Ve;
@@ -457,8 +456,6 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     const void *emitted = nullptr; // gain the last writer of x folded in (xn and ss are current for exactly that norm)
     auto fold_ok = [&](int64_t rows, int n_cls) -> bool {
         if (dt != GR4AD_BF16 || d % 256 || F % 64 || F < 256 || F % 8 || (n_cls && (n_cls < 256 || n_cls % 4))) return false;
-        const char *env = getenv("GR4AD_FOLD_NORM");
-        if (env && !strcmp(env, "0")) return false;
         GemmEpilogue g = plain_epilogue(trunk, d);  // representative writer: a d x d residual update
         g.resid = (const float *)trunk; g.ldr = d; g.out_f32 = 1;
         g.norm_gain = dec->ln_out; g.norm_out = xn; g.norm_ld = d; g.norm_ss = ss;
@@ -538,8 +535,7 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         if (vtbuf && gemm_vt_supported(dt, ctx, d, wv, d, (int64_t)B * S, d, d, S, vtbuf, S)) {
             // (keys and values of rows past a request's length are never read: whole tiles of them are not computed)
             GemmEpilogue ke = plain_epilogue(kvbuf, 2 * d);
-            const char *env = getenv("GR4AD_CTX_SKIP");
-            ke.skip_len = env && !strcmp(env, "0") ? nullptr : ctx_len;
+            ke.skip_len = ctx_len;
             ke.skip_S = S;
             int s = gemm(ctx, (int64_t)B * S, lw.wkv_x, d, d, ke);
             if (s) return s;

@@ -309,8 +309,7 @@ typedef int intx8 __attribute__((ext_vector_type(8)));
 
 template <int KIND, bool F8 = false>
 __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ W, int64_t ldw,
-                                                      int64_t M, int N, int K, int64_t tiles_m, int tiles_n, int group_m, GemmEpilogue epi,
-                                                      int stagger_ticks) {
+                                                      int64_t M, int N, int K, int64_t tiles_m, int tiles_n, int group_m, GemmEpilogue epi) {
     extern __shared__ bf16x8 smem[];
     const int tid = threadIdx.x, lane = tid % 64;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -327,14 +326,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
     const int xcd = blockIdx.x % 8, wslot = blockIdx.x / 8;
     const int64_t per_xcd = (total + 7) / 8;
     const int64_t xcd_end = (xcd + 1) * per_xcd < total ? (xcd + 1) * per_xcd : total;
-    // All workgroups start together and every tile takes the same time, so without help they would all reach their
-    // epilogues together: HBM idles while everybody multiplies and the matrix cores idle while everybody stores.
-    // Workgroup slot i of an XCD therefore starts i/nslots of one tile time late (wall-clock ticks, a bounded wait).
-    if (stagger_ticks > 0) {
-        const uint64_t t0 = wall_clock64();
-        const uint64_t wait = (uint64_t)stagger_ticks * (uint32_t)wslot / (uint32_t)nslots;
-        while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);
-    }
     const uint32_t gsz = (uint32_t)group_m * (uint32_t)tiles_n;
     auto tile_coords = [&](int64_t l64, int64_t &m0, int &n0) {  // fewer than 2^31 tiles: 32-bit division
         const uint32_t l = (uint32_t)l64;
@@ -842,14 +833,6 @@ static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
         n_cu = prop.multiProcessorCount;
         attr_done = true;
     }
-    static double ticks_per_us = -1.0, stagger_scale = 0.0;  // (measured neutral: off unless asked for)
-    if (ticks_per_us < 0) {
-        int khz = 0, dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return GR4AD_EHIP;
-        ticks_per_us = khz / 1000.0;
-        const char *env = getenv("GR4AD_GEMM_STAGGER");  // multiple of the estimated tile time the starts are spread over (0: off)
-        if (env) stagger_scale = atof(env);
-    }
     const int64_t tiles_m = ceil_div64(M, 256);
     const int tiles_n = (N + 255) / 256;
     const int64_t total = tiles_m * tiles_n;
@@ -862,15 +845,7 @@ static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
         const double operand_bytes = F8 ? ((double)M * K + (double)N * K) : 0.0;  // FP8 operands are half the bytes gemm_bytes counts
         ProfScope ps(F8 ? KC_GEMM_RING_F8 : KC_GEMM_RING, st, 2.0 * (double)M * N * K,
                      gemm_bytes(M, N, K, KIND >= EPI_F32 && KIND != EPI_VT, KIND == EPI_F32_RESID) - operand_bytes);
-        // tile time: about 1.7 us per k-tile of 64 in the main loop plus the epilogue; spreading the starts costs up to
-        // one tile time once, so it is only done when a workgroup has many tiles
-        int stagger = 0;
-        if (total >= 8 * grid && stagger_scale > 0) {
-            double us = (K / (F8 ? 128 : 64)) * 1.7 + 4.0;
-            if (us > 200.0) us = 200.0;
-            stagger = (int)(us * ticks_per_us * stagger_scale);
-        }
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), RING_LDS_BYTES, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, 4, epi, stagger);
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), RING_LDS_BYTES, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, 4, epi);
     }
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
@@ -998,12 +973,7 @@ int launch_gemm_vt(const void *A, int64_t lda, const void *W, int64_t ldw, int64
     e.ldc = ld_out;
     e.ctx_len = ctx_len;
     e.vt_S = S;
-    static int skip = -1;
-    if (skip < 0) {
-        const char *env = getenv("GR4AD_CTX_SKIP");  // "0": compute the padded rows too (for comparison)
-        skip = !(env && !strcmp(env, "0"));
-    }
-    e.skip_len = skip ? ctx_len : nullptr;  // key tiles beyond ceil(len / 64) * 64 are never read by the attention kernel
+    e.skip_len = ctx_len;  // key tiles beyond ceil(len / 64) * 64 are never read by the attention kernel
     e.skip_S = S;
     return launch_ring((const bf16 *)A, lda, (const bf16 *)W, ldw, M, N, K, EPI_VT, e, st);
 }
@@ -1019,8 +989,6 @@ static bool ring_f8_ok(int kind, int64_t M, int N, int K, int64_t lda, int64_t l
 }
 
 bool gemm_f8_on_persistent_kernel(const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K, const GemmEpilogue &epi) {
-    const char *env = getenv("GR4AD_GEMM_MODE");
-    if (env && atoi(env) == 1) return false;
     return ring_f8_ok(epilogue_kind(epi), M, N, K, lda, ldw, A, W, epi);
 }
 
@@ -1050,45 +1018,31 @@ int launch_gemm_f8(const void *A, int64_t lda, const float *a_scale, const void 
     return GR4AD_OK;
 }
 
-// 0 auto, 1 plain FMA kernel, 2 128x128 tiles, 3 256x256 tiles with 8 wavefronts, 4 256x256 tiles with 4 wavefronts,
-// 5 persistent 256x256 kernel
-static int g_gemm_mode = -1;
-static int gemm_mode() {
-    if (g_gemm_mode < 0) {
-        const char *e = getenv("GR4AD_GEMM_MODE");
-        g_gemm_mode = e ? atoi(e) : 0;
-    }
-    return g_gemm_mode;
+// Kernel choice by shape: bf16 products with 16-byte aligned, K-contiguous operands run on the matrix cores - the persistent
+// kernel from 8192 rows and 256 columns on (the 256x256 tile kernel where its epilogue does not cover the layout), 128x128
+// tiles below that - everything else on the plain kernel.
+static bool mfma_ok(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int K, int kind) {
+    return dtype == GR4AD_BF16 && kind >= 0 && K % 64 == 0 && lda % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)A % 16) == 0 && ((uintptr_t)W % 16) == 0;
 }
 
 bool gemm_on_persistent_kernel(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K,
                                const GemmEpilogue &epi) {
-    const int mode = gemm_mode();
     const int kind = epilogue_kind(epi);
-    if (M <= 0 || N <= 0 || K <= 0) return false;
-    if (!(dtype == GR4AD_BF16 && mode != 1 && kind >= 0 && K % 64 == 0 && lda % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)A % 16) == 0 &&
-          ((uintptr_t)W % 16) == 0))
-        return false;
-    const bool big = (M >= 8192 && N >= 256);
+    if (M <= 0 || N <= 0 || K <= 0 || !mfma_ok(dtype, A, lda, W, ldw, K, kind)) return false;
     if (epi.skip_len && M > 0x7fffff00LL) return false;  // (the tile test works on 32-bit row numbers)
-    return (mode == 5 || (mode == 0 && big)) && ring_ok(kind, N, K, lda, ldw, epi);
+    return M >= 8192 && N >= 256 && ring_ok(kind, N, K, lda, ldw, epi);
 }
 
 int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, int64_t ldw, int64_t M, int N, int K,
                 const GemmEpilogue &epi, hipStream_t st) {
     if (M <= 0 || N <= 0 || K <= 0) return GR4AD_EINVAL;
-    const int mode = gemm_mode();
     const int kind = epilogue_kind(epi);
     // only the persistent kernel folds the RMSNorm: never drop such a request silently
     if ((epi.norm_out || epi.row_inv) && !gemm_on_persistent_kernel(dtype, A, lda, W, ldw, M, N, K, epi)) return GR4AD_EUNSUPPORTED;
-    if (dtype == GR4AD_BF16 && mode != 1 && kind >= 0 && K % 64 == 0 && lda % 8 == 0 && ldw % 8 == 0 && ((uintptr_t)A % 16) == 0 &&
-        ((uintptr_t)W % 16) == 0) {
+    if (mfma_ok(dtype, A, lda, W, ldw, K, kind)) {
         const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
-        const bool big = (M >= 8192 && N >= 256);
-        if ((mode == 5 || (mode == 0 && big)) && !(epi.skip_len && M > 0x7fffff00LL) && ring_ok(kind, N, K, lda, ldw, epi))
-            return launch_ring(a, lda, w, ldw, M, N, K, kind, epi, st);
-        if (mode == 4) return launch_mfma<256, 256, 128, 128>(a, lda, w, ldw, M, N, K, kind, epi, st);
-        if ((mode == 0 && big) || mode == 3) return launch_mfma<256, 256, 128, 64>(a, lda, w, ldw, M, N, K, kind, epi, st);
+        if (gemm_on_persistent_kernel(dtype, A, lda, W, ldw, M, N, K, epi)) return launch_ring(a, lda, w, ldw, M, N, K, kind, epi, st);
+        if (M >= 8192 && N >= 256) return launch_mfma<256, 256, 128, 64>(a, lda, w, ldw, M, N, K, kind, epi, st);
         return launch_mfma<128, 128, 64, 64>(a, lda, w, ldw, M, N, K, kind, epi, st);
     }
     dim3 grid((unsigned)ceil_div64(M, 64), (unsigned)((N + 63) / 64));

@@ -23,8 +23,12 @@ ProfScope::ProfScope(int cls, hipStream_t st, double flops, double bytes) : idx_
     if (!g_pool.empty()) {
         r = g_pool.back();
         g_pool.pop_back();
-    } else if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) {
-        return;
+    } else {
+        if (hipEventCreate(&r.start) != hipSuccess) return;
+        if (hipEventCreate(&r.stop) != hipSuccess) {
+            (void)hipEventDestroy(r.start);
+            return;
+        }
     }
     r.cls = cls;
     r.flops = flops;

@@ -751,9 +751,6 @@ __global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned lo
 
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// 0: pick the kernel by shape; 1: always the workgroup-per-row kernel (GR4AD_SELECT_MODE, for comparisons)
-static int g_select_mode = getenv("GR4AD_SELECT_MODE") ? atoi(getenv("GR4AD_SELECT_MODE")) : 0;
-
 template <int VEC, bool FULL>
 static int launch_rows_wave_kind(unsigned grid, size_t lds, hipStream_t st, const float *logits, const float *cum, int64_t rows, int n,
                                  int V, int m, unsigned long long *cand, int64_t row_step, const unsigned long long *bound, int *req_count) {
@@ -820,10 +817,10 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
     unsigned long long *cand0 = (unsigned long long *)((char *)ws + sel_ws_cand(B, n, m));
     unsigned long long *bound = (unsigned long long *)((char *)cand0 + sel_ws_cand0(B, m));
     int *req_count = (int *)((char *)bound + align256((size_t)B * sizeof(unsigned long long)));
-    const bool wave_path = V <= 8192 && V % 4 == 0 && ((uintptr_t)logits % 16) == 0 && g_select_mode != 1;
+    const bool wave_path = V <= 8192 && V % 4 == 0 && ((uintptr_t)logits % 16) == 0;
     // Request-level bound (several rows per request, cut smaller than the row): the first row of a request holds its best
     // beam; the m-th best candidate of that row is a score no survivor of the request can lie below.
-    const bool bounded = wave_path && n > 1 && k <= V && g_select_mode != 2;
+    const bool bounded = wave_path && n > 1 && k <= V;
     {
         // algorithmic bytes: every logit once; the candidates written depend on the data (between k per request and m per row):
         // the lower bound is counted when the request-level bound is in use
