@@ -22,7 +22,7 @@ _LP = C.POINTER(C.c_int64)
 
 
 class _Desc(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("d", "H", "F", "L", "K", "T")] + [("V", _IP), ("eps", C.c_float), ("fp8", C.c_int32)]
+    _fields_ = [(n, C.c_int32) for n in ("d", "H", "F", "L", "K", "T")] + [("V", _IP), ("eps", C.c_float), ("fp8", C.c_int32), ("vanilla", C.c_int32)]
 
 
 class _Layer(C.Structure):
@@ -56,6 +56,7 @@ def _lib(precision):
         lib.orc_req_free.argtypes = [C.c_void_p]
         lib.orc_forward_seq.argtypes = [C.c_void_p, C.c_void_p, C.c_int, _IP, _DP, _DP]
         lib.orc_plain_ar_seq.argtypes = [C.c_void_p, C.c_void_p, C.c_int, _IP, _DP]
+        lib.orc_vanilla_ar_seq.argtypes = [C.c_void_p, C.c_void_p, C.c_int, _IP, _DP]
         lib.orc_decode_batch.restype = C.c_int
         lib.orc_decode_batch.argtypes = [C.c_void_p, _FP, _IP, C.c_int, C.c_int, _IP, _IP, _DP, _IP, _IP, _DP, C.c_int]
         lib.orc_prefix_dists.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, _IP, _DP, _DP]
@@ -96,7 +97,7 @@ MODE_CACHED, MODE_PLAIN, MODE_PLAIN_PRECUT = 0, 1, 2
 class Oracle:
     """One model (shapes + weights) loaded into the oracle."""
 
-    def __init__(self, d, H, F, L, K, T, V, weights, eps=1e-6, precision="f64", fp8=False):
+    def __init__(self, d, H, F, L, K, T, V, weights, eps=1e-6, precision="f64", fp8=False, vanilla=False):
         self.lib = _lib(precision)
         self.d, self.H, self.F, self.L, self.K, self.T, self.V, self.eps = d, H, F, L, K, T, list(V), eps
         keep = []  # keeps the float32 copies alive during orc_model_create
@@ -108,7 +109,7 @@ class Oracle:
 
         w = weights
         Varr = _i32(self.V)
-        desc = _Desc(d, H, F, L, K, T, _p(Varr, _IP), eps, int(bool(fp8)))
+        desc = _Desc(d, H, F, L, K, T, _p(Varr, _IP), eps, int(bool(fp8)), int(bool(vanilla)))
         emb = (_FP * max(T - 1, 1))(*[fp(e) for e in w["emb"]]) if T > 1 else (_FP * 1)()
         cls = (_FP * T)(*[fp(c) for c in w["cls"]])
         cb = w.get("cls_bias")
@@ -116,7 +117,8 @@ class Oracle:
         if cb is not None:
             bias = (_FP * T)(*[(fp(b) if b is not None else _FP()) for b in cb])
         layers = (_Layer * L)(*[_Layer(*[fp(lw[n]) for n in _LAYER_FIELDS]) for lw in w["layers"]])
-        ws = _Weights(fp(w["pos"]), fp(w["bos"]), emb, fp(w["w_g"]), fp(w["w_f"]), layers, fp(w["ln_out"]), cls,
+        ws = _Weights(fp(w["pos"]), fp(w["bos"]), emb, None if vanilla else fp(w["w_g"]), None if vanilla else fp(w["w_f"]), layers,
+                      fp(w["ln_out"]), cls,
                       bias if bias is not None else C.POINTER(_FP)())
         self.h = self.lib.orc_model_create(C.byref(desc), C.byref(ws))
         if not self.h:
@@ -191,6 +193,15 @@ class _Request:
         t = len(tokens) + 1
         last = np.zeros(o.V[t - 1])
         self.lib.orc_plain_ar_seq(o.h, self.h, t, _p(tokens, _IP), _p(last, _DP))
+        return last
+
+    def vanilla_ar_seq(self, tokens):
+        """Level-t distribution of the separately written vanilla decoder (input s_{t-1} + p_t, L layers)."""
+        o = self.orc
+        tokens = _i32(tokens)
+        t = len(tokens) + 1
+        last = np.zeros(o.V[t - 1])
+        self.lib.orc_vanilla_ar_seq(o.h, self.h, t, _p(tokens, _IP), _p(last, _DP))
         return last
 
     def prefix_dists(self, t, prefixes):

@@ -46,6 +46,12 @@
  * product is formed.  Products and sums are exact in `real`; everything else
  * (norms, attention, residuals, softmax, the lazy layers) is unchanged.
  *
+ * Vanilla input (orc_desc.vanilla != 0; section 3.2, "Vanilla Autoregressive
+ * Decoding"): the decoder the paper compares LazyAR against.  The input state of
+ * level t is h^(0)_t = s_{t-1} + p_t (embedding of the previous token plus the
+ * position embedding), every one of the L layers runs autoregressively (K must
+ * be 0) and Fuse does not exist (w_g, w_f are ignored and may be NULL).
+ *
  * Parity with the authors' trained model: parity unpinned (no weights exist).
  */
 #include <math.h>
@@ -79,6 +85,7 @@ typedef struct {
     const int32_t *V; /* [T] codebook size per level */
     float eps;
     int32_t fp8;      /* != 0: FP8 mode (see the header comment) */
+    int32_t vanilla;  /* != 0: vanilla autoregressive input h^(0)_t = s_{t-1} + p_t, K must be 0 (see the header comment) */
 } orc_desc;
 
 typedef struct {
@@ -107,7 +114,7 @@ typedef struct orc_model {
     int d, H, F, L, K, T;
     int V[ORC_MAX_LEVELS];
     real eps;
-    int fp8;
+    int fp8, vanilla;
     real *pos, *bos, *emb[ORC_MAX_LEVELS], *w_g, *w_f, *ln_out, *cls[ORC_MAX_LEVELS], *cls_bias[ORC_MAX_LEVELS];
     layer_r *layers;
 } orc_model;
@@ -258,6 +265,13 @@ static void fuse(real *out, const real *m, const real *s, const real *w_g, const
     free(cat);
 }
 
+/* Input state of the first autoregressive layer at one position: Fuse(m, s) with m the trunk output of that position
+ * (eq. fuse), or, for the vanilla decoder, s + p with p the position embedding (then m IS p: no lazy layer ran). */
+static void input_state(const orc_model *md, real *out, const real *m, const real *s) {
+    if (md->vanilla) { for (int i = 0; i < md->d; i++) out[i] = s[i] + m[i]; return; }
+    fuse(out, m, s, md->w_g, md->w_f, md->d, md->fp8);
+}
+
 /* One decoder layer over a sequence x [n,d] of decoder states (in place):
  * cross-attention over the context, causal self-attention over the n states,
  * feed-forward; each sub-layer is pre-normed and residual. */
@@ -315,16 +329,20 @@ static const real *prev_embedding(const orc_model *m, int t, const int32_t *toke
 /* ------------------------------------------------------------------ */
 orc_model *orc_model_create(const orc_desc *ds, const orc_weights *w) {
     if (!ds || !w || ds->T < 1 || ds->T > ORC_MAX_LEVELS || ds->K < 0 || ds->K >= ds->L || ds->d % ds->H) return NULL;
+    if (ds->vanilla && ds->K != 0) return NULL; /* the vanilla decoder has no lazy layer */
     orc_model *m = (orc_model *)calloc(1, sizeof(orc_model));
     m->d = ds->d; m->H = ds->H; m->F = ds->F; m->L = ds->L; m->K = ds->K; m->T = ds->T; m->eps = (real)ds->eps;
     m->fp8 = ds->fp8 != 0;
+    m->vanilla = ds->vanilla != 0;
     size_t d = ds->d, F = ds->F;
     for (int t = 0; t < m->T; t++) m->V[t] = ds->V[t];
     m->pos = rcopy_f(w->pos, m->T * d);
     m->bos = rcopy_f(w->bos, d);
     for (int t = 0; t + 1 < m->T; t++) m->emb[t] = rcopy_f(w->emb[t], (size_t)m->V[t] * d);
-    m->w_g = rcopy_f(w->w_g, d * d);
-    m->w_f = rcopy_f(w->w_f, d * 2 * d);
+    if (!m->vanilla) {
+        m->w_g = rcopy_f(w->w_g, d * d);
+        m->w_f = rcopy_f(w->w_f, d * 2 * d);
+    }
     m->ln_out = rcopy_f(w->ln_out, d);
     for (int t = 0; t < m->T; t++) {
         m->cls[t] = rcopy_f(w->cls[t], (size_t)m->V[t] * d);
@@ -351,12 +369,13 @@ orc_model *orc_model_create(const orc_desc *ds, const orc_weights *w) {
             quant_matrix(&r->w1, &dF, 1); quant_matrix(&r->w2, &dF, 1);
         }
         for (int t = 0; t < m->T; t++) { const size_t n = (size_t)m->V[t] * d; quant_matrix(&m->cls[t], &n, 1); }
-        /* W_f[:, :d]: the first d entries of each of its d rows */
-        real *half = ralloc(dd);
-        for (size_t o = 0; o < d; o++) memcpy(half + o * d, m->w_f + o * 2 * d, d * sizeof(real));
-        quant_matrix(&half, &dd, 1);
-        for (size_t o = 0; o < d; o++) memcpy(m->w_f + o * 2 * d, half + o * d, d * sizeof(real));
-        free(half);
+        if (!m->vanilla) { /* W_f[:, :d]: the first d entries of each of its d rows */
+            real *half = ralloc(dd);
+            for (size_t o = 0; o < d; o++) memcpy(half + o * d, m->w_f + o * 2 * d, d * sizeof(real));
+            quant_matrix(&half, &dd, 1);
+            for (size_t o = 0; o < d; o++) memcpy(m->w_f + o * 2 * d, half + o * d, d * sizeof(real));
+            free(half);
+        }
     }
     return m;
 }
@@ -411,9 +430,9 @@ void orc_forward_seq(const orc_model *m, const orc_req *rq, int t, const int32_t
     /* trunk (eq. trunk): m^(0)_tau = p_tau, K lazy layers, no token enters */
     memcpy(x, m->pos, sizeof(real) * (size_t)t * d);
     for (int l = 0; l < m->K; l++) layer_seq(m, l, x, t, rq->Kc[l], rq->Vc[l], rq->len);
-    /* late injection (eq. fuse) */
+    /* late injection (eq. fuse); the vanilla decoder adds the token embedding to the position embedding instead */
     real *h = ralloc((size_t)t * d);
-    for (int p = 0; p < t; p++) fuse(h + (size_t)p * d, x + (size_t)p * d, prev_embedding(m, p, tokens), m->w_g, m->w_f, d, m->fp8);
+    for (int p = 0; p < t; p++) input_state(m, h + (size_t)p * d, x + (size_t)p * d, prev_embedding(m, p, tokens));
     /* autoregressive head (eq. head) */
     for (int l = m->K; l < m->L; l++) layer_seq(m, l, h, t, rq->Kc[l], rq->Vc[l], rq->len);
     size_t off = 0;
@@ -436,6 +455,23 @@ void orc_plain_ar_seq(const orc_model *m, const orc_req *rq, int t, const int32_
     int d = m->d;
     real *h = ralloc((size_t)t * d);
     for (int p = 0; p < t; p++) fuse(h + (size_t)p * d, m->pos + (size_t)p * d, prev_embedding(m, p, tokens), m->w_g, m->w_f, d, m->fp8);
+    for (int l = 0; l < m->L; l++) layer_seq(m, l, h, t, rq->Kc[l], rq->Vc[l], rq->len);
+    real *lp = ralloc(m->V[t - 1]);
+    classify(m, t - 1, h + (size_t)(t - 1) * d, lp);
+    for (int v = 0; v < m->V[t - 1]; v++) lp_last[v] = (double)lp[v];
+    free(lp); free(h);
+}
+
+/* The vanilla autoregressive decoder (section 3.2, "Vanilla Autoregressive Decoding"), written on its own: the state that
+ * enters the first layer at step tau is s_{tau-1} + p_tau, all L layers are ordinary decoder layers over the tau states,
+ * the level's classifier follows.  A model created with vanilla != 0 must reproduce it through orc_forward_seq. */
+void orc_vanilla_ar_seq(const orc_model *m, const orc_req *rq, int t, const int32_t *tokens, double *lp_last) {
+    int d = m->d;
+    real *h = ralloc((size_t)t * d);
+    for (int p = 0; p < t; p++) {
+        const real *s = prev_embedding(m, p, tokens);
+        for (int i = 0; i < d; i++) h[(size_t)p * d + i] = s[i] + m->pos[(size_t)p * d + i];
+    }
     for (int l = 0; l < m->L; l++) layer_seq(m, l, h, t, rq->Kc[l], rq->Vc[l], rq->len);
     real *lp = ralloc(m->V[t - 1]);
     classify(m, t - 1, h + (size_t)(t - 1) * d, lp);
@@ -587,7 +623,7 @@ int orc_decode_cached(const orc_model *m, const orc_req *rq, const int32_t *beam
 #pragma omp parallel for schedule(dynamic) if (!omp_in_parallel() && n >= 4)
         for (int i = 0; i < n; i++) {
             real *h = ralloc(d), *lp = ralloc(V);
-            fuse(h, trunk + (size_t)t * d, prev_embedding(m, t, paths + (size_t)i * T), m->w_g, m->w_f, d, m->fp8);
+            input_state(m, h, trunk + (size_t)t * d, prev_embedding(m, t, paths + (size_t)i * T));
             for (int a = 0; a < A; a++) {
                 int l = m->K + a;
                 layer_step(m, l, h, t, rq->Kc[l], rq->Vc[l], rq->len, sK + i * kvsz + (size_t)a * T * d, sV + i * kvsz + (size_t)a * T * d);

@@ -36,6 +36,7 @@ class Workload:
     cfg_id: int = 0
     fp8: bool = False  # low-precision inference (appendix A.2): FP8 operands for the per-beam-row products
     Ve: int = 0  # eCPM-token step (section 3.3): number of value buckets, 0 = the model has no such step
+    vanilla: bool = False  # vanilla autoregressive decoder (section 3.2): input s_{t-1} + p_t, no Fuse, K = 0
     extra: dict = field(default_factory=dict)
 
     @property
@@ -50,6 +51,8 @@ class Workload:
         kw = dict(d=self.d, H=self.H, F=self.F, L=self.L, K=self.K, T=self.T, V=list(self.V), eps=self.eps)
         if self.fp8:
             kw["fp8"] = True
+        if self.vanilla:
+            kw["vanilla"] = True
         return kw
 
 
@@ -58,10 +61,12 @@ def scale_beams(beam, factor):
     return [max(1, int(round(b * factor))) for b in beam]
 
 
-def workload(cfg, scale=1.0, batch=None, lazy=None, value=None, fp8=False):
+def workload(cfg, scale=1.0, batch=None, lazy=None, value=None, fp8=False, vanilla=False):
     """The five benchmark configurations (1-based).  lazy: another number of lazy layers K for the same
     model (0 = every layer autoregressive, section 3.2's comparison of LazyAR with plain decoding).
-    value: number of eCPM buckets of a value step appended to the model (section 3.3); None or 0 = none."""
+    value: number of eCPM buckets of a value step appended to the model (section 3.3); None or 0 = none.
+    vanilla: the vanilla autoregressive decoder of section 3.2 on the same weights (input s_{t-1} + p_t instead of Fuse,
+    every layer autoregressive: implies lazy = 0)."""
     if cfg == 1:
         w = Workload("tiny-f32", "f32", 4, 64, 128, 2, 1, 4, 512, 3, [256] * 3, [16] * 3)
     elif cfg == 2:
@@ -79,6 +84,12 @@ def workload(cfg, scale=1.0, batch=None, lazy=None, value=None, fp8=False):
     w.cfg_id = cfg
     if batch is not None:
         w.B = batch
+    if vanilla:
+        if lazy not in (None, 0):
+            raise ValueError("the vanilla decoder has no lazy layer")
+        lazy = 0
+        w.vanilla = True
+        w.name += "-vanilla"
     if lazy is not None:
         if not 0 <= lazy < w.L:
             raise ValueError("lazy must be in [0, L)")

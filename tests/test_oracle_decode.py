@@ -234,6 +234,53 @@ def test_forward_seq_matches_library_composition():
         np.testing.assert_allclose(got[t], F.log_softmax(z, dim=0).numpy(), atol=1e-12)
 
 
+def test_vanilla_decoder_matches_library_composition_and_its_second_form():
+    """Section 3.2, "Vanilla Autoregressive Decoding": h^(0)_t = s_{t-1} + p_t through L decoder layers, then the level's
+    classifier - wired from PyTorch library routines; the model flag and the separately written function must both give it."""
+    import torch
+    import torch.nn.functional as F
+    from test_oracle_primitives import _torch_layer
+    w, W, X, o = make(V=[5, 6, 4, 7], T=4, L=3, K=0, d=24, H=3, F=40, S=6, B=1, vanilla=True)
+    length, toks = 5, [3, 1, 2]
+    ctx = X[0][:length]
+    s = np.stack([W["bos"]] + [W["emb"][t][toks[t]] for t in range(3)]).astype(np.float64)
+    h = s + W["pos"].astype(np.float64)
+    for l in range(w.L):
+        h = _torch_layer(W["layers"][l], h, ctx, w.H, w.eps, w.d)
+    rq = o.request(X[0], length)
+    got = rq.forward_seq(toks)
+    for t in range(w.T):
+        z = F.linear(F.rms_norm(torch.tensor(h[t]), (w.d,), torch.tensor(W["ln_out"].astype(np.float64)), eps=w.eps),
+                     torch.tensor(W["cls"][t].astype(np.float64)))
+        want = F.log_softmax(z, dim=0).numpy()
+        np.testing.assert_allclose(got[t], want, atol=1e-12)
+        np.testing.assert_allclose(rq.vanilla_ar_seq(toks[:t]), want, atol=1e-12)
+    # it is not the K = 0 LazyAR decoder (whose input is Fuse(p_t, s_{t-1})) ...
+    o_fuse = oracle.Oracle(weights=W, **{**w.model_kwargs(), "vanilla": False})
+    assert np.abs(o_fuse.request(X[0], length).forward_seq(toks)[-1] - got[-1]).max() > 1e-3
+    # ... Fuse weights are never read, and lazy layers are refused
+    W2 = dict(W)
+    W2["w_g"], W2["w_f"] = W["w_g"] * 0 + 7, W["w_f"] * 0 - 3
+    np.testing.assert_array_equal(oracle.Oracle(weights=W2, **w.model_kwargs()).request(X[0], length).forward_seq(toks)[-1], got[-1])
+    with pytest.raises(ValueError):
+        oracle.Oracle(weights=W, **{**w.model_kwargs(), "K": 1})
+
+
+@pytest.mark.parametrize("mode", [MODE_CACHED, MODE_PLAIN])
+def test_vanilla_decoder_search_equals_brute_force(mode):
+    V = [3, 4, 5]
+    w, W, X, o = make(V=V, T=3, beam=[3, 12, 60], B=2, L=2, K=0, vanilla=True)
+    sid, lp, _ = o.decode_batch(X, None, w.beam, mode)
+    for r in range(w.B):
+        rq = o.request(X[r])
+        paths = all_paths(V)
+        s = np.array([sum(rq.vanilla_ar_seq(p[:t])[p[t]] for t in range(3)) for p in paths])
+        assert abs(np.exp(s).sum() - 1.0) < 1e-12
+        order = np.argsort(-s, kind="stable")
+        assert np.array_equal(sid[r], paths[order])
+        np.testing.assert_allclose(lp[r], s[order], atol=1e-12)
+
+
 def test_config1_matches_stored_oracle_output():
     import json, os
     with open(os.path.join(os.path.dirname(__file__), "golden", "cfg1_oracle.json")) as f:
