@@ -37,7 +37,7 @@ def algorithmic_flops(w, lens):
     per_req = {
         "ctx_kv": A * 4.0 * lens.mean() * d * d,
         "lazy": T * K * (12.0 * d * d + 4.0 * d * F + 4.0 * lens.mean() * d),
-        "fuse": R * 2.0 * d * d,
+        "fuse": 0.0 if w.vanilla else R * 2.0 * d * d,
         "ar_gemm": R * A * (12.0 * d * d + 4.0 * d * F),
         "cross_attn": R * A * 4.0 * lens.mean() * d,
         "self_attn": sum(n * A * 4.0 * (t + 1) * d for t, n in enumerate(w.rows)),
@@ -46,7 +46,7 @@ def algorithmic_flops(w, lens):
     if w.Ve > 0:  # eCPM-token step: one more position of the lazy pass and one more level for the b_T returned beams
         n = float(w.beam[-1])
         per_req["lazy"] *= (T + 1.0) / T
-        per_req["fuse"] += n * 2.0 * d * d
+        per_req["fuse"] += 0.0 if w.vanilla else n * 2.0 * d * d
         per_req["ar_gemm"] += n * A * (12.0 * d * d + 4.0 * d * F)
         per_req["cross_attn"] += n * A * 4.0 * lens.mean() * d
         per_req["self_attn"] += n * A * 4.0 * (T + 1) * d
@@ -54,33 +54,55 @@ def algorithmic_flops(w, lens):
     return {k: v * w.B for k, v in per_req.items()}
 
 
+def kernel_sources_sha256():
+    """Hash of the library's kernel sources (csrc/*, sorted by name): names the code a counter summary was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2602_22732_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        h.update(name.encode())
+        h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()
+
+
 def measured_traffic(cfg_id):
     """HBM bytes per decode_batch call and kernel class, measured with rocprofv3 counters (FETCH_SIZE + WRITE_SIZE,
-    scaled by a copy kernel of known size), read from the committed summary of that run: {kernel: bytes} or {}."""
+    scaled by a copy kernel of known size), read from the committed summary of that run.  The counters cannot be read
+    inside this process, so the summary records the hash of the kernel sources it was measured on; figures of another
+    version of the kernels are not reported.  Returns ({kernel: bytes}, note)."""
     import re
-    path = os.path.join(ROOT, "profiles", "decode_batch_config%d_hbm_traffic.md" % cfg_id)
-    out = {}
-    if os.path.exists(path):
-        for line in open(path):
-            m = re.match(r"^\|\s*(\w+)\s*\|.*\|\s*([0-9.eE+]+)\s*\|\s*$", line)
-            if m:
-                out[m.group(1)] = float(m.group(2))
-    return out
+    name = "decode_batch_config%d_hbm_traffic.md" % cfg_id
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return {}, "no counter summary profiles/%s" % name
+    out, sha = {}, None
+    for line in open(path):
+        m = re.match(r"^\|\s*(\w+)\s*\|.*\|\s*([0-9.eE+]+)\s*\|\s*$", line)
+        if m:
+            out[m.group(1)] = float(m.group(2))
+        m = re.match(r"^kernel sources sha256:\s*([0-9a-f]{64})", line)
+        if m:
+            sha = m.group(1)
+    if sha != kernel_sources_sha256():
+        return {}, "profiles/%s was measured on other kernel sources (sha256 %s): not reported" % (name, sha and sha[:12])
+    return out, "rocprofv3 FETCH_SIZE/WRITE_SIZE run of this command, profiles/%s (kernel sources sha256 %s)" % (name, sha[:12])
 
 
-def cpu_baseline(w, W, lens, budget_requests):
-    """Times the CPU oracle (double-precision build, as used for parity) on a bounded sample."""
+def cpu_baseline(w, W, lens):
+    """Times the CPU oracle as it stands on a bounded sample of the same workload: one request per host thread (the oracle's
+    batch driver then runs one request per thread), float32 build (the precision the task states for the oracle; the parity
+    tests use the double build of the same source)."""
     import oracle
     from paper_2602_22732_amd import synth
-    n = min(w.B, budget_requests)
+    cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or len(os.sched_getaffinity(0))
+    n = min(w.B, max(cores, {1: 4, 2: 64, 3: 16}.get(w.cfg_id, 1)))
     X = synth.make_context(w, lens, requests=range(n))
-    o = oracle.Oracle(weights=W, **w.model_kwargs())
+    o = oracle.Oracle(weights=W, precision="f32", **w.model_kwargs())
     t0 = time.perf_counter()
     o.decode_batch(X, lens[:n], w.beam)
     dt = time.perf_counter() - t0
-    cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or len(os.sched_getaffinity(0))
     return {"value": n / dt, "unit": "requests/s", "cores": cores, "kind": "oracle",
-            "sample": "first %d of %d requests of the same workload, oracle decode (fp64 build, OpenMP), %.1f s" % (n, w.B, dt)}
+            "sample": "first %d of %d requests of the same workload, one request per thread, oracle decode (float32 build, OpenMP), %.1f s" % (n, w.B, dt)}
 
 
 def main():
@@ -91,6 +113,8 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest-batch one)")
     ap.add_argument("--scale", type=float, default=1.0, help="beam scale of configuration 5")
     ap.add_argument("--lazy", type=int, default=None, help="number of lazy layers K of the same model (default: the configuration's; 0 = plain autoregressive decoding)")
+    ap.add_argument("--vanilla", action="store_true",
+                    help="the vanilla autoregressive decoder of section 3.2 on the same weights (input s_{t-1} + p_t, no Fuse, every layer per beam and level)")
     ap.add_argument("--fp8", action="store_true", help="low-precision inference: FP8 (E4M3) operands for the per-beam-row products (default: bf16)")
     ap.add_argument("--value", type=int, default=0, help="append an eCPM-token step with this many value buckets to the model and run it in every call (default: none)")
     ap.add_argument("--beam", type=str, default=None, help="comma-separated beam widths per level instead of the configuration's (Dynamic Beam Width schedules)")
@@ -113,7 +137,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    w = synth.workload(args.config, scale=args.scale, batch=args.batch, lazy=args.lazy, value=args.value, fp8=args.fp8)
+    w = synth.workload(args.config, scale=args.scale, batch=args.batch, lazy=args.lazy, value=args.value, fp8=args.fp8, vanilla=args.vanilla)
     if args.beam:
         beam = [int(b) for b in args.beam.split(",")]
         if len(beam) != w.T or min(beam) < 1:
@@ -181,7 +205,8 @@ def main():
     total_flops = sum(flops.values())
 
     # per-kernel rooflines from the event-timed launches; the dominant kernel (most event time) goes into "roofline"
-    traffic = measured_traffic(w.cfg_id)
+    traffic, traffic_note = measured_traffic(w.cfg_id) if not (args.lazy is not None or args.fp8 or args.value or args.beam or args.batch or args.vanilla or args.scale != 1.0) \
+        else ({}, "counter summaries exist for the default command lines only")
     kernels = {}
     for name, rec in prof.items():
         sec = rec["ms"] * 1e-3
@@ -214,7 +239,7 @@ def main():
         k = kernels[dom]
         if "bound" in k:
             roofline = {"kernel": dom, "bound": k["bound"], "achieved": k["achieved"], "peak": k["peak"], "unit": k["unit"],
-                        "frac": k["frac"], "traffic": k["traffic"], "avg_launch_ms": k["avg_launch_ms"],
+                        "frac": k["frac"], "traffic": k["traffic"], "traffic_source": traffic_note, "avg_launch_ms": k["avg_launch_ms"],
                         "share_of_step": k["ms_per_step"] / ms_per_step}
 
     out = {
@@ -230,9 +255,8 @@ def main():
         "workspace_gib": ws_bytes / 2**30,
         "roofline": roofline, "kernels": kernels,
     }
-    if not args.no_cpu and w.Ve == 0 and not w.fp8:  # (the baseline is the oracle as it stands, in its default mode)  # the oracle's batch decode ends at the last SID level
-        budget = {1: 4, 2: 64, 3: 16, 4: 2, 5: 2}[w.cfg_id]
-        out["cpu_baseline"] = cpu_baseline(w, W, lens, budget)
+    if not args.no_cpu and w.Ve == 0 and not w.fp8 and not args.graph:  # (the baseline is the oracle as it stands, in its default mode)  # the oracle's batch decode ends at the last SID level
+        out["cpu_baseline"] = cpu_baseline(w, W, lens)
     print(json.dumps(out))
 
 

@@ -68,6 +68,10 @@ typedef struct {
                               * quantises those weights with one scale amax/448 per matrix (the three self-attention input
                               * projections count as one matrix), decode quantises every activation row with its own scale
                               * amax(row)/448.  Everything else (lazy layers, attention, norms, softmax, scores) is unchanged. */
+    int32_t vanilla_input;   /* != 0: the vanilla autoregressive decoder LazyAR is compared against (section 3.2, "Vanilla
+                              * Autoregressive Decoding"): the state entering the first layer at level t is s_{t-1} + p_t (embedding of
+                              * the previous token, BOS at t = 1, plus the position embedding), all L layers run per beam and level.
+                              * n_lazy must be 0; w_g_dev and w_f_dev are not read and may be NULL. */
 } gr4ad_model_desc;
 
 /* One decoder layer (section 3.2: cross-attention over X, self-attention over
@@ -107,7 +111,7 @@ typedef struct gr4ad_decoder gr4ad_decoder;
  * The caller may release its weight buffers afterwards.  On failure *out is
  * left untouched.  Uses the current HIP device; synchronises it once.
  * Errors: EINVAL (null pointer, d % H != 0, K outside [0,L), T outside
- * [1,8], non-positive sizes), EUNSUPPORTED (head width, beam or codebook
+ * [1,8], non-positive sizes, vanilla_input with K > 0), EUNSUPPORTED (head width, beam or codebook
  * beyond the limits above), ENOMEM, EHIP.
  */
 int gr4ad_decode_init(const gr4ad_model_desc *desc, const gr4ad_weights *weights, gr4ad_decoder **out);
@@ -239,9 +243,13 @@ int gr4ad_op_gather_rows(gr4ad_dtype dtype, const void *src_dev, const int32_t *
  * the stream the kernel is launched on.  gr4ad_profile_read waits for the
  * recorded events and sums, per kernel class c < gr4ad_profile_kernel_count():
  * elapsed milliseconds ms[c], algorithmic flops flops[c] (2*M*N*K per GEMM
- * launch; 4*n*S*d per request for cross-attention, i.e. counted on the padded
- * context length S), algorithmic HBM bytes bytes[c] (what the operation must
- * read and write once: operands, outputs) and the number of launches;
+ * launch; 4*n*S*d per request for cross-attention), algorithmic HBM bytes
+ * bytes[c] (what the operation must read and write once: operands, outputs;
+ * a table row shared by several beams once) and the number of launches.
+ * The valid context lengths live on the device, so launches that depend on
+ * them (cross-attention, the context key/value projections) are counted on
+ * the padded length S - an upper bound; a caller that knows the lengths
+ * rescales by mean(len)/S, as bench.py does.
  * reset != 0 forgets the records afterwards.  Not thread-safe.
  */
 int gr4ad_profile_enable(int on);

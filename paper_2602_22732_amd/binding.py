@@ -35,7 +35,7 @@ class ModelDesc(C.Structure):
     _fields_ = [("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ffn", C.c_int32), ("n_layers", C.c_int32),
                 ("n_lazy", C.c_int32), ("n_levels", C.c_int32), ("codebook", _IP), ("max_beam", _IP),
                 ("max_batch", C.c_int32), ("max_ctx", C.c_int32), ("dtype", C.c_int), ("rms_eps", C.c_float),
-                ("n_value_buckets", C.c_int32), ("fp8_gemm", C.c_int32)]
+                ("n_value_buckets", C.c_int32), ("fp8_gemm", C.c_int32), ("vanilla_input", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -200,13 +200,13 @@ def weights_to_device(weights, dtype, device="cuda"):
 class Decoder:
     """gr4ad_decode_init / gr4ad_decode_batch / gr4ad_decode_free."""
 
-    def __init__(self, d, H, F, L, K, T, V, dev_weights, dtype, max_beam, max_batch, max_ctx, eps=1e-6, Ve=0, fp8=False):
+    def __init__(self, d, H, F, L, K, T, V, dev_weights, dtype, max_beam, max_batch, max_ctx, eps=1e-6, Ve=0, fp8=False, vanilla=False):
         self.L_ = lib()
         self.handle = None
         self.T, self.V, self.d, self.dtype, self.Ve = T, list(V), d, dtype_code(dtype), int(Ve)
         V_arr, V_ptr = _i32arr(self.V)
         mb_arr, mb_ptr = _i32arr(max_beam)
-        desc = ModelDesc(d, H, F, L, K, T, V_ptr, mb_ptr, max_batch, max_ctx, self.dtype, eps, self.Ve, int(bool(fp8)))
+        desc = ModelDesc(d, H, F, L, K, T, V_ptr, mb_ptr, max_batch, max_ctx, self.dtype, eps, self.Ve, int(bool(fp8)), int(bool(vanilla)))
         w = dev_weights
         ptr = lambda t: C.c_void_p(t.data_ptr())
         emb = (_VP * max(T - 1, 1))(*[t.data_ptr() for t in w["emb"]])
@@ -215,7 +215,8 @@ class Decoder:
         if w.get("cls_bias") is not None:
             bias = (_VP * T)(*[(b.data_ptr() if b is not None else None) for b in w["cls_bias"]])
         layers = (LayerWeights * L)(*[LayerWeights(*[lw[n].data_ptr() for n in LAYER_FIELDS]) for lw in w["layers"]])
-        ws = Weights(ptr(w["pos"]), ptr(w["bos"]), emb, ptr(w["w_g"]), ptr(w["w_f"]), layers, ptr(w["ln_out"]), cls,
+        ws = Weights(ptr(w["pos"]), ptr(w["bos"]), emb, None if vanilla else ptr(w["w_g"]), None if vanilla else ptr(w["w_f"]), layers,
+                     ptr(w["ln_out"]), cls,
                      bias if bias is not None else C.POINTER(_VP)(),
                      *[(w[k].data_ptr() if w.get(k) is not None else None) for k in ("value_pos", "value_emb", "value_cls", "value_bias")])
         h = _VP()
@@ -287,7 +288,7 @@ def decoder_for(workload, weights, max_beam=None, device="cuda"):
     """Decoder for a synth.Workload and its numpy weight dict."""
     w = workload
     dev_w = weights_to_device(weights, w.dtype, device)
-    dec = Decoder(w.d, w.H, w.F, w.L, w.K, w.T, w.V, dev_w, w.dtype, max_beam or list(w.beam), w.B, w.S, eps=w.eps, Ve=w.Ve, fp8=w.fp8)
+    dec = Decoder(w.d, w.H, w.F, w.L, w.K, w.T, w.V, dev_w, w.dtype, max_beam or list(w.beam), w.B, w.S, eps=w.eps, Ve=w.Ve, fp8=w.fp8, vanilla=w.vanilla)
     dec._keep = dev_w  # init copies the weights; kept only so callers may inspect them
     return dec
 

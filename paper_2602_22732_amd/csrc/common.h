@@ -93,9 +93,11 @@ int launch_gemm_vt(const void *A, int64_t lda, const void *W, int64_t ldw, int64
 int launch_rmsnorm(gr4ad_dtype dtype, const void *x, const void *g, void *y, int64_t rows, int d, float eps, hipStream_t st);
 // inv[r] = 1 / sqrt(sum(ss[r*parts .. r*parts+parts-1]) / dim + eps): per-row factor of the folded RMSNorm from the partial sums
 int launch_row_inv(const float *ss, float *inv, int64_t rows, int parts, int dim, float eps, hipStream_t st);
-// a[(b*n+i), :] = m[b*m_stride + :] * G[tok(b,i), :]   (tok == NULL: row 0 of G); m float32, G and a storage dtype
-int launch_fuse_gate(gr4ad_dtype dtype, const void *m, int64_t m_req_stride, const void *G, const int32_t *tok, void *a, int B, int n,
-                     int d, hipStream_t st);
+// a[(b*n+i), :] = m[b*m_stride + :] * G[tok(b,i), :]   (tok == NULL: row 0 of G); m and G float32 (G: table_rows rows), a storage dtype
+int launch_fuse_gate(gr4ad_dtype dtype, const void *m, int64_t m_req_stride, const void *G, int64_t table_rows, const int32_t *tok, void *a,
+                     int B, int n, int d, hipStream_t st);
+// h[row, :] = E[tok[row], :] + p[:]   (tok == NULL: row 0 of E); E and p storage dtype, h float32: the vanilla decoder's input state
+int launch_embed_pos(gr4ad_dtype dtype, const void *E, const int32_t *tok, const void *p, void *h, int64_t rows, int d, hipStream_t st);
 // dst[b*T + t, :] = pos[t, :]   (pos storage dtype, dst float32)
 int launch_broadcast_rows(gr4ad_dtype dtype, const void *pos, void *dst, int B, int T, int d, hipStream_t st);
 // dst[b, j, 0:row_elems] = src[b, parent[b,j], 0:row_elems]

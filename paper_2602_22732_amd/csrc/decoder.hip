@@ -39,6 +39,8 @@ struct gr4ad_decoder {
     int device;
     void *pos, *ln_out, *wf1;
     void *G[GR4AD_MAX_LEVELS], *P[GR4AD_MAX_LEVELS];  // per-level Fuse tables: W_g s and W_f[:,d:] s of the previous token
+    bool vanilla;                 // vanilla autoregressive decoder: input state s_{t-1} + p_t, no Fuse, no lazy layer
+    void *E[GR4AD_MAX_LEVELS];    // vanilla only: per-level embedding table of the previous token (one BOS row at level 1)
     void *cls[GR4AD_MAX_LEVELS];
     float *cls_bias[GR4AD_MAX_LEVELS];
     std::vector<LayerPacked> layers;
@@ -208,6 +210,7 @@ int validate_desc(const gr4ad_model_desc *ds) {
         return fail(nullptr, GR4AD_EINVAL, "sizes must be positive");
     if (ds->d_model % ds->n_heads) return fail(nullptr, GR4AD_EINVAL, "d_model %d not divisible by n_heads %d", ds->d_model, ds->n_heads);
     if (ds->n_lazy < 0 || ds->n_lazy >= ds->n_layers) return fail(nullptr, GR4AD_EINVAL, "n_lazy %d outside [0, n_layers=%d)", ds->n_lazy, ds->n_layers);
+    if (ds->vanilla_input && ds->n_lazy != 0) return fail(nullptr, GR4AD_EINVAL, "vanilla_input needs n_lazy = 0 (got %d)", ds->n_lazy);
     if (ds->n_levels < 1 || ds->n_levels > GR4AD_MAX_LEVELS) return fail(nullptr, GR4AD_EINVAL, "n_levels %d outside [1,%d]", ds->n_levels, GR4AD_MAX_LEVELS);
     if (ds->dtype != GR4AD_F32 && ds->dtype != GR4AD_BF16) return fail(nullptr, GR4AD_EINVAL, "unknown dtype %d", (int)ds->dtype);
     if (!(ds->rms_eps >= 0.0f)) return fail(nullptr, GR4AD_EINVAL, "rms_eps must be >= 0");
@@ -229,8 +232,8 @@ int validate_desc(const gr4ad_model_desc *ds) {
 
 int validate_weights(const gr4ad_model_desc *ds, const gr4ad_weights *w) {
     if (!w) return fail(nullptr, GR4AD_EINVAL, "weights is NULL");
-    if (!w->pos_dev || !w->bos_dev || !w->w_g_dev || !w->w_f_dev || !w->layers || !w->ln_out_dev || !w->cls_dev)
-        return fail(nullptr, GR4AD_EINVAL, "a weight pointer is NULL");
+    if (!w->pos_dev || !w->bos_dev || !w->layers || !w->ln_out_dev || !w->cls_dev) return fail(nullptr, GR4AD_EINVAL, "a weight pointer is NULL");
+    if (!ds->vanilla_input && (!w->w_g_dev || !w->w_f_dev)) return fail(nullptr, GR4AD_EINVAL, "a Fuse weight pointer is NULL");
     if (ds->n_levels > 1 && !w->emb_dev) return fail(nullptr, GR4AD_EINVAL, "emb_dev is NULL");
     for (int t = 0; t + 1 < ds->n_levels; t++)
         if (!w->emb_dev[t]) return fail(nullptr, GR4AD_EINVAL, "emb_dev[%d] is NULL", t);
@@ -290,9 +293,17 @@ int init_impl(gr4ad_decoder *dec, const gr4ad_model_desc *ds, const gr4ad_weight
             OP_TRY(dec, launch_head_transpose(p.wkv_x, p.wkT_x, (int)d, dec->H, 0), "per-head key weight transpose");
         }
     }
+    if (dec->vanilla) {  // no Fuse: the level's input is an embedding row plus the position embedding
+        for (int t = 0; t < dec->Tp; t++) {
+            const void *emb = t == 0 ? w->bos_dev : t == dec->T ? w->value_emb_dev : w->emb_dev[t - 1];
+            const int64_t rows = t == 0 ? 1 : dec->V[t - 1];
+            if ((s = dev_clone(dec, &dec->E[t], emb, rows * d * e))) return s;
+        }
+    }
     // Fuse (eq. fuse) is linear in the token embedding s: W_f [m*(W_g s); s] = W_f[:, :d] (m * (W_g s)) + W_f[:, d:] s.
     // Split W_f and tabulate W_g s and W_f[:, d:] s for BOS and for every token of every level.
     void *wf2 = nullptr, *wg = nullptr;
+    if (!dec->vanilla) {
     if ((s = dev_alloc(dec, &dec->wf1, d * d * e))) return s;
     if ((s = dev_alloc(dec, &wf2, d * d * e))) return s;
     if ((s = dev_clone(dec, &wg, w->w_g_dev, d * d * e))) return s;
@@ -305,6 +316,7 @@ int init_impl(gr4ad_decoder *dec, const gr4ad_model_desc *ds, const gr4ad_weight
         if ((s = dev_alloc(dec, &dec->P[t], rows * d * sizeof(float)))) return s;
         OP_TRY(dec, launch_gemm(dec->dtype, emb, d, wg, d, rows, (int)d, (int)d, f32_epilogue(dec->G[t], d), 0), "Fuse gate table");
         OP_TRY(dec, launch_gemm(dec->dtype, emb, d, wf2, d, rows, (int)d, (int)d, f32_epilogue(dec->P[t], d), 0), "Fuse token table");
+    }
     }
     if (dec->fp8) {
         unsigned *amax = nullptr;
@@ -324,7 +336,7 @@ int init_impl(gr4ad_decoder *dec, const gr4ad_model_desc *ds, const gr4ad_weight
             if ((s = quant(p.w1, F * d, &p.w1_8, &p.s_w1))) return s;
             if ((s = quant(p.w2, d * F, &p.w2_8, &p.s_w2))) return s;
         }
-        if ((s = quant(dec->wf1, d * d, &dec->wf1_8, &dec->s_wf1))) return s;
+        if (!dec->vanilla && (s = quant(dec->wf1, d * d, &dec->wf1_8, &dec->s_wf1))) return s;
         for (int t = 0; t < dec->Tp; t++)
             if ((s = quant(dec->cls[t], (size_t)dec->V[t] * d, &dec->cls8[t], &dec->s_cls[t]))) return s;
     }
@@ -363,6 +375,7 @@ int gr4ad_decode_init(const gr4ad_model_desc *ds, const gr4ad_weights *w, gr4ad_
     dec->dtype = ds->dtype; dec->esz = ds->dtype == GR4AD_BF16 ? 2 : 4; dec->eps = ds->rms_eps;
     dec->trace = false; dec->err[0] = 0;
     dec->fp8 = ds->fp8_gemm != 0;
+    dec->vanilla = ds->vanilla_input != 0;
     dec->Ve = ds->n_value_buckets; dec->Tp = dec->T + (dec->Ve > 0 ? 1 : 0); dec->value_out = nullptr;
     {
         // The lazy layers attend with only T queries per request, so projecting every context row to keys and values
@@ -576,7 +589,7 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
     };
 
     // ---- step 1: lazy pass (eq. trunk): all T levels at once, no beam dimension ----
-    OP_TRY(dec, launch_broadcast_rows(dt, dec->pos, trunk, B, Tq, d, st), "trunk input");
+    if (!dec->vanilla) OP_TRY(dec, launch_broadcast_rows(dt, dec->pos, trunk, B, Tq, d, st), "trunk input");
     fold = K > 0 && fold_ok((int64_t)B * Tq, 0);
     for (int l = 0; l < K; l++) {
         const LayerPacked &lw = dec->layers[l];
@@ -605,10 +618,13 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         fold = !f8 && fold_ok(rows, dec->V[t]);
         scaled = false;
         emitted = nullptr;
-        {
+        if (dec->vanilla) {
+            // vanilla decoder (section 3.2): h^(0)_t = s_{t-1} + p_t
+            OP_TRY(dec, launch_embed_pos(dt, dec->E[t], tok_prev, (const char *)dec->pos + (size_t)t * d * e, h, rows, d, st), "vanilla input state");
+        } else {
             // the gated embedding goes through q when the Fuse projection also writes the first norm's input into xn
             void *gated = fold ? q : xn;
-            OP_TRY(dec, launch_fuse_gate(dt, (const float *)trunk + (size_t)t * d, (int64_t)Tq * d, dec->G[t], tok_prev, gated, B, n, d, st), "Fuse gate");
+            OP_TRY(dec, launch_fuse_gate(dt, (const float *)trunk + (size_t)t * d, (int64_t)Tq * d, dec->G[t], t == 0 ? 1 : dec->V[t - 1], tok_prev, gated, B, n, d, st), "Fuse gate");
             GemmEpilogue g = plain_epilogue(h, d);
             g.out_f32 = 1;
             g.table = (const float *)dec->P[t];

@@ -115,17 +115,59 @@ __global__ __launch_bounds__(256) void fuse_gate_kernel(const float *__restrict_
     store16<T>(a + row * d + (int64_t)c * N, mv);
 }
 
-int launch_fuse_gate(gr4ad_dtype dtype, const void *m, int64_t m_req_stride, const void *G, const int32_t *tok, void *a, int B, int n,
-                     int d, hipStream_t st) {
+int launch_fuse_gate(gr4ad_dtype dtype, const void *m, int64_t m_req_stride, const void *G, int64_t table_rows, const int32_t *tok, void *a,
+                     int B, int n, int d, hipStream_t st) {
     const int N = dtype == GR4AD_BF16 ? 8 : 4;
     int64_t rows = (int64_t)B * n, total = rows * (d / N);
     int64_t grid = ceil_div64(total, 256);
     if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
-    ProfScope ps(KC_FUSE_GATE, st, 0.0, (double)rows * d * (4 + (dtype == GR4AD_BF16 ? 2 : 4)));
+    // what must move once: the gated rows written, one trunk row per request, and each table row at most once (beams that carry
+    // the same token share it; at most min(rows, table rows) distinct ones)
+    const double distinct = (double)(rows < table_rows ? rows : table_rows);
+    ProfScope ps(KC_FUSE_GATE, st, 0.0, (double)rows * d * (dtype == GR4AD_BF16 ? 2 : 4) + ((double)B + distinct) * d * 4);
     if (dtype == GR4AD_BF16)
         hipLaunchKernelGGL(fuse_gate_kernel<bf16>, dim3((unsigned)grid), dim3(256), 0, st, (const float *)m, m_req_stride, (const float *)G, tok, (bf16 *)a, rows, n, d);
     else
         hipLaunchKernelGGL(fuse_gate_kernel<float>, dim3((unsigned)grid), dim3(256), 0, st, (const float *)m, m_req_stride, (const float *)G, tok, (float *)a, rows, n, d);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Input state of the vanilla autoregressive decoder (section 3.2): h^(0)_t = s_{t-1} + p_t, the embedding of the
+// beam's previous token plus the level's position embedding, written to the float32 residual stream.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void embed_pos_kernel(const T *__restrict__ E, const int32_t *__restrict__ tok, const T *__restrict__ p,
+                                                        float *__restrict__ h, int64_t rows, int d) {
+    constexpr int N = Vec16<T>::N;
+    const int nvec = d / N;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * nvec) return;
+    const int64_t row = idx / nvec;
+    const int c = (int)(idx % nvec);
+    const int64_t t = tok ? (int64_t)tok[row] : 0;
+    float ev[N], pv[N];
+    load16<T>(E + t * d + (int64_t)c * N, ev);
+    load16<T>(p + (int64_t)c * N, pv);
+#pragma unroll
+    for (int e = 0; e < N; e++) ev[e] += pv[e];
+#pragma unroll
+    for (int e = 0; e < N; e += 4) store16<float>(h + row * d + (int64_t)c * N + e, &ev[e]);
+}
+
+int launch_embed_pos(gr4ad_dtype dtype, const void *E, const int32_t *tok, const void *p, void *h, int64_t rows, int d, hipStream_t st) {
+    const int N = dtype == GR4AD_BF16 ? 8 : 4;
+    if (!E || !p || !h || rows < 1 || d < N || d % N) return GR4AD_EINVAL;
+    if (((uintptr_t)E % 16) || ((uintptr_t)p % 16) || ((uintptr_t)h % 16)) return GR4AD_EUNSUPPORTED;
+    const int64_t grid = ceil_div64(rows * (d / N), 256);
+    if (grid > 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
+    // one embedding row per distinct token is the least that must be read; rows of float32 written
+    ProfScope ps(KC_FUSE_GATE, st, 0.0, (double)rows * d * 4);
+    if (dtype == GR4AD_BF16)
+        hipLaunchKernelGGL(embed_pos_kernel<bf16>, dim3((unsigned)grid), dim3(256), 0, st, (const bf16 *)E, tok, (const bf16 *)p, (float *)h, rows, d);
+    else
+        hipLaunchKernelGGL(embed_pos_kernel<float>, dim3((unsigned)grid), dim3(256), 0, st, (const float *)E, tok, (const float *)p, (float *)h, rows, d);
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }
