@@ -66,6 +66,7 @@ def _desc(**over):
     (dict(max_beam=[4, 5000, 4]), -2, "max_beam"),
     (dict(codebook=[8, 8, 20000]), -2, "codebook"),
     (dict(n_value_buckets=-1), -1, "n_value_buckets"),
+    (dict(vanilla_input=1, n_lazy=1), -1, "vanilla_input"),
     (dict(n_value_buckets=16, n_levels=8, codebook=[8] * 8, max_beam=[4] * 8), -2, "value step"),
 ])
 def test_init_rejects_bad_descriptions_without_a_gpu(over, status, needle):

@@ -7,22 +7,20 @@ import oracle
 from gpu_common import MARGIN, TOL_LOGPROB, gpu_decode, judge_decode
 from helpers import tiny
 from paper_2602_22732_amd import binding, synth
+from rounding_model import RoundedModel
 
 pytestmark = pytest.mark.gpu
 
 
-# The toy models below exist to exercise indexing, ragged tiles and degenerate shapes.  Their
-# logits are about twice as large as those of the benchmark configurations (few classes per
-# hidden unit), and so is the rounding noise of bf16 activations; their bf16 runs are judged at
-# 6e-2.  The benchmark configurations are judged at the stated 2e-2 (test_gpu_configs.py).
-TOY_BF16_TOL = 6e-2
-
-
+# The toy models below exist to exercise indexing, ragged tiles and degenerate shapes.  float32 runs are held to the stated
+# 1e-4.  How far bf16 storage moves a log-probability depends on the model (narrow toy models with large logits are far more
+# sensitive than the benchmark configurations), so bf16 runs get their bound from the rounding model of the same shape:
+# see gpu_common.judge_decode.  The benchmark configurations are judged at the stated 2e-2 (test_gpu_configs.py).
 def run_and_judge(w, W, X, lens, requests=None, beam=None):
     sid, lp, tr = gpu_decode(w, W, X, lens, beam=beam)
     requests = range(X.shape[0]) if requests is None else requests
-    tol = TOY_BF16_TOL if w.dtype == "bf16" else None
-    return sid, lp, tr, judge_decode(w, W, X, lens, sid, lp, tr, requests, beam=beam, tol=tol, margin=None if tol is None else 2 * tol)
+    model = RoundedModel(w, W, batch=X.shape[0]) if w.dtype == "bf16" else None
+    return sid, lp, tr, judge_decode(w, W, X, lens, sid, lp, tr, requests, beam=beam, model=model)
 
 
 def test_config1_tiny_fp32_full_batch_matches_oracle_exactly_where_margins_allow():
@@ -84,20 +82,33 @@ def test_random_shapes_match_oracle(dtype, seed):
     shape = random_shape(seed)
     w, W, X = tiny(dtype=dtype, gain_jitter=0.3 if dtype == "f32" else 0.1, seed=4321 + seed, **shape)
     lens = synth.make_lengths(w, seed=seed)
-    if dtype == "bf16" and w.d < 64:
-        # Models narrower than 64 with up to four layers and five levels: their bf16 runs reach 0.12 on cumulative scores (the
-        # fp32 runs of the same shapes, which check the logic, stay within 1e-4).  They are held to a bound that still
-        # separates rounding from a wrong operand or index (errors of the size of the logits, 4 to 6 here).
-        sid, lp, tr = gpu_decode(w, W, X, lens)
-        stats = judge_decode(w, W, X, lens, sid, lp, tr, range(w.B), tol=0.35, margin=0.7)
-    elif dtype == "bf16":
-        # cumulative scores add the levels' errors: the toy bound, set on three-level models, grows with the number of levels
-        tol = TOY_BF16_TOL * max(1.0, w.T / 3.0)
-        sid, lp, tr = gpu_decode(w, W, X, lens)
-        stats = judge_decode(w, W, X, lens, sid, lp, tr, range(w.B), tol=tol, margin=2 * tol)
-    else:
-        sid, lp, tr, stats = run_and_judge(w, W, X, lens)
+    sid, lp, tr, stats = run_and_judge(w, W, X, lens)
     print(dtype, shape, stats)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [
+    dict(T=3, V=[40, 33, 50], d=64, H=2, F=96, L=3, K=0, S=37, B=5, beam=[7, 13, 9], len_min=5),
+    dict(T=2, V=[520, 130], d=256, H=2, F=64, L=2, K=0, S=9, B=2, beam=[300, 77]),
+    dict(T=4, V=[17, 300, 64, 9], d=128, H=8, F=192, L=2, K=0, S=70, B=3, beam=[5, 64, 31, 40], len_min=1),
+])
+def test_vanilla_decoder_matches_oracle(dtype, shape):
+    # section 3.2, "Vanilla Autoregressive Decoding": input state s_{t-1} + p_t, every layer per beam and level, no Fuse
+    w, W, X = tiny(dtype=dtype, gain_jitter=0.3 if dtype == "f32" else 0.1, vanilla=True, **shape)
+    lens = synth.make_lengths(w, seed=11)
+    sid, lp, tr, stats = run_and_judge(w, W, X, lens)
+    print("vanilla", dtype, shape["V"], stats)
+    # not the K = 0 LazyAR decoder: the same weights with Fuse give other beams
+    w.vanilla = False
+    sid2, lp2, _ = gpu_decode(w, W, X, lens, trace=False)
+    assert not np.array_equal(sid, sid2) or np.abs(lp - lp2).max() > 1e-3
+
+
+def test_vanilla_decoder_refuses_lazy_layers():
+    w, W, X = tiny(T=2, V=[50, 60], d=64, H=2, F=64, L=2, K=1, S=6, B=2, beam=[4, 6])
+    w.vanilla = True
+    with pytest.raises(binding.Gr4adError, match="vanilla_input"):
+        binding.decoder_for(w, W)
 
 
 def test_beam_one_is_greedy_and_exhaustive_beam_covers_all_paths():
@@ -188,8 +199,7 @@ def test_largest_codebook_and_beam_the_library_takes(dtype):
     assert sid.shape == (2, 4096, 2) and sid.min() >= 0 and sid.max() < 16384 and (np.diff(lp, axis=1) <= 0).all()
     for r in range(w.B):
         assert len({tuple(p) for p in sid[r]}) == 4096
-    tol = TOY_BF16_TOL if dtype == "bf16" else None
-    print(judge_decode(w, W, X, lens, sid, lp, tr, [1], tol=tol, margin=None if tol is None else 2 * tol))
+    print(judge_decode(w, W, X, lens, sid, lp, tr, [1], model=RoundedModel(w, W) if dtype == "bf16" else None))
     # one more than the limits is refused at init
     for over in (dict(V=[16385, 8]), dict(beam=[4097, 8], max_beam=[4097, 8])):
         w2, W2, _ = tiny(dtype=dtype, T=2, d=64, H=1, F=64, L=2, K=1, S=4, B=1, V=over.get("V", [8192, 8]), beam=over.get("beam", [4, 4]))

@@ -7,9 +7,10 @@ import pytest
 import torch
 
 import oracle
-from gpu_common import gpu_decode, judge_decode, judge_value
+from gpu_common import gpu_decode, judge_decode, judge_value, value_rounding_model
 from helpers import tiny
 from paper_2602_22732_amd import binding, synth
+from rounding_model import RoundedModel
 
 pytestmark = pytest.mark.gpu
 
@@ -87,15 +88,13 @@ def test_linear_fp8_matches_exact_product(M, N, K, out_f32, bias):
     assert np.isfinite(C).all()
 
 
-# Two FP8 pipelines that differ by bf16-level rounding upstream do not stay that close: an activation that differs by delta
-# from the oracle's lands on the neighbouring E4M3 code with probability |delta| / step and then differs by a whole step, an
-# RMS deviation of sqrt(|delta| * step) - for delta = 2^-9 and step = 2^-3.5 of the value that is 1.3 % of it, half of the
-# quantisation noise itself (step / sqrt(12) = 2.5 %).  So the GPU is held to the oracle's FP8 mode within a tolerance of the
-# size of the FP8 effect: on these toy models the oracle's FP8 and full-precision log-probabilities differ by up to 0.8 at a
-# level (mean 0.05 to 0.25), the GPU's cumulative scores were measured up to 0.49 from the FP8 oracle's and are held to 0.6.
-# A wrong scale, operand or weight shows as an error of the size of the logits themselves (a range of 4 to 6 here).  The
-# benchmark-shaped configuration below is held to its own, measured and much smaller, figure.
-TOY_FP8_TOL = 0.6
+# Two FP8 pipelines that differ by bf16-level rounding upstream do not stay close: an activation that differs by delta from the
+# oracle's lands on the neighbouring E4M3 code with probability |delta| / step and then differs by a whole step.  The FP8 oracle
+# (exact arithmetic between the E4M3 roundings) is therefore far from ANY bf16-storage implementation of the same mode - on
+# toy models by up to 0.5 in a cumulative score.  The rounding model (tests/rounding_model.py) rounds to bf16 where the library
+# stores bf16 AND quantises to E4M3 where the library does, with the library's float32 scale arithmetic; it is pinned to the FP8
+# oracle with the bf16 roundings off.  The GPU is held to the rounding model tightly and to the FP8 oracle within the distance
+# between the two (gpu_common.judge_decode with model=...): no bound here comes from a GPU measurement.
 
 
 @pytest.mark.parametrize("shape", [
@@ -110,25 +109,20 @@ def test_fp8_decode_matches_fp8_oracle(shape):
     lens = synth.make_lengths(w, seed=11)
     sid, lp, tr = gpu_decode(w, W, X, lens)
     sample = range(w.B) if w.B <= 8 else [0, 17, w.B - 1]
-    print(shape["V"], judge_decode(w, W, X, lens, sid, lp, tr, sample, tol=TOY_FP8_TOL, margin=2 * TOY_FP8_TOL))
+    print(shape["V"], judge_decode(w, W, X, lens, sid, lp, tr, sample, model=RoundedModel(w, W)))
 
 
 def test_fp8_value_step_and_flag_validation():
     w, W, X = tiny(dtype="bf16", gain_jitter=0.1, T=2, V=[64, 50], Ve=32, d=128, H=2, F=128, L=2, K=1, S=20, B=3, beam=[8, 12])
     w.fp8 = True
     sid, lp, tr, val = gpu_decode(w, W, X, None, value=True)
-    judge_decode(w, W, X, None, sid, lp, tr, range(w.B), tol=TOY_FP8_TOL, margin=2 * TOY_FP8_TOL)
-    print("value:", judge_value(w, W, X, None, sid, lp, val, range(w.B), tol=TOY_FP8_TOL))
+    judge_decode(w, W, X, None, sid, lp, tr, range(w.B), model=RoundedModel(w, W))
+    print("value:", judge_value(w, W, X, None, sid, lp, val, range(w.B), model=value_rounding_model(w, W)))
     # float32 storage has no FP8 mode
     w32, W32, _ = tiny(dtype="f32", T=2, V=[8, 8], d=64, H=2, F=64, L=2, K=1, S=4, B=1, beam=[2, 2])
     w32.fp8 = True
     with pytest.raises(binding.Gr4adError, match="bf16"):
         binding.decoder_for(w32, W32)
-
-
-# Configuration 3: the oracle's FP8 and full-precision log-probabilities differ by up to 0.12 at a level (mean 0.024; 0.08 among
-# the 256 likeliest codes); the GPU's cumulative survivor scores were measured up to 0.15 from the FP8 oracle's over three levels.
-CONFIG_FP8_TOL = 0.2
 
 
 def test_config3_fp8_sampled_requests():
@@ -138,8 +132,21 @@ def test_config3_fp8_sampled_requests():
     X = synth.make_context(w, lens)
     sid, lp, tr = gpu_decode(w, W, X, lens)
     assert np.isfinite(lp).all() and (lp <= 0).all() and (np.diff(lp, axis=1) <= 0).all()
-    stats = judge_decode(w, W, X, lens, sid, lp, tr, [0, 130], tol=CONFIG_FP8_TOL, margin=2 * CONFIG_FP8_TOL)
+    stats = judge_decode(w, W, X, lens, sid, lp, tr, [0, 130], model=RoundedModel(w, W))
     print("config 3 fp8:", stats)
+
+
+def test_config4_fp8_full_batch_sampled_request():
+    # configuration 4 (1024 requests, ragged context lengths, beams 256/512/512/1024) in FP8 mode (bench.py --config 4 --fp8)
+    w = synth.workload(4, fp8=True)
+    W = synth.make_weights(w)
+    lens = synth.make_lengths(w)
+    X = synth.make_context(w, lens)
+    sid, lp, tr = gpu_decode(w, W, X, lens)
+    assert np.isfinite(lp).all() and (lp <= 0).all() and (np.diff(lp, axis=1) <= 0).all()
+    for r in range(0, w.B, 64):
+        assert len({tuple(p) for p in sid[r]}) == w.beam[-1]
+    print("config 4 fp8:", judge_decode(w, W, X, lens, sid, lp, tr, [int(np.argmin(lens))], model=RoundedModel(w, W)))
 
 
 def test_config5_fp8_full_batch_sampled_request():
@@ -152,4 +159,4 @@ def test_config5_fp8_full_batch_sampled_request():
     assert np.isfinite(lp).all() and (lp <= 0).all() and (np.diff(lp, axis=1) <= 0).all()
     for r in range(0, w.B, 64):
         assert len({tuple(p) for p in sid[r]}) == w.beam[-1]
-    print("config 5 fp8:", judge_decode(w, W, X, lens, sid, lp, tr, [777], tol=CONFIG_FP8_TOL, margin=2 * CONFIG_FP8_TOL))
+    print("config 5 fp8:", judge_decode(w, W, X, lens, sid, lp, tr, [777], model=RoundedModel(w, W)))

@@ -4,13 +4,12 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_common import gpu_decode, judge_decode, judge_value
+from gpu_common import gpu_decode, judge_decode, judge_value, value_rounding_model
 from helpers import tiny
 from paper_2602_22732_amd import binding, synth
+from rounding_model import RoundedModel
 
 pytestmark = pytest.mark.gpu
-
-TOY_BF16_TOL = 6e-2  # toy models, see test_gpu_decode.py
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -28,10 +27,12 @@ def test_value_step_matches_oracle(dtype, shape):
         W["value_bias"] = np.linspace(-2.0, 1.0, 21).astype(np.float32)
     lens = synth.make_lengths(w, seed=11)
     sid, lp, tr, val = gpu_decode(w, W, X, lens, value=True)
-    tol = TOY_BF16_TOL if dtype == "bf16" else None
     sample = range(w.B) if w.B <= 8 else [0, 17, w.B - 1]
-    judge_decode(w, W, X, lens, sid, lp, tr, sample, tol=tol, margin=None if tol is None else 2 * tol)
-    print(dtype, shape["V"], shape["Ve"], "max, mean value error", judge_value(w, W, X, lens, sid, lp, val, sample, tol=tol))
+    # float32: the stated 1e-4; bf16: bounds from the rounding model of this shape (gpu_common.judge_decode)
+    bf = dtype == "bf16"
+    judge_decode(w, W, X, lens, sid, lp, tr, sample, model=RoundedModel(w, W) if bf else None)
+    print(dtype, shape["V"], shape["Ve"], "max, mean value error",
+          judge_value(w, W, X, lens, sid, lp, val, sample, model=value_rounding_model(w, W) if bf else None))
 
 
 def test_value_step_switches_on_and_off_per_call_and_leaves_the_sids_alone():
@@ -74,7 +75,7 @@ def test_config3_with_value_step_sampled_requests():
     sid, lp, tr, val = gpu_decode(w, W, X, lens, value=True)
     sample = [0, 201]
     print("config 3 + value:", judge_decode(w, W, X, lens, sid, lp, tr, sample), "max, mean value error",
-          judge_value(w, W, X, lens, sid, lp, val, sample))
+          judge_value(w, W, X, lens, sid, lp, val, sample, model=value_rounding_model(w, W)))
     assert np.isfinite(val).all() and (val <= 0).all()
 
 
@@ -87,7 +88,7 @@ def test_config4_with_value_step_full_batch_sampled_request():
     sid, lp, tr, val = gpu_decode(w, W, X, lens, value=True)
     assert val.shape == (w.B, w.beam[-1], 256) and np.isfinite(val).all() and (val <= 0).all()
     assert np.abs(np.exp(val[::97].astype(np.float64)).sum(axis=2) - 1).max() < 1e-4
-    print("config 4 + value:", judge_decode(w, W, X, lens, sid, lp, tr, [511]), "max, mean value error", judge_value(w, W, X, lens, sid, lp, val, [511]))
+    print("config 4 + value:", judge_decode(w, W, X, lens, sid, lp, tr, [511]), "max, mean value error", judge_value(w, W, X, lens, sid, lp, val, [511], model=value_rounding_model(w, W)))
 
 
 @pytest.mark.parametrize("seed", range(6))
