@@ -8,8 +8,17 @@ import torch.nn.functional as F
 import oracle
 from helpers import tiny
 
-torch.set_default_dtype(torch.float64)
 RNG = np.random.default_rng(7)
+
+
+@pytest.fixture(autouse=True)
+def _float64_default_in_this_module_only():
+    # the library routines below are compared in double; the setting must not leak into other test modules (pytest imports
+    # every module at collection, and a process-wide float64 default silently changes what torch.randn returns elsewhere)
+    old = torch.get_default_dtype()
+    torch.set_default_dtype(torch.float64)
+    yield
+    torch.set_default_dtype(old)
 
 
 def test_linear_matches_library():
