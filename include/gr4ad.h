@@ -176,7 +176,8 @@ void gr4ad_decode_free(gr4ad_decoder *dec);
 const char *gr4ad_strerror(int status);
 
 /* Message of the last failing call on this decoder ("" if none).  With
- * dec == NULL: the last failure of gr4ad_decode_init on this thread. */
+ * dec == NULL: the last failure on this thread of gr4ad_decode_init or of an
+ * entry point that takes no decoder (gr4ad_op_select_static). */
 const char *gr4ad_last_error(const gr4ad_decoder *dec);
 
 /*
@@ -215,6 +216,20 @@ size_t gr4ad_op_select_workspace_bytes(int32_t B, int32_t n, int32_t V, int32_t 
 int gr4ad_op_select(const float *logits_dev, const float *cum_dev, int32_t B, int32_t n, int32_t V, int32_t k,
                     void *workspace_dev, size_t workspace_bytes, int32_t *parent_dev, int32_t *tok_dev, float *score_dev,
                     void *hip_stream);
+
+/*
+ * gr4ad_op_select_static -- gr4ad_op_select for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as gr4ad_op_select without the
+ * workspace: the candidate lists, bounds and counts live in a fixed device array inside the library
+ * (GR4AD_SELECT_STATIC_BYTES per GPU, held until the process ends).  The call allocates nothing (no hipMalloc, hipFree
+ * or allocating library routine; per-kernel timing must be off, it creates events) and only enqueues kernels on
+ * hip_stream.  Sizes with gr4ad_op_select_workspace_bytes(B, n, V, k) > GR4AD_SELECT_STATIC_BYTES are refused with
+ * GR4AD_EWORKSPACE (message through gr4ad_last_error(NULL)).  All calls on one GPU share that GPU's array: calls that
+ * overlap in time on one GPU, on whatever streams, race; nothing needs to be cleared between calls.
+ */
+#define GR4AD_SELECT_STATIC_BYTES (32u << 20)
+int gr4ad_op_select_static(const float *logits_dev, const float *cum_dev, int32_t B, int32_t n, int32_t V, int32_t k,
+                           int32_t *parent_dev, int32_t *tok_dev, float *score_dev, void *hip_stream);
 
 /* Beam-shared cross-attention (section 4.2, Beam-Shared KV Caching): for each
  * request b and head h, out[b, i, h] = softmax(q[b,i,h] . K[b,:len_b,h] / sqrt(dh)) V[b,:len_b,h]

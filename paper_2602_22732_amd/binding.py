@@ -19,7 +19,7 @@ EXPORTS = ["gr4ad_decode_init", "gr4ad_decode_workspace_bytes", "gr4ad_decode_ba
            "gr4ad_decode_set_value_output",
            "gr4ad_decode_free", "gr4ad_strerror", "gr4ad_last_error", "gr4ad_op_linear", "gr4ad_op_select_workspace_bytes",
            "gr4ad_op_quantize_rows", "gr4ad_op_linear_fp8",
-           "gr4ad_op_select", "gr4ad_op_cross_attention_workspace_bytes", "gr4ad_op_cross_attention", "gr4ad_op_gather_rows",
+           "gr4ad_op_select", "gr4ad_op_select_static", "gr4ad_op_cross_attention_workspace_bytes", "gr4ad_op_cross_attention", "gr4ad_op_gather_rows",
            "gr4ad_profile_enable",
            "gr4ad_profile_kernel_count", "gr4ad_profile_kernel_name", "gr4ad_profile_read"]
 
@@ -96,6 +96,8 @@ def lib():
         L.gr4ad_op_select_workspace_bytes.argtypes = [C.c_int32] * 4
         L.gr4ad_op_select.restype = C.c_int
         L.gr4ad_op_select.argtypes = [_VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP, C.c_size_t, _VP, _VP, _VP, _VP]
+        L.gr4ad_op_select_static.restype = C.c_int
+        L.gr4ad_op_select_static.argtypes = [_VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP, _VP, _VP, _VP]
         L.gr4ad_op_cross_attention.restype = C.c_int
         L.gr4ad_op_cross_attention.argtypes = [C.c_int, _VP, _VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP,
                                                C.c_size_t, _VP]
@@ -332,6 +334,18 @@ def op_select(logits, cum, k, stream=None):
     score = torch.empty(B, k, dtype=torch.float32, device=logits.device)
     _check(L.gr4ad_op_select(logits.data_ptr(), None if cum is None else cum.data_ptr(), B, n, V, k, ws.data_ptr(), ws.numel(),
                              parent.data_ptr(), tok.data_ptr(), score.data_ptr(), _stream_ptr(stream)))
+    return parent, tok, score
+
+
+SELECT_STATIC_BYTES = 32 << 20
+
+
+def op_select_static(logits, cum, k, parent, tok, score, stream=None):
+    """gr4ad_op_select_static: the selection without a workspace (static scratch inside the library).  The caller
+    passes the outputs parent, tok [B,k] int32 and score [B,k] float32: the call itself allocates nothing."""
+    B, n, V = logits.shape
+    _check(lib().gr4ad_op_select_static(logits.data_ptr(), None if cum is None else cum.data_ptr(), B, n, V, k, parent.data_ptr(),
+                                        tok.data_ptr(), score.data_ptr(), _stream_ptr(stream)))
     return parent, tok, score
 
 

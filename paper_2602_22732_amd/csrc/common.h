@@ -31,6 +31,9 @@ __device__ __forceinline__ float wave_max(float v) {
 
 static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Records the message gr4ad_last_error(NULL) returns on this thread (entry points that take no decoder); returns `code`.
+int gr4ad_set_thread_error(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
 // ---- GEMM: C[M,N] = A[M,K] * W[N,K]^T with a fused epilogue -----------------
 enum { ACT_NONE = 0, ACT_SILU = 1 };
 struct GemmEpilogue {

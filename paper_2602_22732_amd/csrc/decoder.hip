@@ -346,6 +346,14 @@ int init_impl(gr4ad_decoder *dec, const gr4ad_model_desc *ds, const gr4ad_weight
 
 }  // namespace
 
+int gr4ad_set_thread_error(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_init_error, sizeof(g_init_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
 extern "C" {
 
 const char *gr4ad_strerror(int status) {

@@ -860,3 +860,43 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }
+
+// ---------------------------------------------------------------------------
+// The same selection for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+// harnesses that forbid hipMalloc): the candidate lists, first-row cuts, request bounds and counts live in a fixed device
+// array of this library instead of a caller workspace.  Host code never uses the array's name as an address: the device
+// address is looked up once per device and kept.  Every call on a GPU shares that GPU's array (overlapping calls race);
+// nothing in it has to start at zero - the counts are written by a kernel of every call before they are read.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[GR4AD_SELECT_STATIC_BYTES];
+
+namespace {
+const int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device (NULL: not looked up yet)
+}  // namespace
+
+extern "C" int gr4ad_op_select_static(const float *logits, const float *cum, int32_t B, int32_t n, int32_t V, int32_t k, int32_t *parent,
+                                      int32_t *tok, float *score, void *hip_stream) {
+    if (!logits || !parent || !tok || !score) return gr4ad_set_thread_error(GR4AD_EINVAL, "gr4ad_op_select_static: a required pointer is NULL");
+    if (B < 1 || n < 1 || V < 1 || k < 1 || (int64_t)k > (int64_t)n * V)
+        return gr4ad_set_thread_error(GR4AD_EINVAL, "gr4ad_op_select_static: need B, n, V >= 1 and 1 <= k <= n*V");
+    if (k > GR4AD_MAX_BEAM || V > GR4AD_MAX_CODEBOOK)
+        return gr4ad_set_thread_error(GR4AD_EUNSUPPORTED, "gr4ad_op_select_static: k > %d or V > %d", GR4AD_MAX_BEAM, GR4AD_MAX_CODEBOOK);
+    const int m = k < V ? k : V;
+    // (computed in 64 bits before select_workspace_bytes multiplies the sizes)
+    if ((double)B * n * m * 8.0 > (double)GR4AD_SELECT_STATIC_BYTES || select_workspace_bytes(B, n, V, k) > (size_t)GR4AD_SELECT_STATIC_BYTES)
+        return gr4ad_set_thread_error(GR4AD_EWORKSPACE, "gr4ad_op_select_static: B=%d n=%d V=%d k=%d needs more than the %u bytes of static scratch", B, n,
+                                      V, k, (unsigned)GR4AD_SELECT_STATIC_BYTES);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return gr4ad_set_thread_error(GR4AD_EHIP, "gr4ad_op_select_static: hipGetDevice failed");
+    if (dev < 0 || dev >= kMaxDevices) return gr4ad_set_thread_error(GR4AD_EUNSUPPORTED, "gr4ad_op_select_static: device index %d", dev);
+    if (!g_scratch_ptr[dev]) {  // once per device, with that device current: each GPU holds its own copy of the array
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return gr4ad_set_thread_error(GR4AD_EHIP, "gr4ad_op_select_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    const int s = launch_select(logits, cum, B, n, V, k, g_scratch_ptr[dev], (size_t)GR4AD_SELECT_STATIC_BYTES, parent, tok, score, nullptr, nullptr,
+                                nullptr, nullptr, 0, 0, (hipStream_t)hip_stream);
+    return s == GR4AD_OK ? s : gr4ad_set_thread_error(s, "gr4ad_op_select_static: selection failed: %s", gr4ad_strerror(s));
+}

@@ -109,3 +109,10 @@ def test_ops_reject_bad_arguments_without_a_gpu():
     assert L.gr4ad_op_cross_attention_workspace_bytes(1, 2, 100, 128, 2) == 2 * 128 * 128 * 2   # bf16, dh 64: S padded to 128
     assert L.gr4ad_op_cross_attention_workspace_bytes(0, 2, 100, 128, 2) == 0                   # float32 runs on the plain kernel
     assert L.gr4ad_op_gather_rows(0, None, None, None, 1, 1, 1, 8, 8, None) == -1
+    # the selection on static scratch checks its arguments and its size limit on the host, before any device call
+    assert L.gr4ad_op_select_static(None, None, 1, 1, 8, 1, None, None, None, None) == -1
+    one = C.c_int32(0)
+    p = C.addressof(one)  # stands for a device pointer: never dereferenced, the size check comes first
+    assert L.gr4ad_op_select_static(p, None, 64, 512, 8192, 512, p, p, p, None) == -3
+    assert b"static scratch" in L.gr4ad_last_error(None)
+    assert L.gr4ad_op_select_static(p, None, 1, 2, 4, 9, p, p, p, None) == -1  # k > n*V
