@@ -217,6 +217,14 @@ int gr4ad_op_select(const float *logits_dev, const float *cum_dev, int32_t B, in
                     void *workspace_dev, size_t workspace_bytes, int32_t *parent_dev, int32_t *tok_dev, float *score_dev,
                     void *hip_stream);
 
+/* gr4ad_op_select_f16 -- gr4ad_op_select on half-precision logits (IEEE binary16, [B, n, V] row-major), the form
+ * in which decode_batch hands the classifier's output to the selection in bf16 mode: the log-softmax and the scores are
+ * computed in float32 from the stored halves.  V must be a multiple of 8 and at most 8192 and logits_dev 16-byte aligned
+ * (GR4AD_EUNSUPPORTED otherwise).  Same workspace, outputs and ordering as gr4ad_op_select. */
+int gr4ad_op_select_f16(const void *logits_f16_dev, const float *cum_dev, int32_t B, int32_t n, int32_t V, int32_t k,
+                        void *workspace_dev, size_t workspace_bytes, int32_t *parent_dev, int32_t *tok_dev, float *score_dev,
+                        void *hip_stream);
+
 /*
  * gr4ad_op_select_static -- gr4ad_op_select for callers that cannot allocate device memory: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as gr4ad_op_select without the

@@ -19,7 +19,7 @@ EXPORTS = ["gr4ad_decode_init", "gr4ad_decode_workspace_bytes", "gr4ad_decode_ba
            "gr4ad_decode_set_value_output",
            "gr4ad_decode_free", "gr4ad_strerror", "gr4ad_last_error", "gr4ad_op_linear", "gr4ad_op_select_workspace_bytes",
            "gr4ad_op_quantize_rows", "gr4ad_op_linear_fp8",
-           "gr4ad_op_select", "gr4ad_op_select_static", "gr4ad_op_cross_attention_workspace_bytes", "gr4ad_op_cross_attention", "gr4ad_op_gather_rows",
+           "gr4ad_op_select", "gr4ad_op_select_f16", "gr4ad_op_select_static", "gr4ad_op_cross_attention_workspace_bytes", "gr4ad_op_cross_attention", "gr4ad_op_gather_rows",
            "gr4ad_profile_enable",
            "gr4ad_profile_kernel_count", "gr4ad_profile_kernel_name", "gr4ad_profile_read"]
 
@@ -96,6 +96,8 @@ def lib():
         L.gr4ad_op_select_workspace_bytes.argtypes = [C.c_int32] * 4
         L.gr4ad_op_select.restype = C.c_int
         L.gr4ad_op_select.argtypes = [_VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP, C.c_size_t, _VP, _VP, _VP, _VP]
+        L.gr4ad_op_select_f16.restype = C.c_int
+        L.gr4ad_op_select_f16.argtypes = L.gr4ad_op_select.argtypes
         L.gr4ad_op_select_static.restype = C.c_int
         L.gr4ad_op_select_static.argtypes = [_VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP, _VP, _VP, _VP]
         L.gr4ad_op_cross_attention.restype = C.c_int
@@ -325,14 +327,18 @@ def op_linear_fp8(Aq, a_scale, Wq, w_scale, bias=None, out_f32=False, stream=Non
 
 
 def op_select(logits, cum, k, stream=None):
+    """gr4ad_op_select (float32 logits) or gr4ad_op_select_f16 (float16 logits), by the tensor's dtype."""
     B, n, V = logits.shape
     L = lib()
+    if logits.dtype not in (torch.float32, torch.float16):
+        raise TypeError("op_select takes float32 or float16 logits, got %s" % logits.dtype)
+    entry = L.gr4ad_op_select_f16 if logits.dtype == torch.float16 else L.gr4ad_op_select
     nbytes = int(L.gr4ad_op_select_workspace_bytes(B, n, V, k))
     ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=logits.device)
     parent = torch.empty(B, k, dtype=torch.int32, device=logits.device)
     tok = torch.empty_like(parent)
     score = torch.empty(B, k, dtype=torch.float32, device=logits.device)
-    _check(L.gr4ad_op_select(logits.data_ptr(), None if cum is None else cum.data_ptr(), B, n, V, k, ws.data_ptr(), ws.numel(),
+    _check(entry(logits.data_ptr(), None if cum is None else cum.data_ptr(), B, n, V, k, ws.data_ptr(), ws.numel(),
                              parent.data_ptr(), tok.data_ptr(), score.data_ptr(), _stream_ptr(stream)))
     return parent, tok, score
 

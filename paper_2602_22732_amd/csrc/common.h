@@ -9,6 +9,9 @@ typedef __bf16 bf16;
 typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
@@ -29,6 +32,33 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// The same reductions through data-parallel-primitive operands instead of LDS permutes (a few cycles per step instead of an
+// LDS round trip); every lane must be active.  Rotations by 8, 4, 2, 1 inside each row of 16 lanes leave the row's result in
+// all of its lanes; two row broadcasts (lane 15 into the next row for rows 1 and 3, lane 31 into rows 2 and 3) leave the
+// wavefront's result in lane 63, which is read back as a scalar.  The summation tree differs from wave_sum's: kernels that
+// must agree to the bit use the same one.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_move(float old, float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+    v += dpp_move<0x128, 0xF>(0.0f, v);  // row_ror:8
+    v += dpp_move<0x124, 0xF>(0.0f, v);  // row_ror:4
+    v += dpp_move<0x122, 0xF>(0.0f, v);  // row_ror:2
+    v += dpp_move<0x121, 0xF>(0.0f, v);  // row_ror:1
+    v += dpp_move<0x142, 0xA>(0.0f, v);  // row_bcast:15 into rows 1 and 3 (the other rows add 0)
+    v += dpp_move<0x143, 0xC>(0.0f, v);  // row_bcast:31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_max_dpp(float v) {
+    v = fmaxf(v, dpp_move<0x128, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<0x124, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<0x122, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<0x121, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<0x142, 0xA>(v, v));  // (the other rows take the maximum with themselves)
+    v = fmaxf(v, dpp_move<0x143, 0xC>(v, v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
 static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Records the message gr4ad_last_error(NULL) returns on this thread (entry points that take no decoder); returns `code`.
@@ -40,6 +70,8 @@ struct GemmEpilogue {
     void *C;             // output, row stride ldc elements
     int64_t ldc;
     int out_f32;         // 1: C is float, 0: C has the storage dtype
+    int out_f16;         // with out_f32 = 1 and no residual/table (persistent kernel only): the float32 results (scaled, biased) leave as
+                         // IEEE half precision, C is a half array (row stride ldc elements): the classifier's logits for the selection
     const float *resid;  // float32 [M, stride ldr] residual stream, added to the product (may alias C)
     int64_t ldr;
     const float *bias;   // [N] float, added per column
@@ -147,9 +179,11 @@ int launch_trunk_self_attention(gr4ad_dtype dtype, const void *qkv, void *out, i
 size_t select_workspace_bytes(int B, int n, int V, int k);
 // sid_old [B,n,T] / sid_new [B,k,T] may be NULL (no path bookkeeping); anc_old / anc_new likewise: batch-wide row index of
 // each survivor's ancestor at levels 0..level (anc_new[.., level] = b*n + parent); level = 0-based t
-int launch_select(const float *logits, const float *cum, int B, int n, int V, int k, void *ws, size_t ws_bytes, int32_t *parent,
+// logits_f16 != 0: logits is a half-precision array (what the classifier's persistent GEMM leaves for large levels); needs select_takes_f16(V)
+int launch_select(const void *logits, int logits_f16, const float *cum, int B, int n, int V, int k, void *ws, size_t ws_bytes, int32_t *parent,
                   int32_t *tok, float *score, const int32_t *sid_old, int32_t *sid_new, const int32_t *anc_old, int32_t *anc_new, int T,
                   int level, hipStream_t st);
+bool select_takes_f16(int V);
 
 // ---- optional per-kernel event timing ----------------------------------------
 enum KernelClass { KC_GEMM_256 = 0, KC_GEMM_128, KC_GEMM_SIMPLE, KC_XATTN_FLASH, KC_XATTN_SIMPLE, KC_SELF_STEP, KC_TRUNK_SELF,

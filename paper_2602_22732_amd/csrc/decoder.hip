@@ -85,24 +85,41 @@ bool beams_ok(const gr4ad_decoder *dec, const int32_t *beam) {
     return true;
 }
 
+GemmEpilogue plain_epilogue(void *C, int64_t ldc);
+
+// Level t (0-based) with `rows` beam rows: does the classifier leave its logits in half precision for the selection?  It does
+// where the persistent GEMM runs the classifier (it alone has that epilogue) and the wavefront selection kernel takes the
+// codebook size: the logits then make their round trip through HBM in 2 instead of 4 bytes.  The log-sum-exp, the scores and
+// the selection stay float32; the rounding of a logit (at most 2^-11 of its magnitude) is far below what bf16 operands leave
+// in it.  float32 storage, small levels and the value step (whose output IS the distribution) keep float32 logits.
+bool level_logits_f16(const gr4ad_decoder *dec, int64_t rows, int t) {
+    if (dec->dtype != GR4AD_BF16 || t >= dec->T || !select_takes_f16(dec->V[t])) return false;
+    GemmEpilogue g = plain_epilogue((void *)4096, dec->V[t]);  // (pointers are only inspected for alignment)
+    g.out_f32 = 1;
+    g.out_f16 = 1;
+    if (dec->fp8) return gemm_f8_on_persistent_kernel(dec->ln_out, dec->d, dec->cls8[t], dec->d, rows, dec->V[t], dec->d, g);
+    return gemm_on_persistent_kernel(dec->dtype, dec->ln_out, dec->d, dec->cls[t], dec->d, rows, dec->V[t], dec->d, g);
+}
+
 Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *beam) {
     Plan p;
     memset(&p, 0, sizeof(p));
     const size_t e = dec->esz;
     const int64_t d = dec->d, T = dec->T, Tp = dec->Tp;
-    int64_t n = 1, nmax = 1, bmax = 1, logit_max = 0;
+    int64_t n = 1, nmax = 1, bmax = 1, logit_max = 0;  // logit_max: bytes per request
     size_t selmax = 0;
     for (int t = 0; t < T; t++) {
         if (n > nmax) nmax = n;
         if (beam[t] > bmax) bmax = beam[t];
-        if (n * dec->V[t] > logit_max) logit_max = n * dec->V[t];
+        const int64_t lb = n * dec->V[t] * (level_logits_f16(dec, B * n, t) ? 2 : 4);
+        if (lb > logit_max) logit_max = lb;
         size_t s = select_workspace_bytes((int)B, (int)n, dec->V[t], beam[t]);
         if (s > selmax) selmax = s;
         n = beam[t];
     }
     if (dec->Ve > 0) {  // the value step: one more level of n = b_T rows, no selection
         if (n > nmax) nmax = n;
-        if (n * dec->Ve > logit_max) logit_max = n * dec->Ve;
+        if (n * dec->Ve * 4 > logit_max) logit_max = n * dec->Ve * 4;
     }
     p.nmax = nmax;
     p.bmax = bmax;
@@ -131,7 +148,7 @@ Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *be
     p.o = take((size_t)p.rows_max * d * e);
     p.qkv = take((size_t)B * Tp * 3 * d * e);  // lazy layers; the autoregressive layers keep one buffer per (level, layer), below
     p.f = take((size_t)p.rows_max * dec->F * e);
-    p.logits = take((size_t)B * logit_max * sizeof(float));
+    p.logits = take((size_t)B * logit_max);
     p.aq = take(dec->fp8 ? (size_t)p.rows_max * (dec->F > d ? dec->F : d) : 0);
     p.ascale = take(dec->fp8 ? (size_t)p.rows_max * sizeof(float) : 0);
     p.selws = take(selmax);
@@ -666,9 +683,11 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
             OP_TRY(dec, ffn_block(lw, h, rows, a + 1 < A ? dec->layers[K + a + 1].ln_x : dec->ln_out), "FFN");
         }
         OP_TRY(dec, norm(h, dec->ln_out, rows), "final norm");
+        const bool lf16 = level_logits_f16(dec, rows, t);
         {
             GemmEpilogue g = plain_epilogue(logits, dec->V[t]);
             g.out_f32 = 1;
+            g.out_f16 = lf16 ? 1 : 0;
             g.bias = dec->cls_bias[t];
             if (f8) OP_TRY(dec, gemm8(rows, dec->cls8[t], dec->s_cls[t], dec->V[t], d, g), "classifier");
             else OP_TRY(dec, gemm(xn, rows, dec->cls[t], dec->V[t], d, reads_norm(g)), "classifier");
@@ -681,7 +700,7 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         int32_t *par = (int32_t *)(ws + p.par), *tok_new = (int32_t *)(ws + p.tok[cur ^ 1]);
         float *score_new = last ? out_logprob : (float *)(ws + p.cum[cur ^ 1]);
         int32_t *sid_new = last ? out_sid : (int32_t *)(ws + p.sid[cur ^ 1]);
-        OP_TRY(dec, launch_select(logits, t == 0 ? nullptr : (const float *)(ws + p.cum[cur]), B, n, dec->V[t], bt, ws + p.selws,
+        OP_TRY(dec, launch_select(logits, lf16 ? 1 : 0, t == 0 ? nullptr : (const float *)(ws + p.cum[cur]), B, n, dec->V[t], bt, ws + p.selws,
                                   select_workspace_bytes(B, n, dec->V[t], bt), par, tok_new, score_new, (const int32_t *)(ws + p.sid[cur]),
                                   sid_new, (const int32_t *)(ws + p.anc[cur]), last && !value_step ? nullptr : (int32_t *)(ws + p.anc[cur ^ 1]), T, t, st),
                "selection");
@@ -731,7 +750,14 @@ size_t gr4ad_op_select_workspace_bytes(int32_t B, int32_t n, int32_t V, int32_t 
 int gr4ad_op_select(const float *logits, const float *cum, int32_t B, int32_t n, int32_t V, int32_t k, void *ws, size_t ws_bytes,
                     int32_t *parent, int32_t *tok, float *score, void *hip_stream) {
     if (!logits || !ws || !parent || !tok || !score) return GR4AD_EINVAL;
-    return launch_select(logits, cum, B, n, V, k, ws, ws_bytes, parent, tok, score, nullptr, nullptr, nullptr, nullptr, 0, 0,
+    return launch_select(logits, 0, cum, B, n, V, k, ws, ws_bytes, parent, tok, score, nullptr, nullptr, nullptr, nullptr, 0, 0,
+                         (hipStream_t)hip_stream);
+}
+
+int gr4ad_op_select_f16(const void *logits, const float *cum, int32_t B, int32_t n, int32_t V, int32_t k, void *ws, size_t ws_bytes,
+                        int32_t *parent, int32_t *tok, float *score, void *hip_stream) {
+    if (!logits || !ws || !parent || !tok || !score) return GR4AD_EINVAL;
+    return launch_select(logits, 1, cum, B, n, V, k, ws, ws_bytes, parent, tok, score, nullptr, nullptr, nullptr, nullptr, 0, 0,
                          (hipStream_t)hip_stream);
 }
 

@@ -770,6 +770,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                         if (row < M && col < N) {
                             if (col + 3 < N) {
                                 if (KIND == EPI_F32) x += bias4;
+                                if (KIND == EPI_F32 && epi.out_f16) {  // logits for the selection: half precision, 8 bytes per lane, 128 per row
+                                    halfx4 hx;
+#pragma unroll
+                                    for (int e = 0; e < 4; e++) hx[e] = (_Float16)x[e];
+                                    __builtin_nontemporal_store(hx, (halfx4 *)((_Float16 *)epi.C + row * epi.ldc + col));
+                                } else
                                 __builtin_nontemporal_store(x, (floatx4 *)((float *)epi.C + row * epi.ldc + col));
                                 if (emit) {
                                     bf16x4 nb;
@@ -783,7 +789,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                                     if (KIND == EPI_F32 && epi.bias) y += epi.bias[col + e];
                                     if (KIND == EPI_F32_RESID) y += epi.resid[row * epi.ldr + col + e];
                                     if (KIND == EPI_F32_TABLE) y += epi.table[(epi.tok ? (int64_t)epi.tok[row] : 0) * N + col + e];
-                                    ((float *)epi.C)[row * epi.ldc + col + e] = y;
+                                    if (KIND == EPI_F32 && epi.out_f16) ((_Float16 *)epi.C)[row * epi.ldc + col + e] = (_Float16)y;
+                                    else ((float *)epi.C)[row * epi.ldc + col + e] = y;
                                 }
                             }
                         }
@@ -844,7 +851,7 @@ static int launch_ring_kind(const bf16 *A, int64_t lda, const bf16 *W, int64_t l
     {
         const double operand_bytes = F8 ? ((double)M * K + (double)N * K) : 0.0;  // FP8 operands are half the bytes gemm_bytes counts
         ProfScope ps(F8 ? KC_GEMM_RING_F8 : KC_GEMM_RING, st, 2.0 * (double)M * N * K,
-                     gemm_bytes(M, N, K, KIND >= EPI_F32 && KIND != EPI_VT, KIND == EPI_F32_RESID) - operand_bytes);
+                     gemm_bytes(M, N, K, KIND >= EPI_F32 && KIND != EPI_VT && !epi.out_f16, KIND == EPI_F32_RESID) - operand_bytes);
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), RING_LDS_BYTES, st, A, lda, W, ldw, M, N, K, tiles_m, tiles_n, 4, epi);
     }
     GR4AD_LAUNCH_CHECK();
@@ -857,6 +864,7 @@ static bool ring_ok(int kind, int N, int K, int64_t lda, int64_t ldw, const Gemm
     const bool f32 = kind >= EPI_F32;
     if (e.skip_len && e.skip_S < 1) return false;
     if (K < 192 || lda >= (1 << 22) || ldw >= (1 << 22)) return false;
+    if (e.out_f16 && kind != EPI_F32) return false;
     if (e.ldc % (f32 ? 4 : 8) || ((uintptr_t)e.C % 16)) return false;
     if (kind == EPI_F32 && e.bias && ((uintptr_t)e.bias % 16)) return false;
     if (kind == EPI_F32_RESID && (e.ldr % 4 || ((uintptr_t)e.resid % 16))) return false;
@@ -996,6 +1004,7 @@ int launch_gemm_f8(const void *A, int64_t lda, const float *a_scale, const void 
                    const GemmEpilogue &epi_in, hipStream_t st) {
     if (M <= 0 || N <= 0 || K <= 0 || !A || !W || !a_scale || !(w_scale > 0.0f)) return GR4AD_EINVAL;
     if (epi_in.norm_out || epi_in.row_inv) return GR4AD_EUNSUPPORTED;
+    if (epi_in.out_f16 && !gemm_f8_on_persistent_kernel(A, lda, W, ldw, M, N, K, epi_in)) return GR4AD_EUNSUPPORTED;
     GemmEpilogue epi = epi_in;
     epi.a_scale = a_scale;
     epi.w_scale = w_scale;
@@ -1037,8 +1046,8 @@ int launch_gemm(gr4ad_dtype dtype, const void *A, int64_t lda, const void *W, in
                 const GemmEpilogue &epi, hipStream_t st) {
     if (M <= 0 || N <= 0 || K <= 0) return GR4AD_EINVAL;
     const int kind = epilogue_kind(epi);
-    // only the persistent kernel folds the RMSNorm: never drop such a request silently
-    if ((epi.norm_out || epi.row_inv) && !gemm_on_persistent_kernel(dtype, A, lda, W, ldw, M, N, K, epi)) return GR4AD_EUNSUPPORTED;
+    // only the persistent kernel folds the RMSNorm or writes half-precision logits: never drop such a request silently
+    if ((epi.norm_out || epi.row_inv || epi.out_f16) && !gemm_on_persistent_kernel(dtype, A, lda, W, ldw, M, N, K, epi)) return GR4AD_EUNSUPPORTED;
     if (mfma_ok(dtype, A, lda, W, ldw, K, kind)) {
         const bf16 *a = (const bf16 *)A, *w = (const bf16 *)W;
         if (gemm_on_persistent_kernel(dtype, A, lda, W, ldw, M, N, K, epi)) return launch_ring(a, lda, w, ldw, M, N, K, kind, epi, st);

@@ -298,16 +298,17 @@ __global__ __launch_bounds__(256) void select_rows(const float *__restrict__ log
 }
 
 // ---------------------------------------------------------------------------
-// stage A, wavefront form: one wavefront per beam row (V <= 8192, V % 4 == 0)
+// stage A, wavefront form: one wavefront per beam row (V <= 8192)
 // ---------------------------------------------------------------------------
-// Same cut as select_rows, but a row never leaves one wavefront: no workgroup barrier anywhere, the V logits sit
-// in VEC*4 registers per lane (lane l holds tokens (j*64 + l)*4 .. +3, read as 16-byte pieces), every reduction
-// is a wave reduction, and the histogram, the threshold-bin list and the staged output live in a private LDS
-// region per wavefront.  The kernel is bound by vector instructions per logit, not by its barriers or its
-// bandwidth, so each pass is a handful of instructions per element: max and min; one exp2; scores written back
-// over the logits; a fused multiply-add and a conversion give the bin for the LDS atomic; the emit pass repeats
-// those two, and compaction costs two mbcnt, an add and an 8-byte LDS write per element.  Score bits are staged
-// raw and turned into sortable keys only for the m survivors on the way out.
+// Same cut as select_rows, but a row never leaves one wavefront: no workgroup barrier anywhere, the V logits sit in VEC*4
+// registers per lane, read as 16-byte pieces of E = 4 float32 or E = 8 half-precision values (lane l, piece g holds tokens
+// (g*64 + l)*E .. +E-1; V % E == 0), every reduction is a wave reduction, and the histogram, the threshold-bin list and the
+// staged output live in a private LDS region per wavefront.  The kernel is bound by vector instructions per logit, so the
+// common case is kept to a maximum, one exp2 and one comparison per logit: with a request-level bound in force the row is
+// swept in the logit domain against a threshold a hair below the exact one, and only the few logits that pass it are turned
+// into scores and tested exactly.  Rows that need their own cut (more than m candidates at the bound, or no bound) turn all
+// logits into scores, histogram them and rank the threshold bin exactly; score bits are staged raw and turned into sortable
+// keys only for the survivors on the way out.
 #define WROW_BINS 1024
 #define WROW_LIST 512  // threshold-bin candidates ranked exactly; the list reuses the histogram's 4 KB
 
@@ -315,14 +316,17 @@ __device__ __forceinline__ unsigned long long staged_to_key(unsigned long long s
     return ((unsigned long long)score_key(__uint_as_float((uint32_t)(st >> 32))) << 32) | (st & 0xFFFFFFFFull);
 }
 
+// token held in register i of a lane: piece i / E of the lane, element i % E of the piece
+template <int E> __device__ __forceinline__ int wave_tok(int i, int lane) { return ((i / E) * 64 + lane) * E + (i % E); }
+
 // exact fallback on the registers of one wavefront: radix selection on the score keys, two bits per step
-template <int VEC>
+template <int VEC, int E>
 __device__ __noinline__ void select_row_radix_wave(const float (&sc)[VEC * 4], int V, int m, uint32_t flat0, unsigned long long *stage) {
     const int lane = threadIdx.x % 64;
     uint32_t k_and = 0xFFFFFFFFu, k_or = 0u;
 #pragma unroll
     for (int i = 0; i < VEC * 4; i++)
-        if (((i / 4) * 64 + lane) * 4 < V) { const uint32_t k = score_key(sc[i]); k_and &= k; k_or |= k; }
+        if (wave_tok<E>(i, lane) < V) { const uint32_t k = score_key(sc[i]); k_and &= k; k_or |= k; }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) { k_and &= __shfl_xor(k_and, o, 64); k_or |= __shfl_xor(k_or, o, 64); }
     const uint32_t diff = k_and ^ k_or;
@@ -338,7 +342,7 @@ __device__ __noinline__ void select_row_radix_wave(const float (&sc)[VEC * 4], i
             for (int i = 0; i < VEC * 4; i++) {
                 const uint32_t k = score_key(sc[i]);
                 const uint32_t d = (k >> shb) & 3u;
-                const uint32_t act = (((k ^ prefix) & decided) == 0u && ((i / 4) * 64 + lane) * 4 < V) ? 1u : 0u;
+                const uint32_t act = (((k ^ prefix) & decided) == 0u && wave_tok<E>(i, lane) < V) ? 1u : 0u;
                 c12 += (d >= 1u ? act : 0u) + (d >= 2u ? (act << 16) : 0u);
                 c3 += d >= 3u ? act : 0u;
             }
@@ -356,18 +360,19 @@ __device__ __noinline__ void select_row_radix_wave(const float (&sc)[VEC * 4], i
         }
     }
     // (key & decided) > prefix: above the threshold; == prefix: `active` keys tie there and the krem lowest tokens are taken.
-    // Tokens ascend with (j, lane, e), so a tie's rank is the count of ties in earlier j, in lower lanes of this j, and in lower e.
+    // Tokens ascend with (piece, lane, element), so a tie's rank is the count of ties in earlier pieces, in lower lanes of
+    // this piece, and in lower elements.
     const int n_gt = m - krem;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     int base_gt = 0, base_eq = 0;
 #pragma unroll
-    for (int j = 0; j < VEC; j++) {
+    for (int g = 0; g < VEC * 4 / E; g++) {
         int my_eq = 0;
-        bool gt[4], eq[4];
+        bool gt[E], eq[E];
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
-            const bool ok = (j * 64 + lane) * 4 < V;
-            const uint32_t kk = score_key(sc[j * 4 + e]) & decided;
+        for (int e = 0; e < E; e++) {
+            const bool ok = (g * 64 + lane) * E < V;
+            const uint32_t kk = score_key(sc[g * E + e]) & decided;
             gt[e] = ok && kk > prefix;
             eq[e] = ok && kk == prefix;
             my_eq += eq[e] ? 1 : 0;
@@ -378,10 +383,10 @@ __device__ __noinline__ void select_row_radix_wave(const float (&sc)[VEC * 4], i
         int rank = base_eq + incl - my_eq;
         base_eq += __shfl(incl, 63, 64);
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
+        for (int e = 0; e < E; e++) {
             const unsigned long long mg = __ballot(gt[e]);
-            const uint32_t flat = flat0 + (uint32_t)((j * 64 + lane) * 4 + e);
-            const unsigned long long st = ((unsigned long long)__float_as_uint(sc[j * 4 + e] + 0.0f) << 32) | (0xFFFFFFFFu - flat);
+            const uint32_t flat = flat0 + (uint32_t)((g * 64 + lane) * E + e);
+            const unsigned long long st = ((unsigned long long)__float_as_uint(sc[g * E + e] + 0.0f) << 32) | (0xFFFFFFFFu - flat);
             if (gt[e]) stage[base_gt + __popcll(mg & lt_mask)] = st;
             base_gt += __popcll(mg);
             if (eq[e]) { if (rank < krem) stage[n_gt + rank] = st; rank++; }
@@ -389,103 +394,55 @@ __device__ __noinline__ void select_row_radix_wave(const float (&sc)[VEC * 4], i
     }
 }
 
-// FULL: V == VEC*256, every register holds a token (the validity tests fold away)
-template <int VEC, bool FULL>
-__global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restrict__ logits, const float *__restrict__ cum, int64_t rows,
-                                                          int n, int V, int m, unsigned long long *__restrict__ cand, int64_t row_step,
-                                                          const unsigned long long *__restrict__ bound, int *__restrict__ req_count) {
-    // row_step: the launch visits rows 0, row_step, 2 row_step, ... of the logits (row_step = n: the first beam of every request).
-    // bound / req_count (both or neither): per request, a key no survivor can lie below; the launch then writes only
-    // the candidates that reach it (at most the row's m best), compacted per request behind a running count.
-    extern __shared__ unsigned long long wave_lds[];  // per wavefront: 512 slots of histogram / list, then m slots of staged output
-    const int lane = threadIdx.x % 64, wv = threadIdx.x / 64;
-    const int64_t vrow = (int64_t)blockIdx.x * 4 + wv;  // row of this launch
-    if (vrow >= rows) return;  // whole wavefronts leave; nothing below synchronises across wavefronts
-    const int64_t row = vrow * row_step;  // row of the logits
-    unsigned long long *list = wave_lds + (size_t)wv * ((512 + m + 1) & ~1);  // even number of 8-byte slots: 16-byte accesses stay aligned
+template <typename LT> struct LogitPiece;  // one 16-byte piece of a row of logits as floats
+template <> struct LogitPiece<float> {
+    static constexpr int E = 4;
+    static __device__ __forceinline__ void unpack(const uint4 &r, float *o) {
+        o[0] = __uint_as_float(r.x); o[1] = __uint_as_float(r.y); o[2] = __uint_as_float(r.z); o[3] = __uint_as_float(r.w);
+    }
+};
+template <> struct LogitPiece<_Float16> {
+    static constexpr int E = 8;
+    static __device__ __forceinline__ void unpack(const uint4 &r, float *o) {
+        const halfx8 v = __builtin_bit_cast(halfx8, r);
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] = (float)v[e];
+    }
+};
+
+// The row's own top-m cut.  x[i]: the logit of token wave_tok<E>(i, lane), padding -inf; mx, lse: the row's maximum and
+// log-sum-exp; the m best (score, token) pairs go to dst.
+template <int VEC, bool FULL, int E>
+__device__ __forceinline__ void select_row_own_cut(float (&x)[VEC * 4], float c, float mx, float lse, unsigned long long *__restrict__ dst,
+                                                   uint32_t flat0, uint32_t nflat, int V, int m, unsigned long long *list, int lane) {
+    constexpr int NX = VEC * 4;
     int *hist = (int *)list;
     unsigned long long *stage = list + 512;
-    const floatx4 *z4 = (const floatx4 *)(logits + row * (int64_t)V);
-    const float c = cum ? cum[row] : 0.0f;
-
-    float x[VEC * 4];
-    float mx = -INFINITY, mn = INFINITY;
+    // scores from here on (padding stays -inf)
+    float mn = INFINITY;
 #pragma unroll
-    for (int j = 0; j < VEC; j++) {
-        const int q = j * 64 + lane;
-        floatx4 v = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-        if (FULL || q * 4 < V) v = z4[q];
-#pragma unroll
-        for (int e = 0; e < 4; e++) x[j * 4 + e] = v[e];
-    }
-#pragma unroll
-    for (int i = 0; i < VEC * 4; i++) {
-        mx = fmaxf(mx, x[i]);
-        mn = fminf(mn, (FULL || ((i / 4) * 64 + lane) * 4 < V) ? x[i] : INFINITY);
-    }
-    mx = wave_max(mx);
-    mn = -wave_max(-mn);
-    const float mxl = mx * 1.4426950408889634f;
-    float sum = 0.0f;
-#pragma unroll
-    for (int i = 0; i < VEC * 4; i++) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(x[i], 1.4426950408889634f, -mxl));  // padding gives 0
-    const float lse = mx + __logf(wave_sum(sum));
-#pragma unroll
-    for (int i = 0; i < VEC * 4; i++) x[i] = c + (x[i] - lse);  // scores from here on (padding stays -inf)
-
-    unsigned long long *dst = cand + vrow * (int64_t)m;
-    const uint32_t flat0 = (uint32_t)((row % n) * (int64_t)V);
-    if (bound) {
-        // Request-level bound: the request's first row alone has m candidates at or above `bound`, so nothing below it can
-        // survive the request's selection.  Rows that have at most m candidates there write exactly those - usually far
-        // fewer than m - and skip the histogram; the others fall through to the row's own top-m cut.
-        const int64_t req = row / n;
-        const float sstar = key_score((uint32_t)(bound[req] >> 32));
-        // one sweep: the candidates at or above the bound are compacted into the staging slots (as the cut below does, so that
-        // the keys leave in full wavefront stores); more than m of them means the row needs its own cut after all
-        int cnt = 0;
-        const uint32_t nflat = 0xFFFFFFFFu - flat0 - (uint32_t)lane * 4u;
-#pragma unroll
-        for (int i = 0; i < VEC * 4; i++) {
-            const bool hit = x[i] >= sstar;  // padding is -inf
-            const unsigned long long mk = __ballot(hit);
-            const unsigned long long st = ((unsigned long long)__float_as_uint(x[i] + 0.0f) << 32) | (nflat - (uint32_t)((i / 4) * 256 + (i % 4)));
-            const int at = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(mk >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mk, 0));
-            if (hit && at < m) stage[at] = st;
-            cnt += __popcll(mk);
-        }
-        const int take = cnt <= m ? cnt : m;
-        int base = 0;
-        if (lane == 0) base = atomicAdd(&req_count[req], take);
-        base = __shfl(base, 0, 64);
-        dst = cand + req * ((int64_t)n * m) + base;
-        if (cnt <= m) {
-            for (int i = lane; i < cnt; i += 64) dst[i] = staged_to_key(stage[i]);
-            return;
-        }
+    for (int i = 0; i < NX; i++) {
+        x[i] = c + (x[i] - lse);
+        mn = fminf(mn, (FULL || wave_tok<E>(i, lane) < V) ? x[i] : INFINITY);
     }
     if (m >= V) {  // nothing to cut: every token is a candidate
 #pragma unroll
-        for (int j = 0; j < VEC; j++)
-            if (FULL || (j * 64 + lane) * 4 < V) {
-#pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    const int v = (j * 64 + lane) * 4 + e;
-                    dst[v] = pack_candidate(x[j * 4 + e], flat0 + (uint32_t)v);
-                }
-            }
+        for (int i = 0; i < NX; i++) {
+            const int v = wave_tok<E>(i, lane);
+            if (FULL || v < V) dst[v] = pack_candidate(x[i], flat0 + (uint32_t)v);
+        }
         return;
     }
     // 1. histogram of the scores over equal-width bins of [lo, hi]; the bin index is monotone in the score
-    const float lo = c + (mn - lse), hi = c + (mx - lse);
+    const float lo = -wave_max(-mn), hi = c + (mx - lse);
     const float inv_w = (hi > lo) ? ((float)WROW_BINS - 0.01f) / (hi - lo) : 0.0f;
     const float k0 = -lo * inv_w;
 #pragma unroll
     for (int i = 0; i < 4; i++) ((int4 *)hist)[i * 64 + lane] = make_int4(0, 0, 0, 0);
 #pragma unroll
-    for (int i = 0; i < VEC * 4; i++) {
+    for (int i = 0; i < NX; i++) {
         const uint32_t bi = min((uint32_t)__builtin_fmaf(x[i], inv_w, k0), (uint32_t)(WROW_BINS - 1));  // negative and NaN convert to 0
-        if (FULL || ((i / 4) * 64 + lane) * 4 < V) atomicAdd(&hist[bi], 1);
+        if (FULL || wave_tok<E>(i, lane) < V) atomicAdd(&hist[bi], 1);
     }
     // 2. lane l owns bins 1023-16l .. 1008-16l; inclusive scan from the top bin down finds the bin T of the m-th best score
     int h[16];
@@ -512,26 +469,25 @@ __global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restri
     const int src_lane = __ffsll((long long)__ballot(owner)) - 1;
     const int T = __shfl(selT, src_lane, 64), krem = __shfl(selK, src_lane, 64), cntT = __shfl(selC, src_lane, 64);
     if (cntT > WROW_LIST) {  // crowded threshold bin (e.g. all logits equal): exact radix selection
-        float sc[VEC * 4];  // a copy, so that only this branch keeps the scores in addressable memory
+        float sc[NX];  // a copy, so that only this branch keeps the scores in addressable memory
 #pragma unroll
-        for (int i = 0; i < VEC * 4; i++) sc[i] = x[i];
-        select_row_radix_wave<VEC>(sc, V, m, flat0, stage);
+        for (int i = 0; i < NX; i++) sc[i] = x[i];
+        select_row_radix_wave<VEC, E>(sc, V, m, flat0, stage);
     } else {
         // 3. bins above T go straight to the staged output, bin T to the list (over the dead histogram) for exact ranking
         const int n_gt = m - krem;
         int base_gt = 0, base_eq = 0;
-        const uint32_t nflat = 0xFFFFFFFFu - flat0 - (uint32_t)lane * 4u;
         // The bins are recomputed, not kept: opaque copies of the two constants stop the compiler from holding
-        // all VEC*4 bin indices of the histogram pass in registers until here.
+        // all NX bin indices of the histogram pass in registers until here.
         float inv_w2 = inv_w, k02 = k0;
         asm volatile("" : "+v"(inv_w2), "+v"(k02));
 #pragma unroll
-        for (int i = 0; i < VEC * 4; i++) {
+        for (int i = 0; i < NX; i++) {
             const int bi = (int)min((uint32_t)__builtin_fmaf(x[i], inv_w2, k02), (uint32_t)(WROW_BINS - 1));
-            const bool ok = FULL || ((i / 4) * 64 + lane) * 4 < V;
+            const bool ok = FULL || wave_tok<E>(i, lane) < V;
             const bool gt = ok && bi > T, eq = ok && bi == T;
             const unsigned long long mg = __ballot(gt), me = __ballot(eq);
-            const unsigned long long st = ((unsigned long long)__float_as_uint(x[i] + 0.0f) << 32) | (nflat - (uint32_t)((i / 4) * 256 + (i % 4)));
+            const unsigned long long st = ((unsigned long long)__float_as_uint(x[i] + 0.0f) << 32) | (nflat - (uint32_t)((i / E) * 64 * E + (i % E)));
             if (gt) stage[base_gt + __builtin_amdgcn_mbcnt_hi((uint32_t)(mg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mg, 0))] = st;
             base_gt += __popcll(mg);
             if (me != 0) {
@@ -548,6 +504,242 @@ __global__ __launch_bounds__(256, 3) void select_rows_wave(const float *__restri
         }
     }
     for (int i = lane; i < m; i += 64) dst[i] = staged_to_key(stage[i]);
+}
+
+// One row of logits, already in registers (x[i]: token wave_tok<E>(i, lane); padding -inf), through the cut.  Returns when the
+// row's candidates are written.
+template <int VEC, bool FULL, int E>
+__device__ __forceinline__ void select_one_row_wave(float (&x)[VEC * 4], int64_t vrow, int64_t row, const float *__restrict__ cum, int n, int V,
+                                                    int m, unsigned long long *__restrict__ cand, const unsigned long long *__restrict__ bound,
+                                                    int *__restrict__ req_count, unsigned long long *list, int lane, int64_t dst_at) {
+    constexpr int NX = VEC * 4;
+    unsigned long long *stage = list + 512;
+    const float c = cum ? cum[row] : 0.0f;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NX; i++) mx = fmaxf(mx, x[i]);
+    mx = wave_max_dpp(mx);
+    const float mxl = mx * 1.4426950408889634f;
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NX; i++) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(x[i], 1.4426950408889634f, -mxl));  // padding gives 0
+    const float lse = mx + __logf(wave_sum_dpp(sum));
+
+    unsigned long long *dst = cand + (dst_at >= 0 ? dst_at : vrow * (int64_t)m);  // dst_at: where a listed row reserved its m slots
+    const uint32_t flat0 = (uint32_t)((row % n) * (int64_t)V);
+    // low word of a staged candidate: 0xFFFFFFFF - (flat0 + token)
+    const uint32_t nflat = 0xFFFFFFFFu - flat0 - (uint32_t)lane * (uint32_t)E;
+    if (bound) {
+        // Request-level bound: the request's first row alone has m candidates at or above `bound`, so nothing below it can
+        // survive the request's selection.  Rows that have at most m candidates there write exactly those - usually far
+        // fewer than m - and skip the histogram; the others fall through to the row's own top-m cut.
+        const int64_t req = row / n;
+        const float sstar = key_score((uint32_t)(bound[req] >> 32));
+        // score(x) = c + (x - lse) >= sstar is tested exactly, but only on the logits that pass a threshold in the logit domain
+        // placed a few roundings below the exact one (every candidate at or above the bound passes it)
+        const float t0 = (sstar - c) + lse;
+        const float thr = t0 - 1e-6f * (fabsf(sstar) + fabsf(c) + fabsf(lse) + fabsf(t0));
+        int cnt = 0;
+        constexpr int CH = 16;  // logits per test: one wave-uniform branch per CH elements, taken for the few chunks that hold a candidate
+#pragma unroll
+        for (int i0 = 0; i0 < NX; i0 += CH) {
+            unsigned long long any = 0;
+#pragma unroll
+            for (int u = 0; u < CH; u++) any |= __ballot(x[i0 + u] >= thr);  // padding is -inf
+            if (any != 0) {
+#pragma unroll
+                for (int u = 0; u < CH; u++) {
+                    const int i = i0 + u;
+                    const float sc = c + (x[i] - lse);
+                    const bool hit = sc >= sstar;
+                    const unsigned long long mk = __ballot(hit);
+                    const unsigned long long st = ((unsigned long long)__float_as_uint(sc + 0.0f) << 32) | (nflat - (uint32_t)((i / E) * 64 * E + (i % E)));
+                    const int at = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(mk >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mk, 0));
+                    if (hit && at < m) stage[at] = st;
+                    cnt += __popcll(mk);
+                }
+            }
+        }
+        const int take = cnt <= m ? cnt : m;
+        int base = 0;
+        if (lane == 0) base = atomicAdd(&req_count[req], take);
+        base = __shfl(base, 0, 64);
+        dst = cand + req * ((int64_t)n * m) + base;
+        if (cnt <= m) {
+            for (int i = lane; i < cnt; i += 64) dst[i] = staged_to_key(stage[i]);
+            return;
+        }
+    }
+    select_row_own_cut<VEC, FULL, E>(x, c, mx, lse, dst, flat0, nflat, V, m, list, lane);
+}
+
+// FULL: V == VEC*256, every register holds a token (the validity tests fold away).
+// row_step: the launch visits rows 0, row_step, 2 row_step, ... of the logits (row_step = n: the first beam of every request).
+// bound / req_count (both or neither): per request, a key no survivor can lie below; the launch then writes only
+// the candidates that reach it (at most the row's m best), compacted per request behind a running count.
+// todo / todo_count (both or neither; then without bound): the launch visits only the listed rows {row, slot}; each gets its
+// own cut, written at slot `slot` of its request's segment.  Wavefronts walk their rows with the launch's stride.
+template <int VEC, bool FULL, typename LT>
+__global__ __launch_bounds__(256, 3) void select_rows_wave(const LT *__restrict__ logits, const float *__restrict__ cum, int64_t rows, int n, int V,
+                                                          int m, unsigned long long *__restrict__ cand, int64_t row_step,
+                                                          const unsigned long long *__restrict__ bound, int *__restrict__ req_count,
+                                                          const int2 *__restrict__ todo, const int *__restrict__ todo_count) {
+    constexpr int E = LogitPiece<LT>::E, NX = VEC * 4, G = NX / E;
+    extern __shared__ unsigned long long wave_lds[];  // per wavefront: 512 slots of histogram / list, then m slots of staged output
+    const int lane = threadIdx.x % 64, wv = threadIdx.x / 64;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const int64_t count = todo ? (int64_t)*todo_count : rows;
+    unsigned long long *list = wave_lds + (size_t)wv * ((512 + m + 1) & ~1);  // even number of 8-byte slots: 16-byte accesses stay aligned
+    // whole wavefronts leave the loop; nothing below synchronises across wavefronts
+    for (int64_t at = (int64_t)blockIdx.x * 4 + wv; at < count; at += nwaves) {
+        int64_t vrow = at, dst_at = -1;
+        if (todo) {
+            const int2 t = todo[at];
+            vrow = t.x;
+            dst_at = (vrow / n) * ((int64_t)n * m) + t.y;
+        }
+        const uint4 *z = (const uint4 *)(logits + vrow * row_step * (int64_t)V);
+        float x[NX];
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            if (FULL || (g * 64 + lane) * E < V) {
+                LogitPiece<LT>::unpack(z[g * 64 + lane], &x[g * E]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < E; e++) x[g * E + e] = -INFINITY;
+            }
+        }
+        select_one_row_wave<VEC, FULL, E>(x, vrow, vrow * row_step, cum, n, V, m, cand, bound, req_count, list, lane, dst_at);
+    }
+}
+
+// The bounded pass over half-precision logits.  A row stays packed (raw[g]: tokens (g*64 + lane)*8 .. +7; pieces past V
+// hold -inf): maximum, log-sum-exp and the sweep for candidates at or above the request's bound read the halves in
+// place, and each wavefront asks for its next row before it works on the current one, so the memory latency hides behind the
+// arithmetic.  A row with more than m candidates at the bound reserves m slots and is put on the list for
+// select_rows_wave, which gives it its own cut; this kernel carries none of that code or its registers.
+template <int VEC, bool FULL>
+__global__ __launch_bounds__(256, VEC >= 32 ? 2 : (VEC >= 16 ? 3 : 4)) void select_rows_sweep_f16(
+    const _Float16 *__restrict__ logits, const float *__restrict__ cum, int64_t rows, int n, int V, int m, unsigned long long *__restrict__ cand,
+    const unsigned long long *__restrict__ bound, int *__restrict__ req_count, int2 *__restrict__ todo, int *__restrict__ todo_count) {
+    constexpr int NX = VEC * 4, E = 8, G = NX / E;
+    extern __shared__ unsigned long long wave_lds[];  // per wavefront: m slots of staged output
+    // The row index is made a scalar of the wavefront (rows < 2^31, checked by the host): its cumulative score and bound then
+    // come through scalar loads, which do not queue behind the vector loads of the next row.
+    const int lane = threadIdx.x % 64, wv = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    const uint32_t nwaves = gridDim.x * 4u;
+    uint32_t row = blockIdx.x * 4u + (uint32_t)wv;
+    if (row >= (uint64_t)rows) return;  // whole wavefronts leave; nothing below synchronises across wavefronts
+    unsigned long long *stage = wave_lds + (size_t)wv * m;
+    auto request_row = [&](uint32_t r, uint4 (&raw)[G]) {
+        const uint4 *z = (const uint4 *)(logits + (int64_t)r * V);
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            if (FULL || (g * 64 + lane) * E < V) raw[g] = z[g * 64 + lane];
+            else raw[g] = make_uint4(0xFC00FC00u, 0xFC00FC00u, 0xFC00FC00u, 0xFC00FC00u);  // halves of -inf
+        }
+    };
+    // per row: request, beam, cumulative score and the bound's score, fetched one row ahead like the logits
+    auto row_scalars = [&](uint32_t r, uint32_t &req, uint32_t &beam, float &c, float &sstar) {
+        req = r / (uint32_t)n;
+        beam = r % (uint32_t)n;
+        c = cum ? cum[r] : 0.0f;
+        sstar = key_score((uint32_t)(bound[req] >> 32));
+    };
+    auto pk_max = [](halfx2 a, halfx2 b) {  // (the plain instruction: the generic maximum first quiets both operands)
+        halfx2 r;
+        asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+        return r;
+    };
+    uint4 raw[G];
+    request_row(row, raw);
+    uint32_t req, beam;
+    float c, sstar;
+    row_scalars(row, req, beam, c, sstar);
+    for (;;) {
+        const uint64_t next = (uint64_t)row + nwaves;
+        const bool more = next < (uint64_t)rows;
+        const uint32_t ahead = more ? (uint32_t)next : row;
+        uint4 nxt[G];
+        // (unconditional - the last row is asked for twice: a branch here would make the compiler wait for these loads at the
+        // first use of the current row, as if they had been skipped)
+        request_row(ahead, nxt);
+        uint32_t req_n, beam_n;
+        float c_n, sstar_n;
+        row_scalars(ahead, req_n, beam_n, c_n, sstar_n);
+        __builtin_amdgcn_sched_barrier(0);  // the loads go out here, not where the instruction scheduler finds the registers cheapest
+
+        halfx2 pmax[G];  // per piece: the maximum of its even and of its odd tokens
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            const halfx8 v = __builtin_bit_cast(halfx8, raw[g]);
+            const halfx2 p0 = {v[0], v[1]}, p1 = {v[2], v[3]}, p2 = {v[4], v[5]}, p3 = {v[6], v[7]};
+            pmax[g] = pk_max(pk_max(p0, p1), pk_max(p2, p3));
+        }
+        halfx2 rm = pmax[0];
+#pragma unroll
+        for (int g = 1; g < G; g++) rm = pk_max(rm, pmax[g]);
+        const float lane_mx = fmaxf((float)rm[0], (float)rm[1]);
+        const float mx = wave_max_dpp(lane_mx);
+        const float mxl = mx * 1.4426950408889634f;
+        float sum = 0.0f;
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+            const halfx8 v = __builtin_bit_cast(halfx8, raw[g]);
+#pragma unroll
+            for (int e = 0; e < E; e++) sum += __builtin_amdgcn_exp2f(__builtin_fmaf((float)v[e], 1.4426950408889634f, -mxl));  // padding gives 0
+        }
+        const float lse = mx + __logf(wave_sum_dpp(sum));
+        // (opaque to the compiler: otherwise it keeps the NX widened logits of the sum above in registers for the sweep below)
+#pragma unroll
+        for (int g = 0; g < G; g++) asm volatile("" : "+v"(raw[g].x), "+v"(raw[g].y), "+v"(raw[g].z), "+v"(raw[g].w));
+
+        // score(x) = c + (x - lse) >= sstar is tested exactly, but only inside the pieces whose maximum passes a threshold in the
+        // logit domain placed a few roundings below the exact one (every candidate at or above the bound passes it); most
+        // rows of a request's weaker beams have no such piece at all
+        uint32_t nflat = 0xFFFFFFFFu - beam * (uint32_t)V - (uint32_t)lane * (uint32_t)E;
+        asm volatile("" : "+v"(nflat));  // (opaque: keeps the compiler from carrying NX row-independent parts of the token words across rows)
+        const float t0 = (sstar - c) + lse;
+        const float thr = t0 - 1e-6f * (fabsf(sstar) + fabsf(c) + fabsf(lse) + fabsf(t0));
+        int cnt = 0;
+        if (__ballot(lane_mx >= thr) != 0) {
+#pragma unroll
+            for (int g = 0; g < G; g++) {
+                const unsigned long long any = __ballot(fmaxf((float)pmax[g][0], (float)pmax[g][1]) >= thr);
+                if (any != 0) {
+                    const halfx8 v = __builtin_bit_cast(halfx8, raw[g]);
+#pragma unroll
+                    for (int e = 0; e < E; e++) {
+                        const float sc = c + ((float)v[e] - lse);
+                        const bool hit = sc >= sstar;
+                        const unsigned long long mk = __ballot(hit);
+                        const unsigned long long st = ((unsigned long long)__float_as_uint(sc + 0.0f) << 32) | (nflat - (uint32_t)(g * 64 * E + e));
+                        const int at = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(mk >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mk, 0));
+                        if (hit && at < m) stage[at] = st;
+                        cnt += __popcll(mk);
+                    }
+                }
+            }
+        }
+        if (cnt > 0) {  // (wavefront-uniform)
+            const int take = cnt <= m ? cnt : m;
+            int base = 0;
+            if (lane == 0) {
+                base = atomicAdd(&req_count[req], take);
+                if (cnt > m) todo[atomicAdd(todo_count, 1)] = make_int2((int)row, base);  // its m slots are filled by the listed pass
+            }
+            base = __shfl(base, 0, 64);
+            if (cnt <= m) {
+                unsigned long long *dst = cand + (int64_t)req * ((int64_t)n * m) + base;
+                for (int i = lane; i < cnt; i += 64) dst[i] = staged_to_key(stage[i]);
+            }
+        }
+        if (!more) break;
+#pragma unroll
+        for (int g = 0; g < G; g++) raw[g] = nxt[g];
+        row = (uint32_t)next;
+        req = req_n; beam = beam_n; c = c_n; sstar = sstar_n;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -751,39 +943,94 @@ __global__ __launch_bounds__(SELB_THREADS) void select_request(const unsigned lo
 
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-template <int VEC, bool FULL>
-static int launch_rows_wave_kind(unsigned grid, size_t lds, hipStream_t st, const float *logits, const float *cum, int64_t rows, int n,
-                                 int V, int m, unsigned long long *cand, int64_t row_step, const unsigned long long *bound, int *req_count) {
-    auto kern = select_rows_wave<VEC, FULL>;
+// what the row kernels of one selection share
+struct RowsLaunch {
+    hipStream_t st;
+    const void *logits;
+    int logits_f16;
+    const float *cum;
+    int n, V, m;
+    unsigned long long *cand;
+    const unsigned long long *bound;
+    int *req_count;
+    int2 *todo;
+    int *todo_count;
+};
+static int compute_units() {
+    static int n_cu = 0;
+    if (!n_cu) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+        n_cu = prop.multiProcessorCount;
+    }
+    return n_cu;
+}
+// mode 0: every row (stride row_step) its own cut or, with a bound, the bounded cut; mode 1: the listed rows' own cuts
+template <int VEC, bool FULL, typename LT>
+static int launch_rows_wave_kind(const RowsLaunch &a, int64_t rows, int64_t row_step, int mode) {
+    auto kern = select_rows_wave<VEC, FULL, LT>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (512 + GR4AD_MAX_BEAM + 2) * 8) != hipSuccess) return GR4AD_EHIP;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
+    const size_t lds = 4 * (size_t)((512 + a.m + 1) & ~1) * sizeof(unsigned long long);  // <= 4 * (4 KB + 32 KB)
+    int64_t grid = ceil_div64(rows, 4);  // one wavefront per row, four rows per workgroup
+    if (mode == 1) {  // the list is short as a rule: a few workgroups per compute unit walk it
+        const int n_cu = compute_units();
+        if (!n_cu) return GR4AD_EHIP;
+        if (grid > (int64_t)n_cu * 4) grid = (int64_t)n_cu * 4;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, a.st, (const LT *)a.logits, a.cum, rows, a.n, a.V, a.m, a.cand, row_step,
+                       mode == 1 ? nullptr : a.bound, mode == 1 ? nullptr : a.req_count, mode == 1 ? (const int2 *)a.todo : nullptr,
+                       mode == 1 ? (const int *)a.todo_count : nullptr);
+    return GR4AD_OK;
+}
+// mode 2: the bounded pass over packed half-precision logits, which lists the rows that need their own cut
+template <int VEC, bool FULL>
+static int launch_rows_sweep_kind(const RowsLaunch &a, int64_t rows) {
+    auto kern = select_rows_sweep_f16<VEC, FULL>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * GR4AD_MAX_BEAM * 8) != hipSuccess) return GR4AD_EHIP;
+        attr_done = true;
+    }
+    const int n_cu = compute_units();
+    if (!n_cu) return GR4AD_EHIP;
+    // wavefronts walk the rows with the launch's stride
+    const size_t lds = 4 * (size_t)a.m * sizeof(unsigned long long);
+    int64_t grid = ceil_div64(rows, 4);
+    if (grid > (int64_t)n_cu * 8) grid = (int64_t)n_cu * 8;  // (a few rounds of resident workgroups: measured faster than exactly one)
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, a.st, (const _Float16 *)a.logits, a.cum, rows,
+                       a.n, a.V, a.m, a.cand, a.bound, a.req_count, a.todo, a.todo_count);
     return GR4AD_OK;
 }
 template <int VEC>
-static int launch_rows_wave(unsigned grid, size_t lds, hipStream_t st, const float *logits, const float *cum, int64_t rows, int n, int V,
-                            int m, unsigned long long *cand, int64_t row_step, const unsigned long long *bound, int *req_count) {
-    if (V == VEC * 256) return launch_rows_wave_kind<VEC, true>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
-    return launch_rows_wave_kind<VEC, false>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
+static int launch_rows_vec(const RowsLaunch &a, int64_t rows, int64_t row_step, int mode) {
+    const bool full = a.V == VEC * 256;
+    if (mode == 2) return full ? launch_rows_sweep_kind<VEC, true>(a, rows) : launch_rows_sweep_kind<VEC, false>(a, rows);
+    if (a.logits_f16)
+        return full ? launch_rows_wave_kind<VEC, true, _Float16>(a, rows, row_step, mode) : launch_rows_wave_kind<VEC, false, _Float16>(a, rows, row_step, mode);
+    return full ? launch_rows_wave_kind<VEC, true, float>(a, rows, row_step, mode) : launch_rows_wave_kind<VEC, false, float>(a, rows, row_step, mode);
 }
-static int launch_rows_wave_any(hipStream_t st, const float *logits, const float *cum, int64_t rows, int n, int V, int m,
-                                unsigned long long *cand, int64_t row_step, const unsigned long long *bound, int *req_count) {
-    const size_t lds = 4 * (size_t)((512 + m + 1) & ~1) * sizeof(unsigned long long);  // <= 4 * (4 KB + 32 KB)
-    const unsigned grid = (unsigned)ceil_div64(rows, 4);
-    if (V <= 1024) return launch_rows_wave<4>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
-    if (V <= 2048) return launch_rows_wave<8>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
-    if (V <= 4096) return launch_rows_wave<16>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
-    return launch_rows_wave<32>(grid, lds, st, logits, cum, rows, n, V, m, cand, row_step, bound, req_count);
+static int launch_rows(const RowsLaunch &a, int64_t rows, int64_t row_step, int mode) {
+    if (a.V <= 1024) return launch_rows_vec<4>(a, rows, row_step, mode);
+    if (a.V <= 2048) return launch_rows_vec<8>(a, rows, row_step, mode);
+    if (a.V <= 4096) return launch_rows_vec<16>(a, rows, row_step, mode);
+    return launch_rows_vec<32>(a, rows, row_step, mode);
 }
 
-// bound[b] = smallest of the m keys the first row of request b kept (wavefront per request); count[b] = 0
+// Half-precision logits are taken by the wavefront kernel only: 16-byte pieces of 8 values.
+bool select_takes_f16(int V) { return V >= 8 && V <= 8192 && V % 8 == 0; }
+
+// bound[b] = smallest of the m keys the first row of request b kept (wavefront per request); count[b] = 0; list count = 0
 __global__ __launch_bounds__(256) void request_bound_kernel(const unsigned long long *__restrict__ cand0, int m, int B,
-                                                            unsigned long long *__restrict__ bound, int *__restrict__ req_count) {
+                                                            unsigned long long *__restrict__ bound, int *__restrict__ req_count,
+                                                            int *__restrict__ todo_count) {
     const int lane = threadIdx.x % 64;
     const int b = blockIdx.x * 4 + threadIdx.x / 64;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *todo_count = 0;  // the list of rows that need their own cut starts empty
     if (b >= B) return;
     unsigned long long mn = ~0ull;
     for (int i = lane; i < m; i += 64) { const unsigned long long k = cand0[(int64_t)b * m + i]; mn = k < mn ? k : mn; }
@@ -796,18 +1043,22 @@ __global__ __launch_bounds__(256) void fill_count_kernel(int *__restrict__ req_c
     if (b < B) req_count[b] = v;
 }
 
-// workspace: candidates [B][n*m] keys, then the first rows' cuts [B][m], the request bounds [B] and the request counts [B]
+// workspace: candidates [B][n*m] keys, then the first rows' cuts [B][m], the request bounds [B], the request counts [B], the
+// count of listed rows (one int in 256 bytes) and the list {row, slot} [B*n]
 static inline size_t sel_ws_cand(int B, int n, int m) { return align256((size_t)B * n * m * sizeof(unsigned long long)); }
 static inline size_t sel_ws_cand0(int B, int m) { return align256((size_t)B * m * sizeof(unsigned long long)); }
 size_t select_workspace_bytes(int B, int n, int V, int k) {
     int m = k < V ? k : V;
-    return sel_ws_cand(B, n, m) + sel_ws_cand0(B, m) + align256((size_t)B * sizeof(unsigned long long)) + align256((size_t)B * sizeof(int));
+    return sel_ws_cand(B, n, m) + sel_ws_cand0(B, m) + align256((size_t)B * sizeof(unsigned long long)) + align256((size_t)B * sizeof(int)) + 256 +
+           align256((size_t)B * n * sizeof(int2));
 }
 
-int launch_select(const float *logits, const float *cum, int B, int n, int V, int k, void *ws, size_t ws_bytes, int32_t *parent,
+int launch_select(const void *logits_any, int logits_f16, const float *cum, int B, int n, int V, int k, void *ws, size_t ws_bytes, int32_t *parent,
                   int32_t *tok, float *score, const int32_t *sid_old, int32_t *sid_new, const int32_t *anc_old, int32_t *anc_new, int T, int level,
                   hipStream_t st) {
     if (B <= 0 || n <= 0 || V <= 0 || k <= 0 || (int64_t)k > (int64_t)n * V) return GR4AD_EINVAL;
+    if (logits_f16 && (!select_takes_f16(V) || ((uintptr_t)logits_any % 16))) return GR4AD_EUNSUPPORTED;
+    const float *logits = (const float *)logits_any;  // (float32 unless logits_f16: only the wavefront kernel then reads them)
     if (k > GR4AD_MAX_BEAM || V > GR4AD_MAX_CODEBOOK || (int64_t)n * V >= 0x7fffffffLL) return GR4AD_EUNSUPPORTED;
     if (ws_bytes < select_workspace_bytes(B, n, V, k) || ((uintptr_t)ws % 8)) return GR4AD_EWORKSPACE;
     const int m = k < V ? k : V;
@@ -817,6 +1068,8 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
     unsigned long long *cand0 = (unsigned long long *)((char *)ws + sel_ws_cand(B, n, m));
     unsigned long long *bound = (unsigned long long *)((char *)cand0 + sel_ws_cand0(B, m));
     int *req_count = (int *)((char *)bound + align256((size_t)B * sizeof(unsigned long long)));
+    int *todo_count = (int *)((char *)req_count + align256((size_t)B * sizeof(int)));
+    int2 *todo = (int2 *)((char *)todo_count + 256);
     const bool wave_path = V <= 8192 && V % 4 == 0 && ((uintptr_t)logits % 16) == 0;
     // Request-level bound (several rows per request, cut smaller than the row): the first row of a request holds its best
     // beam; the m-th best candidate of that row is a score no survivor of the request can lie below.
@@ -824,18 +1077,31 @@ int launch_select(const float *logits, const float *cum, int B, int n, int V, in
     {
         // algorithmic bytes: every logit once; the candidates written depend on the data (between k per request and m per row):
         // the lower bound is counted when the request-level bound is in use
-        ProfScope ps(KC_SELECT_ROWS, st, 0.0, (double)rows * V * 4 + (bounded ? (double)B * k : (double)rows * m) * 8);
+        ProfScope ps(KC_SELECT_ROWS, st, 0.0, (double)rows * V * (logits_f16 ? 2 : 4) + (bounded ? (double)B * k : (double)rows * m) * 8);
         if (wave_path) {
-            // one wavefront per row, four rows per workgroup
+            const RowsLaunch a = {st, logits_any, logits_f16, cum, n, V, m, nullptr, bound, req_count, todo, todo_count};
+            RowsLaunch first = a, all = a;
+            first.cand = cand0;
+            first.bound = nullptr;
+            first.req_count = nullptr;
+            all.cand = cand;
             int s;
             if (bounded) {
-                if ((s = launch_rows_wave_any(st, logits, cum, B, n, V, m, cand0, n, nullptr, nullptr))) return s;
+                if ((s = launch_rows(first, B, n, 0))) return s;  // the first row of every request, cut on its own
                 GR4AD_LAUNCH_CHECK();
-                hipLaunchKernelGGL(request_bound_kernel, dim3((unsigned)((B + 3) / 4)), dim3(256), 0, st, cand0, m, B, bound, req_count);
+                hipLaunchKernelGGL(request_bound_kernel, dim3((unsigned)((B + 3) / 4)), dim3(256), 0, st, cand0, m, B, bound, req_count, todo_count);
                 GR4AD_LAUNCH_CHECK();
-                if ((s = launch_rows_wave_any(st, logits, cum, rows, n, V, m, cand, 1, bound, req_count))) return s;
+                if (logits_f16) {
+                    if ((s = launch_rows(all, rows, 1, 2))) return s;
+                    GR4AD_LAUNCH_CHECK();
+                    if ((s = launch_rows(all, rows, 1, 1))) return s;
+                } else {
+                    if ((s = launch_rows(all, rows, 1, 0))) return s;
+                }
             } else {
-                if ((s = launch_rows_wave_any(st, logits, cum, rows, n, V, m, cand, 1, nullptr, nullptr))) return s;
+                all.bound = nullptr;
+                all.req_count = nullptr;
+                if ((s = launch_rows(all, rows, 1, 0))) return s;
             }
         } else {
             const size_t stage_bytes = (size_t)m * sizeof(unsigned long long);  // <= 32 KB (GR4AD_MAX_BEAM)
@@ -896,7 +1162,7 @@ extern "C" int gr4ad_op_select_static(const float *logits, const float *cum, int
         if (e != hipSuccess || !p) return gr4ad_set_thread_error(GR4AD_EHIP, "gr4ad_op_select_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
         g_scratch_ptr[dev] = p;
     }
-    const int s = launch_select(logits, cum, B, n, V, k, g_scratch_ptr[dev], (size_t)GR4AD_SELECT_STATIC_BYTES, parent, tok, score, nullptr, nullptr,
+    const int s = launch_select(logits, 0, cum, B, n, V, k, g_scratch_ptr[dev], (size_t)GR4AD_SELECT_STATIC_BYTES, parent, tok, score, nullptr, nullptr,
                                 nullptr, nullptr, 0, 0, (hipStream_t)hip_stream);
     return s == GR4AD_OK ? s : gr4ad_set_thread_error(s, "gr4ad_op_select_static: selection failed: %s", gr4ad_strerror(s));
 }

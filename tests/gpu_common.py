@@ -189,7 +189,9 @@ def value_rounding_model(w, W, batch=None):
     kw, Wv = synth.value_model(w, W)
     w2 = copy.copy(w)
     w2.T, w2.V, w2.beam, w2.Ve = kw["T"], list(kw["V"]), list(w.beam) + [w.beam[-1]], 0
-    return RoundedModel(w2, Wv, batch=w.B if batch is None else batch)
+    model = RoundedModel(w2, Wv, batch=w.B if batch is None else batch)
+    model.value_level = w.T
+    return model
 
 
 def judge_value(w, W, X, lens, sid, lp, val, requests, tol=None, model=None):

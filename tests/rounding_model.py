@@ -8,7 +8,8 @@ function at exactly the places where the library stores a narrower type:
 
     norm outputs, q, context keys/values, attention probabilities (matrix-core kernel: unnormalised, relative to a
     lazily refreshed maximum; absorbed form: normalised) and outputs, self-attention q/k/v and outputs, FFN hidden
-    rows, the gated embedding of Fuse; float32 for the residual stream, the Fuse tables and the logits.
+    rows, the gated embedding of Fuse; float32 for the residual stream, the Fuse tables and the logits - except the
+    logits of large levels, which the persistent GEMM hands to the selection in IEEE half precision.
 
 It shares no code with the library or with the C oracle.  With every rounding switched off it IS the definition,
 and is pinned to the C oracle in that mode (tests/test_rounding_model.py); with the roundings on, its distance from
@@ -27,6 +28,10 @@ def _f32(x):
 
 def _bf16(x):
     return synth.round_bf16(np.asarray(x, np.float64).astype(np.float32)).astype(np.float64)
+
+
+def _f16(x):
+    return np.asarray(x, np.float64).astype(np.float32).astype(np.float16).astype(np.float64)
 
 
 def _ident(x):
@@ -52,6 +57,7 @@ class RoundedModel:
         self.fp8 = bool(w.fp8 if fp8 is None else fp8)
         self.scale_arith = scale_arith
         self.batch = w.B if batch is None else batch
+        self.value_level = None  # 0-based level that is an eCPM-token step (its float32 distribution is the output: never half logits)
         d, H = w.d, w.H
         self.dh = d // H
         bf = act == "bf16" and w.dtype == "bf16"
@@ -112,6 +118,16 @@ class RoundedModel:
         w = self.w
         return (self.store_bf16 and not self.fp8 and rows >= 8192 and w.d % 256 == 0 and w.F % 64 == 0 and w.F >= 256 and
                 (n_cls == 0 or (n_cls >= 256 and n_cls % 4 == 0)))
+
+    def logits_f16(self, rows, V):
+        """True if the classifier of a level with this many rows leaves its logits in half precision (the persistent GEMM runs
+        it and the wavefront selection kernel takes the codebook size)."""
+        d = self.w.d
+        if not self.store_bf16 or V % 8 or not 256 <= V <= 8192:
+            return False
+        if self.fp8:
+            return rows >= 64 and d % 128 == 0 and d >= 384
+        return rows >= 8192 and d % 64 == 0 and d >= 192
 
     def norm_operand(self, x, gain, fold, f8):
         """What the projection after RMSNorm(x) multiplies, and the row factor applied to its product afterwards."""
@@ -265,7 +281,7 @@ class _Request:
             z = m._proj(a, rf, m.cls[p])
             if m.bias[p] is not None:
                 z = z + m.bias[p]
-            z = m.f32(z)
+            z = _f16(z) if p != m.value_level and m.logits_f16(m.batch * rows[p], w.V[p]) else m.f32(z)
             zmax = z.max(axis=-1, keepdims=True)
             lp = z - (zmax + np.log(np.exp(z - zmax).sum(axis=-1, keepdims=True)))
             if p < t - 1:

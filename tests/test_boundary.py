@@ -92,10 +92,11 @@ def test_init_rejects_null_pointers():
 def test_select_workspace_formula():
     L = binding.lib()
     def expect(B, n, V, k):
-        # candidates [B][n*m] 64-bit keys, the first rows' cuts [B][m], request bounds [B] (64-bit), request counts [B] (32-bit)
+        # candidates [B][n*m] 64-bit keys, the first rows' cuts [B][m], request bounds [B] (64-bit), request counts [B] (32-bit),
+        # the count of rows listed for their own cut (256 bytes) and the list [B*n] of {row, slot} pairs
         m = min(k, V)
         r = lambda x: (x + 255) // 256 * 256
-        return r(B * n * m * 8) + r(B * m * 8) + r(B * 8) + r(B * 4)
+        return r(B * n * m * 8) + r(B * m * 8) + r(B * 8) + r(B * 4) + 256 + r(B * n * 8)
     assert L.gr4ad_op_select_workspace_bytes(3, 5, 100, 7) == expect(3, 5, 100, 7)
     assert L.gr4ad_op_select_workspace_bytes(3, 5, 4, 7) == expect(3, 5, 4, 7)
     assert L.gr4ad_op_select_workspace_bytes(0, 5, 4, 7) == 0
@@ -105,6 +106,7 @@ def test_ops_reject_bad_arguments_without_a_gpu():
     L = binding.lib()
     assert L.gr4ad_op_linear(0, None, None, None, None, 1, 1, 1, 0, None) == -1
     assert L.gr4ad_op_select(None, None, 1, 1, 1, 1, None, 0, None, None, None, None) == -1
+    assert L.gr4ad_op_select_f16(None, None, 1, 1, 8, 1, None, 0, None, None, None, None) == -1
     assert L.gr4ad_op_cross_attention(0, None, None, None, None, 1, 1, 1, 8, 1, None, 0, None) == -1
     assert L.gr4ad_op_cross_attention_workspace_bytes(1, 2, 100, 128, 2) == 2 * 128 * 128 * 2   # bf16, dh 64: S padded to 128
     assert L.gr4ad_op_cross_attention_workspace_bytes(0, 2, 100, 128, 2) == 0                   # float32 runs on the plain kernel

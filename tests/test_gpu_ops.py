@@ -90,6 +90,53 @@ def test_select_request_bound_regimes(profile, B, n, V, k):
         judge_selection(allsc, flat, score[b], k, tol=2e-5, margin=1e-5, what="%s b=%d" % (profile, b))
 
 
+@pytest.mark.parametrize("profile", ["random", "steep", "flat", "first_row_worst", "ties"])
+@pytest.mark.parametrize("B,n,V,k", [(2, 24, 8192, 1024), (1, 9, 5000, 600), (2, 6, 4096, 4096), (1, 300, 512, 200), (3, 1, 256, 16),
+                                     (2, 16, 256, 16), (1, 64, 1024, 128), (1, 130, 2048, 1024), (2, 40, 304, 512), (1, 700, 8, 8),
+                                     (5, 37, 1000, 33)])
+def test_select_f16_matches_oracle(profile, B, n, V, k):
+    # Half-precision logits (what the classifier hands over in bf16 mode).  With several rows per request and k <= V the
+    # bounded pass reads the rows packed and lists the rows that need their own cut; "flat" and "ties" put many rows on that
+    # list, "steep" almost none.
+    rng = np.random.default_rng(zlib.crc32(repr(("f16", profile, B, n, V, k)).encode()))
+    logits = (rng.standard_normal((B, n, V)) * 1.2).astype(np.float16)
+    cum = (-rng.random((B, n)) * 2).astype(np.float32)
+    if profile == "steep":
+        cum = np.tile(-4.0 * np.arange(n, dtype=np.float32), (B, 1))
+    elif profile == "flat":
+        cum = np.full((B, n), -7.5, dtype=np.float32)
+    elif profile == "first_row_worst":
+        cum = np.tile(-3.0 * np.arange(n, dtype=np.float32)[::-1].copy(), (B, 1))
+    elif profile == "ties":  # few distinct values and equal rows: crowded bounds, more than k candidates level with them
+        logits = np.round(rng.standard_normal((B, 1, V)) * 2).astype(np.float16).repeat(n, 1)
+        cum = np.zeros((B, n), dtype=np.float32)
+    parent, tok, score = binding.op_select(torch.from_numpy(logits).cuda(), torch.from_numpy(cum).cuda(), k)
+    torch.cuda.synchronize()
+    parent, tok, score = parent.cpu().numpy(), tok.cpu().numpy(), score.cpu().numpy()
+    assert (parent >= 0).all() and (parent < n).all() and (tok >= 0).all() and (tok < V).all()
+    for b in range(B):
+        lp = np.stack([oracle.prim_log_softmax(logits[b, i].astype(np.float32)) for i in range(n)])
+        allsc = cum[b].astype(np.float64)[:, None] + lp
+        flat = parent[b].astype(np.int64) * V + tok[b]
+        assert len(set(flat.tolist())) == k
+        if profile == "ties":
+            # equal rows are bit-identical on the GPU too: equal scores come out in ascending flat index
+            sc32 = np.float32(np.tile(np.float32(lp[0]), (n, 1)))
+            oflat, _ = oracle.prim_topk(sc32.astype(np.float64), k)
+            assert np.array_equal(flat, oflat)
+        else:
+            judge_selection(allsc, flat, score[b], k, tol=2e-5, margin=1e-5, what="f16 %s b=%d" % (profile, b))
+
+
+def test_select_f16_refuses_shapes_the_packed_rows_cannot_hold():
+    z = torch.zeros(1, 2, 12, dtype=torch.float16, device="cuda")
+    with pytest.raises(RuntimeError):
+        binding.op_select(z, None, 3)          # V not a multiple of 8
+    z = torch.zeros(1, 1, 16384, dtype=torch.float16, device="cuda")
+    with pytest.raises(RuntimeError):
+        binding.op_select(z, None, 3)          # V above 8192
+
+
 def test_select_exact_ties_and_quantised_scores():
     # equal rows: every candidate of equal score must come out in ascending flat index
     B, n, V, k = 2, 6, 500, 700
