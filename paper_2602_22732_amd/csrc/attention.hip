@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16 *__restrict
 // first product with index bits 2 and 3 swapped, which makes the 8 keys a lane holds for
 // one MFMA k-step consecutive (one 16-byte chunk of a V^T row).
 template <int DH, int QT, int NW, int SUBS>
-__global__ __launch_bounds__(NW * 64, (QT == 1 && SUBS == 1) ? 4 : 1) void cross_attn_flash_bf16(const bf16 *__restrict__ q, int64_t ldq, const bf16 *__restrict__ kv,
+__global__ __launch_bounds__(NW * 64, (QT == 1 && SUBS == 1) ? 16 / NW : 1) void cross_attn_flash_bf16(const bf16 *__restrict__ q, int64_t ldq, const bf16 *__restrict__ kv,
                                                                  const bf16 *__restrict__ vt, const int32_t *__restrict__ ctx_len,
                                                                  bf16 *__restrict__ out, int64_t ldo, int n, int S, int Spad, int d,
                                                                  int H, float scale_log2e, int beam_blocks, int64_t total_blocks) {
@@ -154,30 +154,44 @@ __global__ __launch_bounds__(NW * 64, (QT == 1 && SUBS == 1) ? 4 : 1) void cross
     // loads of one macro-tile: per 64-key tile, K_CHUNKS/64 wave loads of K rows and V_CHUNKS/64 of V^T rows, dealt round-robin
     // to the wavefronts.  A wave load fills 64 consecutive 16-byte slots; slot p of row r holds chunk p ^ swizzle(r), applied on
     // the global side.  Keys past the context end re-read its last row (masked later); V^T is zero beyond the length.
+    // The macro-tiles are requested in ascending order, so each of a wavefront's NL loads keeps a running per-lane source
+    // address that advances by a fixed step per macro-tile; only a tile that reaches past row S-1 of the keys (the last one,
+    // when S is not a multiple of 64) computes clamped addresses.
     const bf16 *kbase = kv + (int64_t)b * S * 2 * d + h * DH;
     const bf16 *vbase = vt + ((int64_t)b * d + h * DH) * Spad;
-    auto issue_macro = [&](int macro, int buf) {
-        constexpr int KI = K_CHUNKS / 64, VI = V_CHUNKS / 64, PER_TILE = KI + VI;
+    constexpr int KI = K_CHUNKS / 64, VI = V_CHUNKS / 64, PER_TILE = KI + VI, NL = (SUBS * PER_TILE + NW - 1) / NW;
+    const bf16 *lsrc[NL];
 #pragma unroll
-        for (int i = 0; i < (SUBS * PER_TILE + NW - 1) / NW; i++) {
-            const int idx = i * NW + wave;  // wave-uniform
+    for (int i = 0; i < NL; i++) {
+        const int idx = i * NW + wave;  // wave-uniform
+        const int sub = idx / PER_TILE, w = idx % PER_TILE;
+        if (w < KI) {
+            const int id = w * 64 + lane, r = id / KCH, pslot = id % KCH;
+            const int c = pslot ^ ((KCH == 8 ? (r >> 1) : (r >> 2)) & (KCH - 1));
+            lsrc[i] = kbase + (int64_t)(sub * 64 + r) * 2 * d + c * 8;
+        } else {
+            const int id = (w - KI) * 64 + lane, r = id / 8, pslot = id % 8;
+            const int c = pslot ^ ((r >> 1) & 7);
+            lsrc[i] = vbase + (int64_t)r * Spad + sub * 64 + c * 8;
+        }
+    }
+    const int64_t kstep = (int64_t)SUBS * 64 * 2 * d, vstep = SUBS * 64;  // elements per macro-tile
+    auto issue_macro = [&](int macro, int buf) {  // macro = 0, 1, 2, ... in this order
+#pragma unroll
+        for (int i = 0; i < NL; i++) {
+            const int idx = i * NW + wave;
             const int sub = idx / PER_TILE, w = idx % PER_TILE;
             const int tile = macro * SUBS + sub;
+            const bf16 *src = lsrc[i];
+            lsrc[i] += w < KI ? kstep : vstep;
             if (idx < SUBS * PER_TILE && tile < ntiles) {
-                bf16x8 *dst = smem + buf * MACRO + sub * STAGE;
-                const bf16 *src;
-                if (w < KI) {
+                bf16x8 *dst = smem + buf * MACRO + sub * STAGE + (w < KI ? w * 64 : K_CHUNKS + (w - KI) * 64);
+                if (w < KI && tile * 64 + 63 > S - 1) {
                     const int id = w * 64 + lane, r = id / KCH, pslot = id % KCH;
                     const int c = pslot ^ ((KCH == 8 ? (r >> 1) : (r >> 2)) & (KCH - 1));
                     int key = tile * 64 + r;
                     if (key > S - 1) key = S - 1;
                     src = kbase + (int64_t)key * 2 * d + c * 8;
-                    dst += w * 64;
-                } else {
-                    const int id = (w - KI) * 64 + lane, r = id / 8, pslot = id % 8;
-                    const int c = pslot ^ ((r >> 1) & 7);
-                    src = vbase + (int64_t)r * Spad + tile * 64 + c * 8;
-                    dst += K_CHUNKS + (w - KI) * 64;
                 }
                 __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)src,
                                                  (void __attribute__((address_space(3))) *)dst, 16, 0, 0);
@@ -214,20 +228,33 @@ __global__ __launch_bounds__(NW * 64, (QT == 1 && SUBS == 1) ? 4 : 1) void cross
             if (macro + 1 < nmacro) issue_macro(macro + 1, (macro + 1) & 1);
         }
         const bf16x8 *sk = smem + (macro & 1) * MACRO + sub_tile * STAGE, *sv = sk + K_CHUNKS;
+        // first product: the two 32-key halves are independent accumulation chains, issued in turn; the key fragments of
+        // k-step st+1 are read while step st multiplies
         floatx16 s[QT][2];
 #pragma unroll
-        for (int sub = 0; sub < 2; sub++) {
+        for (int sub = 0; sub < 2; sub++)
 #pragma unroll
             for (int qt = 0; qt < QT; qt++)
 #pragma unroll
                 for (int v = 0; v < 16; v++) s[qt][sub][v] = 0.0f;
+        auto key_frag = [&](int sub, int st) {
             const int r = sub * 32 + krow;
+            return sk[r * KCH + ((2 * st + hf) ^ ((KCH == 8 ? (r >> 1) : (r >> 2)) & (KCH - 1)))];
+        };
+        bf16x8 kf[2][2];
+        kf[0][0] = key_frag(0, 0);
+        kf[0][1] = key_frag(1, 0);
 #pragma unroll
-            for (int st = 0; st < KSTEPS; st++) {
-                const bf16x8 kf = sk[r * KCH + ((2 * st + hf) ^ ((KCH == 8 ? (r >> 1) : (r >> 2)) & (KCH - 1)))];
-#pragma unroll
-                for (int qt = 0; qt < QT; qt++) s[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][st], s[qt][sub], 0, 0, 0);
+        for (int st = 0; st < KSTEPS; st++) {
+            if (st + 1 < KSTEPS) {
+                kf[(st + 1) & 1][0] = key_frag(0, st + 1);
+                kf[(st + 1) & 1][1] = key_frag(1, st + 1);
             }
+#pragma unroll
+            for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+                for (int qt = 0; qt < QT; qt++)
+                    s[qt][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st & 1][sub], qf[qt][st], s[qt][sub], 0, 0, 0);
         }
         // this lane holds, for beam frow of each tile qt, keys tile*64 + 32*sub + 16*(v/8) + 8*hf + v%8.
         // The softmax is the instruction-bound part of the kernel (about three vector instructions per MFMA flop-cycle),
@@ -431,11 +458,13 @@ int launch_cross_attention(gr4ad_dtype dtype, const void *q, int64_t ldq, const 
         const bf16 *qq = (const bf16 *)q, *kk = (const bf16 *)kv, *vv = (const bf16 *)vt;
         bf16 *oo = (bf16 *)out;
         if (dh == 64) {
-            // Measured at 256 and 512 beams per request: small workgroups (4 wavefronts x 32 beams) with single 64-key
-            // macro-tiles, three of which share a compute unit, beat larger beam blocks with deeper staging by 7 %: the
-            // kernel is bound by the softmax's vector instructions, and independent workgroups interleave those with
-            // each other's MFMAs better than the two wavefronts of one block do.
+            // Measured at 256, 512 and 1024 beams per request: 32 beams per wavefront with single 64-key tiles, four wavefronts
+            // per SIMD, beat two-tile staging (-25 %) and 64 beams per wavefront (-10 %), which both halve the wavefronts per
+            // SIMD: the kernel waits on LDS, barrier and dependent-MFMA latencies, and occupancy is what hides them.  Blocks
+            // of 8 wavefronts (256 beams) share each staged tile among twice as many beams and are 3-7 % faster than blocks
+            // of 4; they are used where they waste no more beam slots.
             if (n <= 128) return launch_flash<64, 1, 4, 2>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
+            if ((n + 255) / 256 * 256 == (n + 127) / 128 * 128) return launch_flash<64, 1, 8, 1>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
             return launch_flash<64, 1, 4, 1>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
         } else {
             if (n <= 128) return launch_flash<32, 1, 4, 2>(qq, ldq, kk, vv, ctx_len, oo, ldo, B, n, S, d, H, st);
