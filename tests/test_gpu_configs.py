@@ -63,13 +63,13 @@ def test_config3_medium_bf16_sampled_requests():
 
 def test_config4_large_bf16_full_batch_sampled_requests():
     # B=1024, ragged context lengths, beams 256/512/512/1024 (bench.py --config 4): two requests judged on all their beams,
-    # fourteen more (the shortest and the longest context among them) on a sample of their beams
-    run_config(4, sample=[3, 1023], rows_sample=12)
+    # sixteen more (the shortest and the longest context among them) on a sample of their beams
+    run_config(4, sample=[3, 1023], rows_sample=14)
 
 
 @pytest.mark.parametrize("scale,batch,sample,rows_sample", [
-    (0.25, 2048, [2047], 8),   # the full batch of 2048 at every schedule of the sweep
-    (0.5, 2048, [5], 8),
+    (0.25, 2048, [2047], 15),   # the full batch of 2048 at every schedule of the sweep
+    (0.5, 2048, [5], 15),
     (1.0, 2048, [0, 1095, 1800, 2047], 12),    # the workload bench.py times by default
     (1.0, 96, [95], 0),        # and a slice of the batch: same model, same per-request work, another batch composition
 ])

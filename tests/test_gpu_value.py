@@ -19,7 +19,7 @@ pytestmark = pytest.mark.gpu
     dict(T=1, V=[1000], Ve=8, d=64, H=1, F=64, L=2, K=1, S=3, B=4, beam=[10]),                              # one SID level
     dict(T=3, V=[40, 33, 50], Ve=64, d=128, H=2, F=96, L=3, K=2, S=37, B=5, beam=[7, 13, 9], len_min=1),      # absorbed lazy attention in bf16
     dict(T=7, V=[12] * 7, Ve=256, d=640, H=10, F=64, L=2, K=1, S=200, B=2, beam=[4, 6, 5, 6, 4, 6, 5], len_min=90),  # most levels the library takes
-    dict(T=2, V=[512, 512], Ve=512, d=256, H=4, F=256, L=3, K=1, S=64, B=48, beam=[64, 96]),                # rows and widths of the persistent GEMM
+    dict(T=2, V=[512, 512], Ve=512, d=256, H=4, F=256, L=3, K=1, S=64, B=96, beam=[64, 96]),                # 9216 rows at the last level and the value step: the persistent GEMM
 ])
 def test_value_step_matches_oracle(dtype, shape):
     w, W, X = tiny(dtype=dtype, gain_jitter=0.3 if dtype == "f32" else 0.1, **shape)
