@@ -128,6 +128,42 @@ def test_select_f16_matches_oracle(profile, B, n, V, k):
             judge_selection(allsc, flat, score[b], k, tol=2e-5, margin=1e-5, what="f16 %s b=%d" % (profile, b))
 
 
+@pytest.mark.parametrize("seed", range(40))
+@pytest.mark.parametrize("half", [True, False])
+def test_select_random_shapes(seed, half):
+    # seeded random shapes through both logit formats: every register width of the wavefront kernels with and without a ragged
+    # tail, cuts above and below the codebook size, one to many rows per request, -inf beams, crowded ties
+    rng = np.random.default_rng(1000 + seed)
+    V = int(rng.choice([8, 16, 24, 64, 200, 256, 264, 1000, 1024, 2048, 2056, 4096, 5000, 8192]))
+    n = int(rng.choice([1, 2, 3, 7, 33, 64, 130, 257]))
+    B = int(rng.integers(1, 4))
+    k = int(min(n * V, rng.choice([1, 2, 7, 16, 33, 128, 512, 1000, 4096])))
+    prof = str(rng.choice(["rand", "steep", "flat", "ties", "neginf"]))
+    sigma = float(rng.choice([0.3, 1.5, 4.0]))
+    logits = (rng.standard_normal((B, n, V)) * sigma).astype(np.float16 if half else np.float32)
+    cum = (-rng.random((B, n)) * 3).astype(np.float32)
+    if prof == "steep":
+        cum = np.tile(-2.5 * np.arange(n, dtype=np.float32), (B, 1))
+    elif prof == "flat":
+        cum[:] = -1.25
+    elif prof == "ties":
+        logits = np.round(logits.astype(np.float32)).astype(logits.dtype)
+    elif prof == "neginf" and n > 1:
+        cum[:, int(rng.integers(0, n))] = -np.inf
+    parent, tok, score = binding.op_select(torch.from_numpy(logits).cuda(), torch.from_numpy(cum).cuda(), k)
+    torch.cuda.synchronize()
+    parent, tok, score = parent.cpu().numpy(), tok.cpu().numpy(), score.cpu().numpy()
+    what = "seed %d half=%s B=%d n=%d V=%d k=%d %s" % (seed, half, B, n, V, k, prof)
+    assert (parent >= 0).all() and (parent < n).all() and (tok >= 0).all() and (tok < V).all(), what
+    for b in range(B):
+        lp = np.stack([oracle.prim_log_softmax(logits[b, i].astype(np.float32)) for i in range(n)])
+        allsc = cum[b].astype(np.float64)[:, None] + lp
+        flat = parent[b].astype(np.int64) * V + tok[b]
+        fin = np.isfinite(allsc.ravel()[flat])  # (-inf candidates may fill a cut larger than the finite ones: any of them is right)
+        sc = np.where(np.isfinite(allsc), allsc, -1e30)
+        judge_selection(sc, flat, np.where(fin, score[b], -1e30), k, tol=3e-5, margin=2e-5, what=what + " b=%d" % b)
+
+
 def test_select_f16_refuses_shapes_the_packed_rows_cannot_hold():
     z = torch.zeros(1, 2, 12, dtype=torch.float16, device="cuda")
     with pytest.raises(RuntimeError):
