@@ -696,15 +696,27 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                             }
                     }
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // wave-private region: no barrier needed
+                    if (wrow0 + 128 <= M && wcol0 + 64 <= N) {
+                        // the wave's block lies inside C (all but the last row and column of tiles): no bounds tests, one running
+                        // address, LDS offsets that are instruction immediates (rows it*8 + lane/8: the swizzle only sees lane/8)
+                        const char *rd = stage + (lane / 8) * 128 + (((lane % 8) ^ ((lane / 8) & 7)) * 16);
+                        bf16 *wr = (bf16 *)epi.C + (wrow0 + pass * 64 + lane / 8) * epi.ldc + wcol0 + (lane % 8) * 8;
+#pragma unroll
+                        for (int it = 0; it < 8; it++) {
+                            __builtin_nontemporal_store(*(const bf16x8 *)(rd + it * 1024), (bf16x8 *)wr);  // C streams out: not re-read before it leaves the caches
+                            wr += 8 * epi.ldc;
+                        }
+                    } else {
 #pragma unroll 4
-                    for (int it = 0; it < 8; it++) {
-                        const int r = it * 8 + lane / 8, c = lane % 8;
-                        const bf16x8 x = *(const bf16x8 *)(stage + r * 128 + ((c ^ (r & 7)) * 16));
-                        const int64_t row = wrow0 + pass * 64 + r;
-                        const int col = wcol0 + c * 8;
-                        if (row < M && col < N) {
-                            if (col + 7 < N) __builtin_nontemporal_store(x, (bf16x8 *)((bf16 *)epi.C + row * epi.ldc + col));  // C streams out: not re-read before it leaves the caches
-                            else for (int e = 0; e < 8 && col + e < N; e++) ((bf16 *)epi.C)[row * epi.ldc + col + e] = x[e];
+                        for (int it = 0; it < 8; it++) {
+                            const int r = it * 8 + lane / 8, c = lane % 8;
+                            const bf16x8 x = *(const bf16x8 *)(stage + r * 128 + ((c ^ (r & 7)) * 16));
+                            const int64_t row = wrow0 + pass * 64 + r;
+                            const int col = wcol0 + c * 8;
+                            if (row < M && col < N) {
+                                if (col + 7 < N) __builtin_nontemporal_store(x, (bf16x8 *)((bf16 *)epi.C + row * epi.ldc + col));
+                                else for (int e = 0; e < 8 && col + e < N; e++) ((bf16 *)epi.C)[row * epi.ldc + col + e] = x[e];
+                            }
                         }
                     }
                     if (pass == 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -724,10 +736,23 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
 #pragma unroll
                     for (int e = 0; e < 4; e++) gain4[e] = (float)g4[e];
                 }
+                // the wave's block lies inside C (all but the last row and column of tiles): no bounds tests and running addresses
+                const bool interior = wrow0 + 128 <= M && wcol0 + 64 <= N;
 #pragma unroll
                 for (int pass = 0; pass < 4; pass++) {
                     floatx4 adds[8];
-                    if (HAS_ADD) {
+                    if (HAS_ADD && interior) {
+                        const int64_t row0 = wrow0 + pass * 32 + erow;
+                        if (KIND == EPI_F32_RESID) {
+                            const float *rp = epi.resid + row0 * epi.ldr + ecol;
+#pragma unroll
+                            for (int it = 0; it < 8; it++) adds[it] = *(const floatx4 *)(rp + (int64_t)(it * 4) * epi.ldr);
+                        } else {
+#pragma unroll
+                            for (int it = 0; it < 8; it++)
+                                adds[it] = *(const floatx4 *)(epi.table + (epi.tok ? (int64_t)epi.tok[row0 + it * 4] : 0) * N + ecol);
+                        }
+                    } else if (HAS_ADD) {
 #pragma unroll
                         for (int it = 0; it < 8; it++) {
                             const int64_t row = wrow0 + pass * 32 + it * 4 + erow;
@@ -750,6 +775,42 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring(const bf16 *__restrict__ A
                             *(floatx4 *)(stage + r * 256 + ((c ^ (r & 15)) * 16)) = pk;
                         }
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    if (interior) {
+                        const int64_t row0 = wrow0 + pass * 32 + erow;
+                        char *cp = (char *)epi.C + (row0 * epi.ldc + ecol) * (KIND == EPI_F32 && epi.out_f16 ? 2 : 4);
+                        const int64_t cstep = (int64_t)4 * epi.ldc * (KIND == EPI_F32 && epi.out_f16 ? 2 : 4);
+                        bf16 *np = emit ? (bf16 *)epi.norm_out + row0 * epi.norm_ld + ecol : nullptr;
+                        float *ssp = emit ? epi.norm_ss + row0 * (N / 64) + (wcol0 >> 6) : nullptr;
+#pragma unroll
+                        for (int it = 0; it < 8; it++) {  // (fully unrolled: the addends must stay in registers)
+                            const int rr = it * 4 + erow, c = lane % 16;
+                            floatx4 x = *(const floatx4 *)(stage + rr * 256 + ((c ^ (rr & 15)) * 16));
+                            if (HAS_ADD) x += adds[it];
+                            if (emit) {  // (as below)
+                                float sq = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
+                                sq += __shfl_xor(sq, 1, 64);
+                                sq += __shfl_xor(sq, 2, 64);
+                                sq += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sq), 0x114, 0xf, 0xf, true));
+                                sq += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sq), 0x118, 0xf, 0xf, true));
+                                if (lane % 16 == 15) ssp[(int64_t)(it * 4) * (N / 64)] = sq;
+                            }
+                            if (KIND == EPI_F32) x += bias4;
+                            if (KIND == EPI_F32 && epi.out_f16) {
+                                halfx4 hx;
+#pragma unroll
+                                for (int e = 0; e < 4; e++) hx[e] = (_Float16)x[e];
+                                __builtin_nontemporal_store(hx, (halfx4 *)(cp + it * cstep));
+                            } else {
+                                __builtin_nontemporal_store(x, (floatx4 *)(cp + it * cstep));
+                            }
+                            if (emit) {
+                                bf16x4 nb;
+#pragma unroll
+                                for (int e = 0; e < 4; e++) nb[e] = (bf16)(x[e] * gain4[e]);
+                                *(bf16x4 *)(np + (int64_t)(it * 4) * epi.norm_ld) = nb;
+                            }
+                        }
+                    } else
 #pragma unroll
                     for (int it = 0; it < 8; it++) {  // (fully unrolled: the addends must stay in registers)
                         const int rr = it * 4 + erow, c = lane % 16;
