@@ -218,6 +218,10 @@ def main():
         if name == "gemm_bf16_ring":
             # likewise the context key/value projections of the A autoregressive layers: counted on B*S rows, needed on the valid ones
             fl -= args.steps * w.A * (w.B * w.S - float(np.sum(lens))) * 2.0 * (2 * w.d) * w.d
+        if name == "context_attn_flash_bf16":
+            # the lazy layers' one-pass attention: the library counts all S context rows, the kernel reads (and needs) the valid ones
+            rec = dict(rec, bytes=rec["bytes"] - rec["launches"] * (w.B * w.S - float(np.sum(lens))) * w.d * 2.0)
+            fl = 0.0  # priced against HBM: 4 * RQ flops per context byte pair is far below the machine balance
         if fl > 0 and name.startswith("gemm_fp8"):
             k.update(bound="mfma", achieved=fl / sec / 1e12, peak=PEAK_FP8_MFMA / 1e12, unit="TFLOP/s", frac=fl / sec / PEAK_FP8_MFMA,
                      flops_per_launch=fl / rec["launches"])

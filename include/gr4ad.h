@@ -251,6 +251,17 @@ int gr4ad_op_cross_attention(gr4ad_dtype dtype, const void *q_dev, const void *k
                              void *out_dev, int32_t B, int32_t n, int32_t S, int32_t d, int32_t H, void *workspace_dev,
                              size_t workspace_bytes, void *hip_stream);
 
+/* Attention of query rows over the raw context rows as keys AND values: the core of the lazy layers' cross-attention
+ * (section 3.2, eq. trunk) in absorbed form, where q_h . (W_k,h x_s) = (W_k,h^T q_h) . x_s and
+ * sum_s p_s W_v,h x_s = W_v,h sum_s p_s x_s leave one query of width d per (position, head).  For each request b and
+ * query row i < RQ:  out[b, i, :] = sum_{s < len_b} softmax_s(scale * q[b, i, :] . x[b, s, :]) x[b, s, :].
+ * q, out [B, RQ, d]; x [B, S, d]; all bf16, device, row-major, 16-byte aligned; ctx_len [B] int32 or NULL (all S rows,
+ * values clamped to [1, S]); rows of x past a request's length are never used.  One kernel that reads the context once.
+ * Covers dtype GR4AD_BF16, d = 512 or 1024 and RQ <= 64: GR4AD_EUNSUPPORTED otherwise (gr4ad_decode_batch then forms
+ * scores, softmax and sums in three launches); GR4AD_EINVAL for null or misaligned pointers.  No workspace. */
+int gr4ad_op_context_attention(gr4ad_dtype dtype, const void *q_dev, const void *x_dev, const int32_t *ctx_len_dev, void *out_dev,
+                               int32_t B, int32_t RQ, int32_t S, int32_t d, float scale, void *hip_stream);
+
 /* Beam reorder as a row gather: dst[b, j, 0:row_elems] = src[b, parent[b,j],
  * 0:row_elems] for j < k; rows are `row_stride` elements apart in both buffers,
  * src holds n rows per request and dst k.  Element size follows dtype.

@@ -19,7 +19,7 @@ EXPORTS = ["gr4ad_decode_init", "gr4ad_decode_workspace_bytes", "gr4ad_decode_ba
            "gr4ad_decode_set_value_output",
            "gr4ad_decode_free", "gr4ad_strerror", "gr4ad_last_error", "gr4ad_op_linear", "gr4ad_op_select_workspace_bytes",
            "gr4ad_op_quantize_rows", "gr4ad_op_linear_fp8",
-           "gr4ad_op_select", "gr4ad_op_select_f16", "gr4ad_op_select_static", "gr4ad_op_cross_attention_workspace_bytes", "gr4ad_op_cross_attention", "gr4ad_op_gather_rows",
+           "gr4ad_op_select", "gr4ad_op_select_f16", "gr4ad_op_select_static", "gr4ad_op_cross_attention_workspace_bytes", "gr4ad_op_cross_attention", "gr4ad_op_context_attention", "gr4ad_op_gather_rows",
            "gr4ad_profile_enable",
            "gr4ad_profile_kernel_count", "gr4ad_profile_kernel_name", "gr4ad_profile_read"]
 
@@ -103,6 +103,8 @@ def lib():
         L.gr4ad_op_cross_attention.restype = C.c_int
         L.gr4ad_op_cross_attention.argtypes = [C.c_int, _VP, _VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _VP,
                                                C.c_size_t, _VP]
+        L.gr4ad_op_context_attention.restype = C.c_int
+        L.gr4ad_op_context_attention.argtypes = [C.c_int, _VP, _VP, _VP, _VP, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float, _VP]
         L.gr4ad_op_cross_attention_workspace_bytes.restype = C.c_size_t
         L.gr4ad_op_cross_attention_workspace_bytes.argtypes = [C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.gr4ad_op_gather_rows.restype = C.c_int
@@ -363,6 +365,15 @@ def op_cross_attention(q, kv, ctx_len, H, stream=None):
     ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=q.device)
     _check(lib().gr4ad_op_cross_attention(dtype_code(q.dtype), q.data_ptr(), kv.data_ptr(), None if ctx_len is None else ctx_len.data_ptr(),
                                           out.data_ptr(), B, n, S, d, H, ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return out
+
+
+def op_context_attention(q, x, ctx_len, scale, stream=None):
+    """gr4ad_op_context_attention: q, out [B,RQ,d], x [B,S,d] (bf16): attention over the raw context rows as keys and values."""
+    B, RQ, d = q.shape
+    out = torch.empty_like(q)
+    _check(lib().gr4ad_op_context_attention(dtype_code(q.dtype), q.data_ptr(), x.data_ptr(), None if ctx_len is None else ctx_len.data_ptr(),
+                                            out.data_ptr(), B, RQ, x.shape[1], d, float(scale), _stream_ptr(stream)))
     return out
 
 

@@ -424,6 +424,290 @@ int launch_masked_softmax(const float *sc, void *p, const int32_t *ctx_len, int6
     return GR4AD_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Lazy layers, cross-attention in absorbed form, one pass over the context.  In that form (eq. trunk with
+// q_h . (W_k,h x_s) = (W_k,h^T q_h) . x_s and sum_s p_s W_v,h x_s = W_v,h sum_s p_s x_s) every (position, head) of a
+// request is a query q' of width D over keys AND values that are the raw context rows:
+//     z[b, i, :] = sum_{s < len_b} softmax_s(scale * q'[b, i, :] . x[b, s, :]) x[b, s, :],      i < RQ = positions * heads.
+// One workgroup of 8 wavefronts owns a request and streams its rows once, in double-buffered tiles of 32 rows filled
+// by direct global->LDS loads (16-byte piece c of tile row r at position c ^ swz(r), applied on the global side).
+// Per tile:
+//   1. scores^T [32 rows x 32*QT queries]: the contraction over D is split over the 8/QT wavefronts that share a query
+//      tile, each with its slice of q' in registers; all but the first leave their partial sums in LDS;
+//   2. the first wavefront of each query tile adds the partials in a fixed order and does the online softmax with
+//      lane-local running maximum and sum (a lane owns one query), as the beam-shared kernel above does: raw scores,
+//      a maximum that is refreshed only when outgrown by 2^8, unrounded terms in the sum, bf16 terms in the product;
+//      it leaves P [queries x 32] and the rescale factor of each query in LDS;
+//   3. z^T += x^T P^T: every wavefront owns D/8 columns of z for all queries.  The operand x^T (8 rows of one column
+//      per lane) comes from the row-major tile through the transposing LDS read (ds_read_b64_tr_b16: of 16 lanes that
+//      pass the addresses of a 4 x 16 block of 16-bit words, four words a lane, lane i receives column i).
+// Rows past the length re-read the last valid row (finite) and enter with p = 0.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int ctx_swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }  // 16 rows -> 16 values; 4 rows -> 4 groups of 64 bytes
+
+template <int D, int QT>
+__global__ __launch_bounds__(512) void context_attn_flash_bf16(const bf16 *__restrict__ qp, const bf16 *__restrict__ x,
+                                                               const int32_t *__restrict__ ctx_len, bf16 *__restrict__ z, int RQ, int S,
+                                                               float scale_log2e) {
+    constexpr int ROWB = D * 2, CH = D / 8, TILE = 32 * ROWB;  // bytes per row, 16-byte pieces per row, bytes per tile
+    constexpr int KSPLIT = 8 / QT, KSL = D / KSPLIT, KSTEPS = KSL / 16;
+    constexpr int CW = D / 8, MT = CW / 32;  // columns of z per wavefront
+    constexpr int NL = D / 128;              // wave loads per wavefront and tile (32 * CH / 64 dealt to 8 wavefronts)
+    constexpr int NPART = QT * (KSPLIT - 1);
+    constexpr int PART = 2 * TILE, PBUF = PART + NPART * 4096, ABUF = PBUF + QT * 2048;
+    extern __shared__ __attribute__((aligned(16))) char ctx_lds[];  // 2 tiles | partial scores | P | per-query factor
+    const int lane = threadIdx.x % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    const int b = blockIdx.x;
+    const int r32 = lane % 32, g = lane / 32;
+    int len = ctx_len ? ctx_len[b] : S;
+    len = len < 1 ? 1 : (len > S ? S : len);
+    const int ntiles = (len + 31) / 32;
+    const bf16 *xb = x + (int64_t)b * S * D;
+
+    // (Everything a lane derives from its id for addressing is recomputed per tile from a value the compiler cannot see through:
+    // hoisted out of the tile loop these addresses cost some 50 registers on top of the 192 that hold q' and z, and the spills
+    // that follow are scratch loads whose waits drain the tile loads in flight.)
+    auto issue_tile = [&](int tile, int buf) {
+        unsigned lv = lane;
+        asm volatile("" : "+v"(lv));
+#pragma unroll
+        for (int i = 0; i < NL; i++) {
+            const int idx = i * 8 + wave;  // wave-uniform: 64 consecutive 16-byte slots of the tile
+            const unsigned id = idx * 64 + lv;
+            const int r = id / CH, pos = id % CH;
+            int row = tile * 32 + r;
+            if (row > len - 1) row = len - 1;
+            const bf16 *src = xb + (int64_t)row * D + (pos ^ ctx_swz(r)) * 8;
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)src,
+                                             (void __attribute__((address_space(3))) *)(ctx_lds + buf * TILE + idx * 1024), 16, 0, 0);
+        }
+    };
+
+    // first product: wavefront = (query tile qh, slice kq of the contraction)
+    const int kq = wave % KSPLIT, qh = wave / KSPLIT;
+    bf16x8 qf[KSTEPS];
+    {
+        int qrow = qh * 32 + r32;
+        if (qrow > RQ - 1) qrow = RQ - 1;  // queries past the end are computed and dropped
+        const bf16 *qr = qp + ((int64_t)b * RQ + qrow) * D + kq * KSL + 8 * g;
+#pragma unroll
+        for (int st = 0; st < KSTEPS; st++) qf[st] = *(const bf16x8 *)(qr + 16 * st);
+    }
+    float m_run = -INFINITY, l_run = 0.0f;
+
+    // second product: wavefront = columns [wave*CW, wave*CW + CW) of z
+    floatx16 o[QT][MT];
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++)
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) o[qt][mt][v] = 0.0f;
+    issue_tile(0, 0);
+    issue_tile(1, 1);  // (unconditional, so that the wait for q' is a count the compiler knows: past the length it re-reads the last row)
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NL) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    for (int tile = 0; tile < ntiles; tile++) {
+        char *xt = ctx_lds + (tile & 1) * TILE;
+        const uint32_t xt0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)ctx_lds + (tile & 1) * TILE;
+        unsigned lv = lane;
+        asm volatile("" : "+v"(lv));
+        const int r32 = lv % 32, g = lv / 32;
+        const int xrow_off = r32 * ROWB, xswz = ctx_swz(r32);
+        char *part_w = ctx_lds + PART + (qh * (KSPLIT - 1) + (kq > 0 ? kq - 1 : 0)) * 4096 + r32 * 128;  // this wavefront's partial tile (kq > 0)
+        const int prow = qh * 32 + r32;                                                                 // P row of this lane's query
+        char *p_w = ctx_lds + PBUF + prow * 64 + g * 8;
+        // ---- 1. partial scores^T of this wavefront's slice ----
+        floatx16 sacc;
+#pragma unroll
+        for (int v = 0; v < 16; v++) sacc[v] = 0.0f;
+#pragma unroll
+        for (int st = 0; st < KSTEPS; st++) {
+            const bf16x8 xf = *(const bf16x8 *)(xt + xrow_off + (((kq * (KSL / 8) + 2 * st + g) ^ xswz) * 16));
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, qf[st], sacc, 0, 0, 0);
+        }
+        // this lane: query r32 of the tile, rows 8i + 4g + e at sacc[4i + e]
+        if (kq > 0) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                floatx4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; e++) pk[e] = sacc[4 * i + e];
+                *(floatx4 *)(part_w + (((2 * i + g) ^ (r32 & 7)) * 16)) = pk;
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        // ---- 2. online softmax (first wavefront of each query tile) ----
+        if (kq == 0) {
+#pragma unroll
+            for (int k = 0; k < KSPLIT - 1; k++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const floatx4 pk = *(const floatx4 *)(part_w + k * 4096 + (((2 * i + g) ^ (r32 & 7)) * 16));
+#pragma unroll
+                    for (int e = 0; e < 4; e++) sacc[4 * i + e] += pk[e];
+                }
+            if (tile * 32 + 32 > len) {
+#pragma unroll
+                for (int v = 0; v < 16; v++)
+                    if (tile * 32 + 8 * (v / 4) + 4 * g + (v % 4) >= len) sacc[v] = -INFINITY;
+            }
+            float mx = -INFINITY;
+#pragma unroll
+            for (int v = 0; v < 16; v++) mx = fmaxf(mx, sacc[v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2e;  // finite: every tile holds at least one valid row
+            float alpha = 1.0f;
+            if (mx > m_run + 8.0f) {
+                alpha = __builtin_amdgcn_exp2f(m_run - mx);  // m_run = -inf on the first tile gives 0
+                m_run = mx;
+                l_run *= alpha;
+            }
+            const float neg_m = -m_run;
+            float lsum = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                bf16x4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * i + e], scale_log2e, neg_m));
+                    lsum += pv;
+                    pk[e] = (bf16)pv;
+                }
+                *(bf16x4 *)(p_w + ((i ^ ((prow >> 2) & 3)) * 16)) = pk;  // rows 8i + 4g .. + 3: half g of 16-byte piece i
+            }
+            l_run += lsum;  // per half-wave partial sum, joined at the end
+            if (g == 0) *(float *)(ctx_lds + ABUF + prow * 4) = alpha;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        // ---- 3. z^T += x^T P^T ----
+        // the 8-byte piece this lane passes to the transposing read h (rows 8g + 4h + i16/4 of a 16-row k-step), before the column tile
+        const int i16 = lv % 16, b1 = (lv / 16) & 1;
+        int tr_off[2], tr_swz[2];
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int sr = 8 * g + 4 * h + i16 / 4;
+            tr_off[h] = sr * ROWB + (i16 & 1) * 8;
+            tr_swz[h] = ctx_swz(sr);  // (rows 16 apart share the value)
+        }
+        const int tr_piece = wave * (CW / 8) + 2 * b1 + (i16 % 4) / 2;
+#pragma unroll
+        for (int qt = 0; qt < QT; qt++) {
+            const float a = *(const float *)(ctx_lds + ABUF + (qt * 32 + r32) * 4);
+            if (__builtin_amdgcn_ballot_w64(a != 1.0f) != 0) {
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                    for (int v = 0; v < 16; v++) o[qt][mt][v] *= a;
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ks++) {
+            bf16x8 pf[QT];
+#pragma unroll
+            for (int qt = 0; qt < QT; qt++) {
+                const int q = qt * 32 + r32;
+                pf[qt] = *(const bf16x8 *)(ctx_lds + PBUF + q * 64 + (((2 * ks + g) ^ ((q >> 2) & 3)) * 16));
+            }
+            // (The transposing reads are inline assembly: issued through the builtin, each would be preceded by a wait for every
+            // tile load in flight.  The wait below carries them as operands so that the MFMAs stay behind it.)
+            intx2 t[MT][2];
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int h = 0; h < 2; h++) {
+                    const uint32_t addr = xt0 + ks * 16 * ROWB + tr_off[h] + (((tr_piece + mt * 4) ^ tr_swz[h]) * 16);
+                    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(t[mt][h]) : "v"(addr));
+                }
+            if (MT == 4)
+                asm volatile("s_waitcnt lgkmcnt(0)"
+                             : "+v"(t[0][0]), "+v"(t[0][1]), "+v"(t[1][0]), "+v"(t[1][1]), "+v"(t[MT - 2][0]), "+v"(t[MT - 2][1]), "+v"(t[MT - 1][0]),
+                               "+v"(t[MT - 1][1]));
+            else
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(t[0][0]), "+v"(t[0][1]), "+v"(t[1][0]), "+v"(t[1][1]));
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                const intx4 both = __builtin_shufflevector(t[mt][0], t[mt][1], 0, 1, 2, 3);
+                const bf16x8 xf = __builtin_bit_cast(bf16x8, both);
+#pragma unroll
+                for (int qt = 0; qt < QT; qt++) o[qt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, pf[qt], o[qt][mt], 0, 0, 0);
+            }
+        }
+        // ---- the tile is consumed: refill its buffer two tiles ahead, then wait for the next one ----
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (tile + 2 < ntiles) issue_tile(tile + 2, tile & 1);
+        if (tile + 1 < ntiles) {
+            if (tile + 2 < ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NL) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (a one-tile request never waited for its second buffer: no load may outlive the workgroup's LDS)
+    // 1 / sum of every query through LDS (the last barrier of the loop is behind every read of the factors)
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);  // (all lanes: the exchange needs both half-waves)
+    if (kq == 0 && g == 0) *(float *)(ctx_lds + ABUF + (qh * 32 + r32) * 4) = 1.0f / l_tot;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) {
+        const int q = qt * 32 + r32;
+        const float inv = *(const float *)(ctx_lds + ABUF + q * 4);
+        if (q < RQ) {
+            bf16 *zr = z + ((int64_t)b * RQ + q) * D + wave * CW + 4 * g;
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    bf16x4 pk;
+#pragma unroll
+                    for (int e = 0; e < 4; e++) pk[e] = (bf16)(o[qt][mt][4 * i + e] * inv);
+                    *(bf16x4 *)(zr + mt * 32 + 8 * i) = pk;
+                }
+        }
+    }
+}
+
+bool context_attention_covers(gr4ad_dtype dtype, int RQ, int d) { return dtype == GR4AD_BF16 && (d == 512 || d == 1024) && RQ >= 1 && RQ <= 64; }
+
+template <int D, int QT>
+static int launch_context_flash(const bf16 *qp, const bf16 *x, const int32_t *ctx_len, bf16 *z, int B, int RQ, int S, float scale, hipStream_t st) {
+    auto kern = context_attn_flash_bf16<D, QT>;
+    constexpr int LDS_BYTES = 2 * 32 * D * 2 + QT * (8 / QT - 1) * 4096 + QT * 2048 + QT * 128;
+    static_assert(LDS_BYTES <= 160 * 1024, "the workgroup's LDS");
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) return GR4AD_EHIP;
+        attr_done = true;
+    }
+    // flops on the padded length S, both products; bytes: the context once, queries and sums once
+    ProfScope ps(KC_CONTEXT_ATTN, st, 4.0 * B * (double)RQ * S * D, (2.0 * B * (double)RQ * D + B * (double)S * D) * sizeof(bf16));
+    hipLaunchKernelGGL(kern, dim3((unsigned)B), dim3(512), LDS_BYTES, st, qp, x, ctx_len, z, RQ, S, scale * 1.4426950408889634f);
+    GR4AD_LAUNCH_CHECK();
+    return GR4AD_OK;
+}
+
+// z [B, RQ, d] = attention of the queries qp [B, RQ, d] over the context rows x [B, S, d] as keys and values (above).
+int launch_context_attention(gr4ad_dtype dtype, const void *qp, const void *x, const int32_t *ctx_len, void *z, int B, int RQ, int S, int d,
+                             float scale, hipStream_t st) {
+    if (!context_attention_covers(dtype, RQ, d) || B < 1 || S < 1) return GR4AD_EUNSUPPORTED;
+    if (!qp || !x || !z || ((uintptr_t)qp % 16) || ((uintptr_t)x % 16) || ((uintptr_t)z % 8)) return GR4AD_EINVAL;
+    const bf16 *q = (const bf16 *)qp, *xx = (const bf16 *)x;
+    if (d == 1024) return RQ > 32 ? launch_context_flash<1024, 2>(q, xx, ctx_len, (bf16 *)z, B, RQ, S, scale, st)
+                                  : launch_context_flash<1024, 1>(q, xx, ctx_len, (bf16 *)z, B, RQ, S, scale, st);
+    return RQ > 32 ? launch_context_flash<512, 2>(q, xx, ctx_len, (bf16 *)z, B, RQ, S, scale, st)
+                   : launch_context_flash<512, 1>(q, xx, ctx_len, (bf16 *)z, B, RQ, S, scale, st);
+}
+
 template <int DH, int QT, int NW, int SUBS>
 static int launch_flash(const bf16 *q, int64_t ldq, const bf16 *kv, const bf16 *vt, const int32_t *ctx_len, bf16 *out, int64_t ldo, int B,
                         int n, int S, int d, int H, hipStream_t st) {

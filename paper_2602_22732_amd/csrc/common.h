@@ -14,6 +14,8 @@ typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef int intx2 __attribute__((ext_vector_type(2)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float to_f(float x) { return x; }
 __device__ __forceinline__ float to_f(bf16 x) { return (float)x; }
@@ -166,6 +168,11 @@ int launch_context_transpose(const void *x, const int32_t *ctx_len, void *xt, in
 // p[r, :] = softmax(scale * sc[r, :len]) (bf16, zero from len to ld) for float32 score rows; request of row r = r / rows_per_req
 int launch_masked_softmax(const float *sc, void *p, const int32_t *ctx_len, int64_t rows, int rows_per_req, int S, int ld, float scale,
                           hipStream_t st);
+// Lazy layers in absorbed form, one pass: z [B, RQ, d] = softmax(scale * qp x^T) x per request over its first len rows
+// (qp [B, RQ, d], x [B, S, d], bf16).  GR4AD_EUNSUPPORTED for shapes context_attention_covers() refuses.
+bool context_attention_covers(gr4ad_dtype dtype, int RQ, int d);
+int launch_context_attention(gr4ad_dtype dtype, const void *qp, const void *x, const int32_t *ctx_len, void *z, int B, int RQ, int S, int d,
+                             float scale, hipStream_t st);
 // autoregressive self-attention of position `pos` for rows (b*n+i).  qkv [rows,3d] holds q, k, v of the new position;
 // the keys and values of position p < pos are columns d..3d of row anc[row*T + p] of prev.p[p] (the [*,3d] q/k/v buffer
 // that level wrote): the beam reorder is the ancestor table, no rows are moved.
@@ -187,7 +194,7 @@ bool select_takes_f16(int V);
 
 // ---- optional per-kernel event timing ----------------------------------------
 enum KernelClass { KC_GEMM_256 = 0, KC_GEMM_128, KC_GEMM_SIMPLE, KC_XATTN_FLASH, KC_XATTN_SIMPLE, KC_SELF_STEP, KC_TRUNK_SELF,
-                   KC_RMSNORM, KC_FUSE_GATE, KC_SELECT_ROWS, KC_SELECT_REQUEST, KC_GATHER, KC_BROADCAST, KC_V_TRANSPOSE, KC_GEMM_RING, KC_SOFTMAX, KC_GEMM_RING_F8, KC_QUANTIZE, KC_COUNT };
+                   KC_RMSNORM, KC_FUSE_GATE, KC_SELECT_ROWS, KC_SELECT_REQUEST, KC_GATHER, KC_BROADCAST, KC_V_TRANSPOSE, KC_GEMM_RING, KC_SOFTMAX, KC_GEMM_RING_F8, KC_QUANTIZE, KC_CONTEXT_ATTN, KC_COUNT };
 // Declared around a kernel launch: records an event before and (on scope exit) after it when timing is on.
 struct ProfScope {
     ProfScope(int cls, hipStream_t st, double flops = 0.0, double bytes = 0.0);  // algorithmic work of the launch

@@ -134,11 +134,12 @@ Plan make_plan(const gr4ad_decoder *dec, int64_t B, int64_t S, const int32_t *be
     p.vt_lazy = take(lazy_kv ? p.vt_bytes : 0);
     if (dec->absorbed) {  // bf16 only
         const int64_t Spad = (S + 63) / 64 * 64, RQ = Tp * dec->H;
-        p.xt = take((size_t)B * d * Spad * e);
+        const bool two_pass = !context_attention_covers(dec->dtype, (int)RQ, dec->d);  // (else one kernel, no transposed copy, scores or probabilities in HBM)
+        p.xt = take(two_pass ? (size_t)B * d * Spad * e : 0);
         p.qp = take((size_t)B * RQ * d * e);
         p.zb = take((size_t)B * RQ * d * e);
-        p.sc = take((size_t)B * RQ * Spad * sizeof(float));
-        p.pb = take((size_t)B * RQ * Spad * e);
+        p.sc = take(two_pass ? (size_t)B * RQ * Spad * sizeof(float) : 0);
+        p.pb = take(two_pass ? (size_t)B * RQ * Spad * e : 0);
     }
     p.ss = take((size_t)p.rows_max * (d / 64 + 1) * sizeof(float));  // partial sums of squares of the folded RMSNorm
     p.trunk = take((size_t)B * Tp * d * sizeof(float));  // residual streams stay float32 whatever the storage dtype
@@ -598,16 +599,22 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
         float *sc = (float *)(ws + p.sc);
         const char *wv = (const char *)lw.wkv_x + (size_t)d * d * e;
         int s;
-        if (first && (s = launch_context_transpose(ctx, ctx_len, xt, B, S, d, st))) return s;  // once per decode, shared by all lazy layers
+        const bool one_pass = context_attention_covers(dt, (int)RQ, d);
+        if (first && !one_pass && (s = launch_context_transpose(ctx, ctx_len, xt, B, S, d, st))) return s;  // once per decode, shared by all lazy layers
         if ((s = norm(trunk, lw.ln_x, rows))) return s;
         if ((s = gemm(xn, rows, lw.wq_x, d, d, reads_norm(plain_epilogue(q, d))))) return s;
         // q'[row][h][:] = W_{k,h}^T q[row][h*dh : (h+1)*dh]      (batch = head)
         if ((s = launch_gemm_batched(q, d, dh, lw.wkT_x, dh, (int64_t)d * dh, qp, (int64_t)H * d, d, 0, rows, d, dh, H, nullptr, 0, st))) return s;
+        if (one_pass) {
+            // scores, softmax and z in one kernel that reads the request's context rows once (widths and query counts it covers)
+            if ((s = launch_context_attention(dt, qp, ctx, ctx_len, zb, B, (int)RQ, S, d, 1.0f / sqrtf((float)dh), st))) return s;
+        } else {
         // raw scores[b][(t,h)][s] = q'[b][(t,h)] . x[b][s]         (batch = request; columns beyond the length are not needed)
         if ((s = launch_gemm_batched(qp, d, RQ * d, ctx, d, (int64_t)S * d, sc, Spad, RQ * Spad, 1, RQ, S, d, B, ctx_len, 1, st))) return s;
         if ((s = launch_masked_softmax(sc, pb, ctx_len, (int64_t)B * RQ, (int)RQ, S, Spad, 1.0f / sqrtf((float)dh), st))) return s;
         // z[b][(t,h)][:] = sum_s p[b][(t,h)][s] x[b][s][:]         (batch = request; p and x^T are zero beyond the length)
         if ((s = launch_gemm_batched(pb, Spad, RQ * Spad, xt, Spad, (int64_t)d * Spad, zb, d, RQ * d, 0, RQ, d, Spad, B, ctx_len, 2, st))) return s;
+        }
         // o[row][h*dh : (h+1)*dh] = W_{v,h} z[row][h][:]           (batch = head)
         if ((s = launch_gemm_batched(zb, (int64_t)H * d, d, wv, d, (int64_t)dh * d, o, d, dh, 0, rows, dh, d, H, nullptr, 0, st))) return s;
         return gemm(o, rows, lw.wo_x, d, d, emit_norm(resid_epi(trunk, d), lw.ln_s));
@@ -774,6 +781,12 @@ int gr4ad_op_cross_attention(gr4ad_dtype dtype, const void *q, const void *kv, c
     int s = launch_cross_attention_prepare(dtype, kv, ctx_len, workspace, B, S, d, H, (hipStream_t)hip_stream);
     if (s) return s;
     return launch_cross_attention(dtype, q, d, kv, need ? workspace : nullptr, ctx_len, out, d, B, n, S, d, H, (hipStream_t)hip_stream);
+}
+
+int gr4ad_op_context_attention(gr4ad_dtype dtype, const void *q, const void *x, const int32_t *ctx_len, void *out, int32_t B, int32_t RQ,
+                               int32_t S, int32_t d, float scale, void *hip_stream) {
+    if (!q || !x || !out || B < 1 || RQ < 1 || S < 1 || d < 1 || !(scale > 0.0f)) return GR4AD_EINVAL;
+    return launch_context_attention(dtype, q, x, ctx_len, out, B, RQ, S, d, scale, (hipStream_t)hip_stream);
 }
 
 int gr4ad_op_gather_rows(gr4ad_dtype dtype, const void *src, const int32_t *parent, void *dst, int32_t B, int32_t n, int32_t k,

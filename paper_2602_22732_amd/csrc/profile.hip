@@ -14,7 +14,7 @@ const size_t kMaxRecords = 1 << 16;
 const char *kNames[KC_COUNT] = {"gemm_bf16_mfma_256x256", "gemm_bf16_mfma_128x128", "gemm_simple", "cross_attn_flash_bf16",
                                 "cross_attn_simple", "self_attn_step", "trunk_self_attn", "rmsnorm", "fuse_gate", "select_rows",
                                 "select_request", "gather_rows", "broadcast_rows", "v_transpose", "gemm_bf16_ring", "masked_softmax_rows",
-                                "gemm_fp8_ring", "quantize_rows"};
+                                "gemm_fp8_ring", "quantize_rows", "context_attn_flash_bf16"};
 }  // namespace
 
 ProfScope::ProfScope(int cls, hipStream_t st, double flops, double bytes) : idx_(-1), st_(st) {

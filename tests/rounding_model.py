@@ -7,7 +7,7 @@ the vanilla decoder's input s_{t-1} + p_t) teacher-forced on given prefixes, in 
 function at exactly the places where the library stores a narrower type:
 
     norm outputs, q, context keys/values, attention probabilities (matrix-core kernel: unnormalised, relative to a
-    lazily refreshed maximum; absorbed form: normalised) and outputs, self-attention q/k/v and outputs, FFN hidden
+    lazily refreshed maximum; absorbed form: normalised, or like the matrix-core kernel where one kernel forms it) and outputs, self-attention q/k/v and outputs, FFN hidden
     rows, the gated embedding of Fuse; float32 for the residual stream, the Fuse tables and the logits - except the
     logits of large levels, which the persistent GEMM hands to the selection in IEEE half precision.
 
@@ -183,6 +183,28 @@ class RoundedModel:
         qh = q.reshape(-1, H, dh)
         Wk, Wv = lw["wk_x"].reshape(H, dh, d), lw["wv_x"].reshape(H, dh, d)
         qp = self.rnd(np.einsum("nhc,hcj->nhj", qh, Wk))           # absorbed queries [n, H, d]
+        if d in (512, 1024) and qh.shape[0] * H <= 64:
+            # one kernel over 32-row tiles of the context (these widths, at most 64 queries per request): probabilities relative
+            # to a maximum that is refreshed when outgrown by more than 8 (exp2 domain), rounded in the product, not in the sum
+            s = self.f32(np.einsum("nhj,sj->nhs", qp, X))
+            c = np.log2(np.e) / np.sqrt(dh)
+            m = np.full(s.shape[:2], -np.inf)
+            l = np.zeros(s.shape[:2])
+            O = np.zeros(s.shape[:2] + (d,))
+            for j0 in range(0, s.shape[-1], 32):
+                st = s[:, :, j0:j0 + 32]
+                mx = st.max(axis=-1) * c
+                upd = mx > m + 8.0
+                mnew = np.where(upd, mx, m)
+                alpha = np.where(upd, np.exp2(m - mnew), 1.0)
+                m = mnew
+                l, O = l * alpha, O * alpha[..., None]
+                p = np.exp2(st * c - m[..., None])
+                l = l + p.sum(axis=-1)
+                O = O + np.einsum("nhs,sj->nhj", self.rnd(p), X[j0:j0 + 32])
+            z = self.rnd(O / l[..., None])
+            o = self.rnd(np.einsum("nhj,hcj->nhc", z, Wv))
+            return o.reshape(q.shape)
         s = self.f32(np.einsum("nhj,sj->nhs", qp, X)) / np.sqrt(dh)
         p = np.exp(s - s.max(axis=-1, keepdims=True))
         p = self.rnd(p / p.sum(axis=-1, keepdims=True))

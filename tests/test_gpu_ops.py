@@ -206,6 +206,37 @@ def test_cross_attention_matches_oracle(dtype, B, n, S, d, H):
         np.testing.assert_allclose(out[b], ref, atol=2e-5 if dtype == "f32" else 1.5e-2)
 
 
+@pytest.mark.parametrize("B,RQ,S,d,gain", [(3, 64, 200, 1024, 1.0), (2, 48, 33, 1024, 4.0), (2, 17, 1, 1024, 1.0), (3, 32, 95, 1024, 2.0),
+                                          (2, 24, 130, 512, 1.0), (3, 64, 64, 512, 6.0), (2, 5, 31, 512, 1.0), (4, 40, 257, 512, 3.0)])
+def test_context_attention_matches_oracle(B, RQ, S, d, gain):
+    """Attention over the raw context rows as keys and values (the lazy layers' absorbed form) = single-head attention with
+    K = V = x in the oracle; `gain` sharpens the softmax so that the running maximum moves between tiles."""
+    q = synth.round_bf16((gain * RNG.standard_normal((B, RQ, d))).astype(np.float32))
+    x = synth.round_bf16(RNG.standard_normal((B, S, d)).astype(np.float32))
+    lens = RNG.integers(1, S + 1, size=B).astype(np.int32)
+    lens[0] = S
+    for b in range(B):
+        x[b, lens[b]:] = 1e4  # padding must not matter
+    scale = 1.0 / np.sqrt(d)
+    out = binding.op_context_attention(dev(q, "bf16"), dev(x, "bf16"), torch.from_numpy(lens).cuda(), scale)
+    full = binding.op_context_attention(dev(q[:1], "bf16"), dev(x[:1], "bf16"), None, scale)
+    torch.cuda.synchronize()
+    out = out.float().cpu().numpy()
+    for b in range(B):
+        ref = oracle.prim_mha(q[b], x[b, :lens[b]], x[b, :lens[b]], 1, False)
+        np.testing.assert_allclose(out[b], ref, atol=1.5e-2)
+    assert np.array_equal(full.float().cpu().numpy()[0], out[0])  # no length array = all rows
+
+
+def test_context_attention_refuses_what_it_does_not_cover():
+    q = torch.zeros((1, 65, 512), dtype=torch.bfloat16, device="cuda")
+    x = torch.zeros((1, 8, 512), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(RuntimeError):
+        binding.op_context_attention(q, x, None, 1.0)
+    with pytest.raises(RuntimeError):
+        binding.op_context_attention(q[:, :8, :256].contiguous(), x[:, :, :256].contiguous(), None, 1.0)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_gather_rows_is_an_exact_copy(dtype):
     B, n, k, T, d2 = 3, 9, 14, 4, 64
