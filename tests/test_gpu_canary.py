@@ -41,6 +41,7 @@ SHAPES = [
     dict(dtype="bf16", T=2, V=[520, 1028], d=256, H=4, F=320, L=3, K=1, S=100, B=37, beam=[250, 300], len_min=3),    # 9250 rows: persistent GEMM, ragged last tile
     dict(dtype="bf16", fp8=True, T=2, V=[520, 516], d=256, H=4, F=384, L=2, K=1, S=64, B=37, beam=[250, 300]),      # FP8 persistent GEMM
     dict(dtype="bf16", Ve=33, T=2, V=[64, 50], d=128, H=2, F=128, L=2, K=1, S=20, B=3, beam=[8, 12]),                 # value step
+    dict(dtype="bf16", T=3, V=[24, 20, 30], d=512, H=8, F=64, L=2, K=1, S=75, B=3, beam=[5, 8, 6], len_min=1),          # one-pass absorbed attention
 ]
 
 

@@ -50,6 +50,10 @@ def test_config1_tiny_fp32_full_batch_matches_oracle_exactly_where_margins_allow
     dict(T=3, V=[40, 33, 50], d=128, H=2, F=96, L=3, K=2, S=37, B=5, beam=[7, 13, 9], len_min=1),    # one ragged key tile
     dict(T=2, V=[64, 50], d=256, H=2, F=64, L=2, K=1, S=150, B=3, beam=[8, 12], len_min=1),       # dh=128, three key tiles
     dict(T=7, V=[12, 12, 12, 12, 12, 12, 12], d=640, H=10, F=64, L=2, K=1, S=200, B=2, beam=[4, 6, 5, 6, 4, 6, 5], len_min=90),  # T*H > 64
+    # widths 512 and 1024 with at most 64 (position, head) queries: in bf16 the absorbed form runs as one kernel over the context
+    dict(T=3, V=[24, 20, 30], d=512, H=8, F=64, L=3, K=2, S=75, B=3, beam=[5, 8, 6], len_min=1),           # 24 queries, ragged tiles of 32 rows
+    dict(T=5, V=[12, 16, 12, 10, 14], d=512, H=8, F=64, L=2, K=1, S=100, B=2, beam=[4, 6, 5, 6, 4], len_min=33),  # 40 queries: two query tiles
+    dict(T=4, V=[24, 20, 16, 30], d=1024, H=16, F=64, L=2, K=1, S=45, B=2, beam=[5, 8, 6, 7], len_min=3),   # 64 queries, the benchmark's shape
 ])
 def test_small_shapes_match_oracle(dtype, shape):
     w, W, X = tiny(dtype=dtype, gain_jitter=0.3 if dtype == "f32" else 0.1, **shape)
