@@ -8,6 +8,10 @@
 //                           softmax.
 //  * cross_attn_simple<T>   one wavefront per (beam row, head), any shape; float32
 //                           path and fallback.
+//  * context_attn_flash_bf16  the lazy layers' cross-attention in absorbed form
+//                           (keys = values = the raw context rows, one query of
+//                           width d per (position, head)): one pass over the
+//                           context, MFMA, online softmax.
 //  * self_attn_step<T>      autoregressive self-attention of the new position over
 //                           the beam path's earlier positions (at most T keys), read
 //                           in place from the buffers their levels wrote, through

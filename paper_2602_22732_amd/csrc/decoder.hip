@@ -609,11 +609,11 @@ int gr4ad_decode_batch(gr4ad_decoder *dec, const void *ctx, const int32_t *ctx_l
             // scores, softmax and z in one kernel that reads the request's context rows once (widths and query counts it covers)
             if ((s = launch_context_attention(dt, qp, ctx, ctx_len, zb, B, (int)RQ, S, d, 1.0f / sqrtf((float)dh), st))) return s;
         } else {
-        // raw scores[b][(t,h)][s] = q'[b][(t,h)] . x[b][s]         (batch = request; columns beyond the length are not needed)
-        if ((s = launch_gemm_batched(qp, d, RQ * d, ctx, d, (int64_t)S * d, sc, Spad, RQ * Spad, 1, RQ, S, d, B, ctx_len, 1, st))) return s;
-        if ((s = launch_masked_softmax(sc, pb, ctx_len, (int64_t)B * RQ, (int)RQ, S, Spad, 1.0f / sqrtf((float)dh), st))) return s;
-        // z[b][(t,h)][:] = sum_s p[b][(t,h)][s] x[b][s][:]         (batch = request; p and x^T are zero beyond the length)
-        if ((s = launch_gemm_batched(pb, Spad, RQ * Spad, xt, Spad, (int64_t)d * Spad, zb, d, RQ * d, 0, RQ, d, Spad, B, ctx_len, 2, st))) return s;
+            // raw scores[b][(t,h)][s] = q'[b][(t,h)] . x[b][s]         (batch = request; columns beyond the length are not needed)
+            if ((s = launch_gemm_batched(qp, d, RQ * d, ctx, d, (int64_t)S * d, sc, Spad, RQ * Spad, 1, RQ, S, d, B, ctx_len, 1, st))) return s;
+            if ((s = launch_masked_softmax(sc, pb, ctx_len, (int64_t)B * RQ, (int)RQ, S, Spad, 1.0f / sqrtf((float)dh), st))) return s;
+            // z[b][(t,h)][:] = sum_s p[b][(t,h)][s] x[b][s][:]         (batch = request; p and x^T are zero beyond the length)
+            if ((s = launch_gemm_batched(pb, Spad, RQ * Spad, xt, Spad, (int64_t)d * Spad, zb, d, RQ * d, 0, RQ, d, Spad, B, ctx_len, 2, st))) return s;
         }
         // o[row][h*dh : (h+1)*dh] = W_{v,h} z[row][h][:]           (batch = head)
         if ((s = launch_gemm_batched(zb, (int64_t)H * d, d, wv, d, (int64_t)dh * d, o, d, dh, 0, rows, dh, d, H, nullptr, 0, st))) return s;
