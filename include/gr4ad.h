@@ -257,8 +257,9 @@ int gr4ad_op_cross_attention(gr4ad_dtype dtype, const void *q_dev, const void *k
  * query row i < RQ:  out[b, i, :] = sum_{s < len_b} softmax_s(scale * q[b, i, :] . x[b, s, :]) x[b, s, :].
  * q, out [B, RQ, d]; x [B, S, d]; all bf16, device, row-major, 16-byte aligned; ctx_len [B] int32 or NULL (all S rows,
  * values clamped to [1, S]); rows of x past a request's length are never used.  One kernel that reads the context once.
- * Covers dtype GR4AD_BF16, d = 512 or 1024 and RQ <= 64: GR4AD_EUNSUPPORTED otherwise (gr4ad_decode_batch then forms
- * scores, softmax and sums in three launches); GR4AD_EINVAL for null or misaligned pointers.  No workspace. */
+ * Covers dtype GR4AD_BF16, d = 512 or 1024 and RQ <= 128 (more than 64 query rows: two launches, each reading the
+ * context): GR4AD_EUNSUPPORTED otherwise (gr4ad_decode_batch then forms scores, softmax and sums in three launches);
+ * GR4AD_EINVAL for null or misaligned pointers.  No workspace. */
 int gr4ad_op_context_attention(gr4ad_dtype dtype, const void *q_dev, const void *x_dev, const int32_t *ctx_len_dev, void *out_dev,
                                int32_t B, int32_t RQ, int32_t S, int32_t d, float scale, void *hip_stream);
 

@@ -451,8 +451,8 @@ __device__ __forceinline__ int ctx_swz(int r) { return ((r & 3) << 2) | ((r >> 2
 
 template <int D, int QT>
 __global__ __launch_bounds__(512) void context_attn_flash_bf16(const bf16 *__restrict__ qp, const bf16 *__restrict__ x,
-                                                               const int32_t *__restrict__ ctx_len, bf16 *__restrict__ z, int RQ, int S,
-                                                               float scale_log2e) {
+                                                               const int32_t *__restrict__ ctx_len, bf16 *__restrict__ z, int RQ, int rq_stride,
+                                                               int S, float scale_log2e) {
     constexpr int ROWB = D * 2, CH = D / 8, TILE = 32 * ROWB;  // bytes per row, 16-byte pieces per row, bytes per tile
     constexpr int KSPLIT = 8 / QT, KSL = D / KSPLIT, KSTEPS = KSL / 16;
     constexpr int CW = D / 8, MT = CW / 32;  // columns of z per wavefront
@@ -494,7 +494,7 @@ __global__ __launch_bounds__(512) void context_attn_flash_bf16(const bf16 *__res
     {
         int qrow = qh * 32 + r32;
         if (qrow > RQ - 1) qrow = RQ - 1;  // queries past the end are computed and dropped
-        const bf16 *qr = qp + ((int64_t)b * RQ + qrow) * D + kq * KSL + 8 * g;
+        const bf16 *qr = qp + ((int64_t)b * rq_stride + qrow) * D + kq * KSL + 8 * g;
 #pragma unroll
         for (int st = 0; st < KSTEPS; st++) qf[st] = *(const bf16x8 *)(qr + 16 * st);
     }
@@ -667,7 +667,7 @@ __global__ __launch_bounds__(512) void context_attn_flash_bf16(const bf16 *__res
         const int q = qt * 32 + r32;
         const float inv = *(const float *)(ctx_lds + ABUF + q * 4);
         if (q < RQ) {
-            bf16 *zr = z + ((int64_t)b * RQ + q) * D + wave * CW + 4 * g;
+            bf16 *zr = z + ((int64_t)b * rq_stride + q) * D + wave * CW + 4 * g;
 #pragma unroll
             for (int mt = 0; mt < MT; mt++)
 #pragma unroll
@@ -681,10 +681,12 @@ __global__ __launch_bounds__(512) void context_attn_flash_bf16(const bf16 *__res
     }
 }
 
-bool context_attention_covers(gr4ad_dtype dtype, int RQ, int d) { return dtype == GR4AD_BF16 && (d == 512 || d == 1024) && RQ >= 1 && RQ <= 64; }
+// (more than 64 queries per request run as two launches, each reading the context: beyond 128 the stored-score form moves fewer bytes)
+bool context_attention_covers(gr4ad_dtype dtype, int RQ, int d) { return dtype == GR4AD_BF16 && (d == 512 || d == 1024) && RQ >= 1 && RQ <= 128; }
 
 template <int D, int QT>
-static int launch_context_flash(const bf16 *qp, const bf16 *x, const int32_t *ctx_len, bf16 *z, int B, int RQ, int S, float scale, hipStream_t st) {
+static int launch_context_flash(const bf16 *qp, const bf16 *x, const int32_t *ctx_len, bf16 *z, int B, int RQ, int rq_stride, int S, float scale,
+                                hipStream_t st) {  // RQ <= 32 * QT queries per request, rows rq_stride apart from one request to the next
     auto kern = context_attn_flash_bf16<D, QT>;
     constexpr int LDS_BYTES = 2 * 32 * D * 2 + QT * (8 / QT - 1) * 4096 + QT * 2048 + QT * 128;
     static_assert(LDS_BYTES <= 160 * 1024, "the workgroup's LDS");
@@ -695,7 +697,7 @@ static int launch_context_flash(const bf16 *qp, const bf16 *x, const int32_t *ct
     }
     // flops on the padded length S, both products; bytes: the context once, queries and sums once
     ProfScope ps(KC_CONTEXT_ATTN, st, 4.0 * B * (double)RQ * S * D, (2.0 * B * (double)RQ * D + B * (double)S * D) * sizeof(bf16));
-    hipLaunchKernelGGL(kern, dim3((unsigned)B), dim3(512), LDS_BYTES, st, qp, x, ctx_len, z, RQ, S, scale * 1.4426950408889634f);
+    hipLaunchKernelGGL(kern, dim3((unsigned)B), dim3(512), LDS_BYTES, st, qp, x, ctx_len, z, RQ, rq_stride, S, scale * 1.4426950408889634f);
     GR4AD_LAUNCH_CHECK();
     return GR4AD_OK;
 }
@@ -705,11 +707,19 @@ int launch_context_attention(gr4ad_dtype dtype, const void *qp, const void *x, c
                              float scale, hipStream_t st) {
     if (!context_attention_covers(dtype, RQ, d) || B < 1 || S < 1) return GR4AD_EUNSUPPORTED;
     if (!qp || !x || !z || ((uintptr_t)qp % 16) || ((uintptr_t)x % 16) || ((uintptr_t)z % 8)) return GR4AD_EINVAL;
-    const bf16 *q = (const bf16 *)qp, *xx = (const bf16 *)x;
-    if (d == 1024) return RQ > 32 ? launch_context_flash<1024, 2>(q, xx, ctx_len, (bf16 *)z, B, RQ, S, scale, st)
-                                  : launch_context_flash<1024, 1>(q, xx, ctx_len, (bf16 *)z, B, RQ, S, scale, st);
-    return RQ > 32 ? launch_context_flash<512, 2>(q, xx, ctx_len, (bf16 *)z, B, RQ, S, scale, st)
-                   : launch_context_flash<512, 1>(q, xx, ctx_len, (bf16 *)z, B, RQ, S, scale, st);
+    const bf16 *xx = (const bf16 *)x;
+    for (int q0 = 0; q0 < RQ; q0 += 64) {  // 64 queries of every request per launch
+        const bf16 *q = (const bf16 *)qp + (int64_t)q0 * d;
+        bf16 *zz = (bf16 *)z + (int64_t)q0 * d;
+        const int nq = RQ - q0 < 64 ? RQ - q0 : 64;
+        int s;
+        if (d == 1024) s = nq > 32 ? launch_context_flash<1024, 2>(q, xx, ctx_len, zz, B, nq, RQ, S, scale, st)
+                                   : launch_context_flash<1024, 1>(q, xx, ctx_len, zz, B, nq, RQ, S, scale, st);
+        else s = nq > 32 ? launch_context_flash<512, 2>(q, xx, ctx_len, zz, B, nq, RQ, S, scale, st)
+                         : launch_context_flash<512, 1>(q, xx, ctx_len, zz, B, nq, RQ, S, scale, st);
+        if (s) return s;
+    }
+    return GR4AD_OK;
 }
 
 template <int DH, int QT, int NW, int SUBS>

@@ -169,7 +169,8 @@ int launch_context_transpose(const void *x, const int32_t *ctx_len, void *xt, in
 int launch_masked_softmax(const float *sc, void *p, const int32_t *ctx_len, int64_t rows, int rows_per_req, int S, int ld, float scale,
                           hipStream_t st);
 // Lazy layers in absorbed form, one pass: z [B, RQ, d] = softmax(scale * qp x^T) x per request over its first len rows
-// (qp [B, RQ, d], x [B, S, d], bf16).  GR4AD_EUNSUPPORTED for shapes context_attention_covers() refuses.
+// (qp [B, RQ, d], x [B, S, d], bf16; 64 queries of every request per launch).  GR4AD_EUNSUPPORTED for shapes
+// context_attention_covers() refuses.
 bool context_attention_covers(gr4ad_dtype dtype, int RQ, int d);
 int launch_context_attention(gr4ad_dtype dtype, const void *qp, const void *x, const int32_t *ctx_len, void *z, int B, int RQ, int S, int d,
                              float scale, hipStream_t st);

@@ -183,8 +183,8 @@ class RoundedModel:
         qh = q.reshape(-1, H, dh)
         Wk, Wv = lw["wk_x"].reshape(H, dh, d), lw["wv_x"].reshape(H, dh, d)
         qp = self.rnd(np.einsum("nhc,hcj->nhj", qh, Wk))           # absorbed queries [n, H, d]
-        if d in (512, 1024) and qh.shape[0] * H <= 64:
-            # one kernel over 32-row tiles of the context (these widths, at most 64 queries per request): probabilities relative
+        if d in (512, 1024) and qh.shape[0] * H <= 128:
+            # one kernel over 32-row tiles of the context (these widths, at most 128 queries per request): probabilities relative
             # to a maximum that is refreshed when outgrown by more than 8 (exp2 domain), rounded in the product, not in the sum
             s = self.f32(np.einsum("nhj,sj->nhs", qp, X))
             c = np.log2(np.e) / np.sqrt(dh)

@@ -114,7 +114,7 @@ def test_ops_reject_bad_arguments_without_a_gpu():
     assert L.gr4ad_op_context_attention(1, None, None, None, None, 1, 1, 1, 512, 1.0, None) == -1
     some = C.c_int32(0)  # (shapes are refused on the host, before any pointer is looked at)
     ptr = C.addressof(some)
-    for args in ((0, 1, 8, 16, 512), (1, 1, 65, 16, 512), (1, 1, 8, 16, 256)):  # float32; too many query rows; a width without a kernel
+    for args in ((0, 1, 8, 16, 512), (1, 1, 129, 16, 512), (1, 1, 8, 16, 256)):  # float32; too many query rows; a width without a kernel
         assert L.gr4ad_op_context_attention(args[0], ptr, ptr, None, ptr, args[1], args[2], args[3], args[4], 1.0, None) == -2
     # the selection on static scratch checks its arguments and its size limit on the host, before any device call
     assert L.gr4ad_op_select_static(None, None, 1, 1, 8, 1, None, None, None, None) == -1

@@ -54,6 +54,7 @@ def test_config1_tiny_fp32_full_batch_matches_oracle_exactly_where_margins_allow
     dict(T=3, V=[24, 20, 30], d=512, H=8, F=64, L=3, K=2, S=75, B=3, beam=[5, 8, 6], len_min=1),           # 24 queries, ragged tiles of 32 rows
     dict(T=5, V=[12, 16, 12, 10, 14], d=512, H=8, F=64, L=2, K=1, S=100, B=2, beam=[4, 6, 5, 6, 4], len_min=33),  # 40 queries: two query tiles
     dict(T=4, V=[24, 20, 16, 30], d=1024, H=16, F=64, L=2, K=1, S=45, B=2, beam=[5, 8, 6, 7], len_min=3),   # 64 queries, the benchmark's shape
+    dict(T=5, V=[12, 16, 12, 10, 14], d=1024, H=16, F=64, L=2, K=1, S=70, B=2, beam=[4, 6, 5, 6, 4], len_min=20),  # 80 queries: two launches per layer
 ])
 def test_small_shapes_match_oracle(dtype, shape):
     w, W, X = tiny(dtype=dtype, gain_jitter=0.3 if dtype == "f32" else 0.1, **shape)

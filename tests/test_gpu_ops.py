@@ -207,7 +207,8 @@ def test_cross_attention_matches_oracle(dtype, B, n, S, d, H):
 
 
 @pytest.mark.parametrize("B,RQ,S,d,gain", [(3, 64, 200, 1024, 1.0), (2, 48, 33, 1024, 4.0), (2, 17, 1, 1024, 1.0), (3, 32, 95, 1024, 2.0),
-                                          (2, 24, 130, 512, 1.0), (3, 64, 64, 512, 6.0), (2, 5, 31, 512, 1.0), (4, 40, 257, 512, 3.0)])
+                                          (2, 24, 130, 512, 1.0), (3, 64, 64, 512, 6.0), (2, 5, 31, 512, 1.0), (4, 40, 257, 512, 3.0),
+                                          (2, 80, 150, 1024, 2.0), (3, 128, 70, 512, 1.0), (2, 65, 40, 512, 3.0)])  # more than 64 query rows: two launches
 def test_context_attention_matches_oracle(B, RQ, S, d, gain):
     """Attention over the raw context rows as keys and values (the lazy layers' absorbed form) = single-head attention with
     K = V = x in the oracle; `gain` sharpens the softmax so that the running maximum moves between tiles."""
@@ -229,7 +230,7 @@ def test_context_attention_matches_oracle(B, RQ, S, d, gain):
 
 
 def test_context_attention_refuses_what_it_does_not_cover():
-    q = torch.zeros((1, 65, 512), dtype=torch.bfloat16, device="cuda")
+    q = torch.zeros((1, 129, 512), dtype=torch.bfloat16, device="cuda")
     x = torch.zeros((1, 8, 512), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(RuntimeError):
         binding.op_context_attention(q, x, None, 1.0)
