@@ -206,6 +206,14 @@ def test_cross_attention_matches_oracle(dtype, B, n, S, d, H):
         np.testing.assert_allclose(out[b], ref, atol=2e-5 if dtype == "f32" else 1.5e-2)
 
 
+def context_attention_bound(xv):
+    """What bf16 storage allows: the kernel rounds every probability that enters the product (8 significand bits: relative
+    error up to 2^-8; the normaliser sums the unrounded ones) and the weighted sum itself (2^-8), so an output is off by at
+    most 2^-8 (sum_s p_s |x_s| + |z|) <= 2^-7 of the largest value it averages; 1e-3 on top for the fp32 accumulation and the
+    hardware's exp2.  (A wrong operand, index or mask shows as an error of the size of the values themselves.)"""
+    return 2.0 ** -7 * float(np.abs(xv).max()) + 1e-3
+
+
 @pytest.mark.parametrize("B,RQ,S,d,gain", [(3, 64, 200, 1024, 1.0), (2, 48, 33, 1024, 4.0), (2, 17, 1, 1024, 1.0), (3, 32, 95, 1024, 2.0),
                                           (2, 24, 130, 512, 1.0), (3, 64, 64, 512, 6.0), (2, 5, 31, 512, 1.0), (4, 40, 257, 512, 3.0),
                                           (2, 80, 150, 1024, 2.0), (3, 128, 70, 512, 1.0), (2, 65, 40, 512, 3.0)])  # more than 64 query rows: two launches
@@ -225,8 +233,26 @@ def test_context_attention_matches_oracle(B, RQ, S, d, gain):
     out = out.float().cpu().numpy()
     for b in range(B):
         ref = oracle.prim_mha(q[b], x[b, :lens[b]], x[b, :lens[b]], 1, False)
-        np.testing.assert_allclose(out[b], ref, atol=1.5e-2)
+        np.testing.assert_allclose(out[b], ref, atol=context_attention_bound(x[b, :lens[b]]))
     assert np.array_equal(full.float().cpu().numpy()[0], out[0])  # no length array = all rows
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_context_attention_random_shapes(seed):
+    rng = np.random.default_rng(900 + seed)
+    d = int(rng.choice([512, 1024]))
+    B, RQ, S = int(rng.integers(1, 6)), int(rng.integers(1, 129)), int(rng.integers(1, 300))
+    gain = float(rng.choice([1.0, 3.0, 8.0]))
+    q = synth.round_bf16((gain * rng.standard_normal((B, RQ, d))).astype(np.float32))
+    x = synth.round_bf16(rng.standard_normal((B, S, d)).astype(np.float32))
+    lens = rng.integers(1, S + 1, size=B).astype(np.int32)
+    print("seed", seed, "B RQ S d gain", B, RQ, S, d, gain, "lens", lens.tolist(), flush=True)
+    out = binding.op_context_attention(dev(q, "bf16"), dev(x, "bf16"), torch.from_numpy(lens).cuda(), 1.0 / np.sqrt(d))
+    torch.cuda.synchronize()
+    out = out.float().cpu().numpy()
+    for b in range(B):
+        ref = oracle.prim_mha(q[b], x[b, :lens[b]], x[b, :lens[b]], 1, False)
+        np.testing.assert_allclose(out[b], ref, atol=context_attention_bound(x[b, :lens[b]]))
 
 
 def test_context_attention_refuses_what_it_does_not_cover():
