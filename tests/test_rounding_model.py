@@ -13,6 +13,7 @@ SHAPES = [
     dict(T=3, V=[17, 30, 9], d=128, H=8, F=64, L=4, K=2, S=70, B=2, beam=[5, 12, 7], len_min=1),      # dh 16: plain form
     dict(T=3, V=[40, 33, 50], d=128, H=2, F=96, L=3, K=2, S=150, B=2, beam=[7, 13, 9], len_min=70),   # dh 64: absorbed lazy layers, 3 key tiles
     dict(T=2, V=[52, 13], d=256, H=2, F=64, L=2, K=0, S=9, B=2, beam=[30, 7]),                        # no lazy layer
+    dict(T=3, V=[24, 20, 30], d=512, H=8, F=64, L=2, K=1, S=75, B=2, beam=[5, 8, 6], len_min=1),       # dh 64, width 512: absorbed lazy layers in one pass (tiles of 32 rows)
 ]
 
 
